@@ -1,0 +1,631 @@
+"""Seeded synthetic checkpoints: tensor lists, shard layouts and values.
+
+This module only *describes* workloads.  A stored shard is written down the way the
+paper's checkpoint representation does (Sec. 3.2, "Decoupled Checkpoint Representation"):
+a tensor is named by an integer FQN id and a global shape, and a shard is the box
+(nD offsets, nD lengths) it holds.  A ZeRO-style irregular shard (Sec. 3.2, "Decomposing
+irregular tensors"; Appendix A on hybrid 3-D parallelism) is written as a slice
+[flat_begin, flat_end) of the concatenation of several row-major-flattened boxes.
+
+Nothing here intersects boxes, decomposes flat ranges or moves bytes by index arithmetic:
+blob contents are produced with library slicing / concatenation of the seeded global
+tensors, so the same routine, applied to the *target* layout, yields the expected result
+of a reshard independently of both the HIP path and the CPU oracle.
+"""
+from __future__ import annotations
+
+import math
+from collections import defaultdict
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+BASE_SEED = 20143
+BLOB_ALIGN = 256  # tensors are packed back-to-back at 256-byte aligned offsets
+
+
+# ----------------------------------------------------------------------------------------
+# descriptions
+# ----------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class TensorSpec:
+    fqn: int
+    name: str
+    shape: Tuple[int, ...]
+    dtype: torch.dtype
+    dist: Tuple  # ("uniform", lo, hi) | ("normal", mean, std) | ("normal_sq", std) | ("bits",)
+
+
+@dataclass(frozen=True)
+class Part:
+    """One box of one tensor: offsets/lengths along the axes of the global shape."""
+    fqn: int
+    global_shape: Tuple[int, ...]
+    offsets: Tuple[int, ...]
+    lengths: Tuple[int, ...]
+
+    @property
+    def volume(self) -> int:
+        return math.prod(self.lengths)
+
+
+@dataclass
+class Shard:
+    """Stored shard = elements [flat_begin, flat_end) of concat(flatten(part) for part in parts).
+
+    Packed at `byte_offset` of buffer `buf` unless `strides` (element strides, one per
+    dimension of the single part) is given.
+    """
+    parts: Tuple[Part, ...]
+    flat_begin: int
+    flat_end: int
+    itemsize: int
+    buf: int
+    byte_offset: int
+    strides: Optional[Tuple[int, ...]] = None
+    group: int = -1  # >= 0: shards with the same group share one `parts` tuple (a flat buffer)
+
+    @property
+    def numel(self) -> int:
+        return self.flat_end - self.flat_begin
+
+
+@dataclass
+class Layout:
+    shards: List[Shard] = field(default_factory=list)
+    buf_bytes: List[int] = field(default_factory=list)
+
+    def payload_bytes(self) -> int:
+        return sum(s.numel * s.itemsize for s in self.shards)
+
+
+@dataclass
+class Case:
+    name: str
+    seed: int
+    tensors: Dict[int, TensorSpec]
+    saved: Layout
+    target: Layout
+
+
+def regular(part: Part, itemsize: int, buf: int, byte_offset: int, strides=None) -> Shard:
+    return Shard((part,), 0, part.volume, itemsize, buf, byte_offset, strides)
+
+
+def _align_up(x: int, a: int) -> int:
+    return (x + a - 1) // a * a
+
+
+class _Packer:
+    """Running byte cursor per buffer."""
+
+    def __init__(self, n_bufs: int, align: int = BLOB_ALIGN):
+        self.cur = [0] * n_bufs
+        self.align = align
+
+    def take(self, buf: int, nbytes: int) -> int:
+        off = _align_up(self.cur[buf], self.align)
+        self.cur[buf] = off + nbytes
+        return off
+
+    def sizes(self) -> List[int]:
+        return [max(c, 1) for c in self.cur]
+
+
+# ----------------------------------------------------------------------------------------
+# values
+# ----------------------------------------------------------------------------------------
+def global_tensor(spec: TensorSpec, seed: int, device="cpu") -> torch.Tensor:
+    """Seeded contents of one whole (unsharded) tensor."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed((seed * 1000003 + spec.fqn * 7919 + 12345) & 0x7FFFFFFFFFFFFFFF)
+    shape = tuple(spec.shape)
+    kind = spec.dist[0]
+    if kind == "uniform":
+        lo, hi = spec.dist[1], spec.dist[2]
+        t = torch.rand(shape, generator=gen, device=device, dtype=torch.float32) * (hi - lo) + lo
+    elif kind == "normal":
+        t = torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * spec.dist[2] + spec.dist[1]
+    elif kind == "normal_sq":
+        t = (torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * spec.dist[1]) ** 2
+    elif kind == "bits":  # arbitrary bit patterns (NaN payloads, -0.0, denormals all occur)
+        n = max(1, math.prod(shape)) * spec.dtype.itemsize
+        raw = torch.randint(0, 256, (n,), generator=gen, device=device, dtype=torch.uint8)
+        return raw.view(spec.dtype).reshape(shape)
+    elif kind == "fill":  # every byte == dist[1] (coverage masks)
+        n = max(1, math.prod(shape)) * spec.dtype.itemsize
+        return torch.full((n,), spec.dist[1], device=device, dtype=torch.uint8).view(spec.dtype).reshape(shape)
+    elif kind == "iota":  # element value == its global row-major index
+        t = torch.arange(max(1, math.prod(shape)), device=device, dtype=torch.float64).reshape(shape)
+    else:
+        raise ValueError(kind)
+    return t.to(spec.dtype)
+
+
+def _box(G: torch.Tensor, p: Part) -> torch.Tensor:
+    return G[tuple(slice(o, o + l) for o, l in zip(p.offsets, p.lengths))]
+
+
+def _store(buf: torch.Tensor, sh: Shard, vals: torch.Tensor, dtype: torch.dtype) -> None:
+    if sh.strides is None:
+        n = vals.numel() * sh.itemsize
+        if n:
+            buf[sh.byte_offset:sh.byte_offset + n] = vals.contiguous().view(-1).view(torch.uint8)
+        return
+    lens = sh.parts[0].lengths
+    if math.prod(lens) == 0:
+        return
+    span = 1 + sum((l - 1) * s for l, s in zip(lens, sh.strides))
+    typed = buf[sh.byte_offset:sh.byte_offset + span * sh.itemsize].view(dtype)
+    torch.as_strided(typed, lens, sh.strides).copy_(vals.reshape(lens))
+
+
+def coverage_mask(layout: Layout, tensors: Dict[int, TensorSpec], device="cpu") -> List[torch.Tensor]:
+    """Per buffer: 1 where some shard of `layout` stores a byte, else 0 (library slicing only)."""
+    ones = {f: TensorSpec(f, s.name, s.shape, s.dtype, ("fill", 1)) for f, s in tensors.items()}
+    return materialize(layout, ones, 0, device, poison=0)
+
+
+def materialize(layout: Layout, tensors: Dict[int, TensorSpec], seed: int, device="cpu",
+                poison: Optional[int] = None) -> List[torch.Tensor]:
+    """Byte buffers of `layout` holding the seeded values (library slicing only).
+
+    Applied to a saved layout this gives the source blobs; applied to a target layout it
+    gives what a correct reshard must leave in the destination buffers (bytes no shard
+    covers keep `poison`, or are unspecified when poison is None).
+    """
+    bufs = []
+    for n in layout.buf_bytes:
+        if poison is None:
+            bufs.append(torch.zeros(n, dtype=torch.uint8, device=device))
+        else:
+            bufs.append(torch.full((n,), poison, dtype=torch.uint8, device=device))
+    by_fqn = defaultdict(list)
+    groups = defaultdict(list)
+    for sh in layout.shards:
+        if sh.group >= 0:
+            groups[sh.group].append(sh)
+        else:
+            assert len(sh.parts) == 1
+            by_fqn[sh.parts[0].fqn].append(sh)
+    for fqn, shs in by_fqn.items():
+        spec = tensors[fqn]
+        G = global_tensor(spec, seed, device)
+        for sh in shs:
+            box = _box(G, sh.parts[0])
+            if sh.strides is not None:
+                _store(bufs[sh.buf], sh, box, spec.dtype)
+            else:
+                _store(bufs[sh.buf], sh, box.reshape(-1)[sh.flat_begin:sh.flat_end], spec.dtype)
+    for _, shs in groups.items():
+        parts = shs[0].parts
+        flat = torch.cat([_box(global_tensor(tensors[p.fqn], seed, device), p).reshape(-1) for p in parts])
+        for sh in shs:
+            assert sh.parts is parts or sh.parts == parts
+            _store(bufs[sh.buf], sh, flat[sh.flat_begin:sh.flat_end], tensors[parts[0].fqn].dtype)
+        del flat
+    return bufs
+
+
+# ----------------------------------------------------------------------------------------
+# model tensor lists
+# ----------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class _ModelTensor:
+    name: str
+    shape: Tuple[int, ...]
+    tp_dim: Optional[int]  # None: replicated under tensor parallelism
+    layer: int             # -1: first pipeline stage, -2: last pipeline stage, else layer index
+
+
+def llama_tensors(layers: int, hidden: int, ffn: int, vocab: int) -> List[_ModelTensor]:
+    """Decoder in model-definition order: embedding, per layer [ln1,q,k,v,o,ln2,gate,up,down],
+    final norm, lm_head (untied).  Column-parallel GEMMs split dim 0 of [out,in], row-parallel
+    ones dim 1, norms are replicated (Appendix A)."""
+    ts = [_ModelTensor("embed.weight", (vocab, hidden), 0, -1)]
+    for i in range(layers):
+        p = f"layers.{i}."
+        ts += [
+            _ModelTensor(p + "ln1.weight", (hidden,), None, i),
+            _ModelTensor(p + "attn.q.weight", (hidden, hidden), 0, i),
+            _ModelTensor(p + "attn.k.weight", (hidden, hidden), 0, i),
+            _ModelTensor(p + "attn.v.weight", (hidden, hidden), 0, i),
+            _ModelTensor(p + "attn.o.weight", (hidden, hidden), 1, i),
+            _ModelTensor(p + "ln2.weight", (hidden,), None, i),
+            _ModelTensor(p + "mlp.gate.weight", (ffn, hidden), 0, i),
+            _ModelTensor(p + "mlp.up.weight", (ffn, hidden), 0, i),
+            _ModelTensor(p + "mlp.down.weight", (hidden, ffn), 1, i),
+        ]
+    ts += [_ModelTensor("final_norm.weight", (hidden,), None, -2),
+           _ModelTensor("lm_head.weight", (vocab, hidden), 0, -2)]
+    return ts
+
+
+# state sets: (suffix, dtype, distribution)
+STATE_BF16_WEIGHT = ("", torch.bfloat16, ("normal", 0.0, 0.02))
+STATE_FP32_MASTER = (".master", torch.float32, ("normal", 0.0, 0.02))
+STATE_FP32_EXP_AVG = (".exp_avg", torch.float32, ("normal", 0.0, 1e-3))
+STATE_FP32_EXP_AVG_SQ = (".exp_avg_sq", torch.float32, ("normal_sq", 1e-3))
+
+
+def _specs(model: Sequence[_ModelTensor], states) -> Dict[int, TensorSpec]:
+    out = {}
+    for si, (suffix, dtype, dist) in enumerate(states):
+        for ti, mt in enumerate(model):
+            fqn = si * len(model) + ti
+            out[fqn] = TensorSpec(fqn, mt.name + suffix, mt.shape, dtype, dist)
+    return out
+
+
+def _stage_of(mt: _ModelTensor, layers: int, pp: int) -> int:
+    if mt.layer == -1:
+        return 0
+    if mt.layer == -2:
+        return pp - 1
+    return mt.layer * pp // layers
+
+
+def _tp_box(shape, tp_dim, tp, r):
+    off = [0] * len(shape)
+    ln = list(shape)
+    if tp_dim is not None:
+        assert shape[tp_dim] % tp == 0, (shape, tp_dim, tp)
+        ln[tp_dim] = shape[tp_dim] // tp
+        off[tp_dim] = r * ln[tp_dim]
+    return tuple(off), tuple(ln)
+
+
+def megatron_layout(model: Sequence[_ModelTensor], states, layers: int, tp: int, pp: int,
+                    replicate_norms: bool, only_ranks=None) -> Layout:
+    """One buffer per (pp_rank, tp_rank).  Replicated tensors are stored once (lowest TP rank)
+    when `replicate_norms` is False -- the saved side, where every element has exactly one
+    saver -- and on every TP rank otherwise (the target side).  `only_ranks`: keep just these
+    (pp_rank, tp_rank) pairs (one target rank's share); buffers are renumbered densely."""
+    ranks = [(p, t) for p in range(pp) for t in range(tp)]
+    if only_ranks is not None:
+        ranks = [r for r in ranks if r in set(only_ranks)]
+    buf_of = {r: i for i, r in enumerate(ranks)}
+    pk = _Packer(len(ranks))
+    lay = Layout()
+    for si, (_, dtype, _) in enumerate(states):
+        e = dtype.itemsize
+        for ti, mt in enumerate(model):
+            fqn = si * len(model) + ti
+            stage = _stage_of(mt, layers, pp)
+            for r in range(tp):
+                if (stage, r) not in buf_of:
+                    continue
+                if mt.tp_dim is None and not replicate_norms and r != 0:
+                    continue
+                off, ln = _tp_box(mt.shape, mt.tp_dim, tp, r)
+                part = Part(fqn, tuple(mt.shape), off, ln)
+                b = buf_of[(stage, r)]
+                lay.shards.append(regular(part, e, b, pk.take(b, part.volume * e)))
+    lay.buf_bytes = pk.sizes()
+    return lay
+
+
+def zero_layout(model: Sequence[_ModelTensor], states, tp: int, dp: int, replicate_norms: bool,
+                only=None) -> Layout:
+    """ZeRO-style flat sharding: per state and TP rank the TP-local shards are flattened and
+    concatenated in parameter order, then cut evenly into `dp` slices of ceil(N/dp) elements
+    (the last ones short or empty).  One buffer per (state, tp_rank, dp_rank).  `only`:
+    optional predicate (state, tp_rank, dp_rank) -> keep."""
+    lay = Layout()
+    gid = 0
+    for si, (_, dtype, _) in enumerate(states):
+        e = dtype.itemsize
+        for r in range(tp):
+            parts = []
+            for ti, mt in enumerate(model):
+                if mt.tp_dim is None and not replicate_norms and r != 0:
+                    continue
+                off, ln = _tp_box(mt.shape, mt.tp_dim, tp, r)
+                parts.append(Part(si * len(model) + ti, tuple(mt.shape), off, ln))
+            parts = tuple(parts)
+            n = sum(p.volume for p in parts)
+            chunk = -(-n // dp)
+            for d in range(dp):
+                if only is not None and not only(si, r, d):
+                    continue
+                a, b = min(n, d * chunk), min(n, (d + 1) * chunk)
+                lay.shards.append(Shard(parts, a, b, e, len(lay.buf_bytes), 0, None, gid))
+                lay.buf_bytes.append(max(1, (b - a) * e))
+            gid += 1
+    return lay
+
+
+def moe_tensors(layers: int, hidden: int, experts: int, ffn: int):
+    """Stacked expert weights: gate, up [E, ffn, h]; down [E, h, ffn].  EP splits dim 0, TP splits
+    dim 1 of gate/up and dim 2 of down."""
+    ts = []
+    for i in range(layers):
+        p = f"layers.{i}.experts."
+        ts += [(p + "gate", (experts, ffn, hidden), 1),
+               (p + "up", (experts, ffn, hidden), 1),
+               (p + "down", (experts, hidden, ffn), 2)]
+    return ts
+
+
+def moe_layout(ts, ep: int, tp: int, itemsize: int, fqn_base: int = 0) -> Layout:
+    pk = _Packer(ep * tp)
+    lay = Layout()
+    for ti, (_, shape, tp_dim) in enumerate(ts):
+        for er in range(ep):
+            for tr in range(tp):
+                off = [0, 0, 0]
+                ln = list(shape)
+                ln[0] = shape[0] // ep
+                off[0] = er * ln[0]
+                ln[tp_dim] = shape[tp_dim] // tp
+                off[tp_dim] = tr * ln[tp_dim]
+                part = Part(fqn_base + ti, tuple(shape), tuple(off), tuple(ln))
+                b = er * tp + tr
+                lay.shards.append(regular(part, itemsize, b, pk.take(b, part.volume * itemsize)))
+    lay.buf_bytes = pk.sizes()
+    return lay
+
+
+def _random_shape(rng: np.random.Generator, lo: int, hi: int) -> Tuple[int, ...]:
+    n = int(rng.integers(lo, hi + 1))
+    rank = int(rng.integers(1, 4))
+    if rank == 1:
+        return (n,)
+    d0 = int(rng.integers(1, max(2, int(round(n ** 0.5)) + 1)))
+    if rank == 2:
+        return (d0, max(1, n // d0))
+    rest = max(1, n // d0)
+    d1 = int(rng.integers(1, max(2, int(round(rest ** 0.5)) + 1)))
+    return (d0, d1, max(1, rest // d1))
+
+
+def _random_1d_sharding(rng: np.random.Generator, shape, max_shards: int):
+    """Cut one random dimension at sorted random points (empty shards can occur)."""
+    dim = int(rng.integers(0, len(shape)))
+    s = int(rng.integers(1, max_shards + 1))
+    cuts = sorted(int(c) for c in rng.integers(0, shape[dim] + 1, size=s - 1))
+    edges = [0] + cuts + [shape[dim]]
+    boxes = []
+    for a, b in zip(edges[:-1], edges[1:]):
+        off = [0] * len(shape)
+        ln = list(shape)
+        off[dim], ln[dim] = a, b - a
+        boxes.append((tuple(off), tuple(ln)))
+    return boxes
+
+
+def small_tensor_case(n_tensors: int, seed: int, n_bufs: int = 64, max_shards: int = 16,
+                      lo: int = 4, hi: int = 4096, fqn_base: int = 0,
+                      dtype: torch.dtype = torch.float32, granule: int = 4,
+                      buf_base: Tuple[int, int] = (0, 0)):
+    """Many small random-shape tensors under independent random 1-D shardings on the saved
+    and the target side, packed at `granule`-byte granularity into `n_bufs` buffers each."""
+    rng = np.random.default_rng(seed)
+    e = dtype.itemsize
+    specs: Dict[int, TensorSpec] = {}
+    saved, target = Layout(), Layout()
+    pks = _Packer(n_bufs, granule), _Packer(n_bufs, granule)
+    for i in range(n_tensors):
+        fqn = fqn_base + i
+        shape = _random_shape(rng, lo, hi)
+        specs[fqn] = TensorSpec(fqn, f"small.{i}", shape, dtype, ("normal", 0.0, 1.0))
+        for lay, pk, base in ((saved, pks[0], buf_base[0]), (target, pks[1], buf_base[1])):
+            for off, ln in _random_1d_sharding(rng, shape, max_shards):
+                part = Part(fqn, shape, off, ln)
+                b = int(rng.integers(0, n_bufs))
+                lay.shards.append(regular(part, e, base + b, pk.take(b, part.volume * e)))
+    saved.buf_bytes = pks[0].sizes()
+    target.buf_bytes = pks[1].sizes()
+    return specs, saved, target
+
+
+# ----------------------------------------------------------------------------------------
+# the five benchmark configurations (full size by default; every builder takes smaller
+# dimensions so tests can run the same structure at sizes a CPU finishes in seconds)
+# ----------------------------------------------------------------------------------------
+def cfg1(n: int = 1024, m: int = 1024, strided_target: bool = False) -> Case:
+    """One fp32 [n,m] tensor, uniform[-1,1); saved as 2 row shards, loaded as 4 column shards.
+    strided_target: each target buffer holds its [n, m/4] shard column-major (a transposed view)."""
+    spec = TensorSpec(0, "w", (n, m), torch.float32, ("uniform", -1.0, 1.0))
+    saved, target = Layout(), Layout()
+    for r in range(2):
+        part = Part(0, (n, m), (r * (n // 2), 0), (n // 2, m))
+        saved.shards.append(regular(part, 4, r, 0))
+        saved.buf_bytes.append(part.volume * 4)
+    for c in range(4):
+        part = Part(0, (n, m), (0, c * (m // 4)), (n, m // 4))
+        strides = (1, n) if strided_target else None
+        target.shards.append(regular(part, 4, c, 0, strides))
+        target.buf_bytes.append(part.volume * 4)
+    return Case("cfg1" + ("_strided" if strided_target else ""), BASE_SEED + 1, {0: spec}, saved, target)
+
+
+def llama_case(name: str, seed: int, layers: int, hidden: int, ffn: int, vocab: int, states,
+               tp_s: int, pp_s: int, tp_t: int, pp_t: int, only_target_ranks=None) -> Case:
+    model = llama_tensors(layers, hidden, ffn, vocab)
+    return Case(name, seed, _specs(model, states),
+                megatron_layout(model, states, layers, tp_s, pp_s, replicate_norms=False),
+                megatron_layout(model, states, layers, tp_t, pp_t, replicate_norms=True,
+                                only_ranks=only_target_ranks))
+
+
+def cfg2(layers: int = 24, hidden: int = 2048, ffn: int = 5504, vocab: int = 32000) -> Case:
+    """bf16 decoder saved TP4 PP2, loaded TP2 PP4, all target shards."""
+    return llama_case("cfg2", BASE_SEED + 2, layers, hidden, ffn, vocab, [STATE_BF16_WEIGHT], 4, 2, 2, 4)
+
+
+CFG3_STATES = [STATE_BF16_WEIGHT, STATE_FP32_MASTER, STATE_FP32_EXP_AVG, STATE_FP32_EXP_AVG_SQ]
+
+
+def cfg3(layers: int = 32, hidden: int = 4096, ffn: int = 11008, vocab: int = 32000,
+         rank_share: bool = False) -> Case:
+    """7B-shaped decoder, bf16 weights + three fp32 Adam states, TP4 PP2 -> TP2 PP4.
+    rank_share: only target rank (pp 0, tp 0)."""
+    return llama_case("cfg3" + ("_rank0" if rank_share else ""), BASE_SEED + 3, layers, hidden, ffn, vocab,
+                      CFG3_STATES, 4, 2, 2, 4, only_target_ranks=[(0, 0)] if rank_share else None)
+
+
+CFG4_STATES = [STATE_FP32_MASTER, STATE_FP32_EXP_AVG, STATE_FP32_EXP_AVG_SQ]
+
+
+def cfg4(layers: int = 32, hidden: int = 4096, ffn: int = 11008, vocab: int = 32000,
+         dp_s: int = 16, dp_t: int = 12, tp_t: int = 2, n_states: int = 3) -> Case:
+    """fp32 optimizer states flattened in parameter order: saved TP1 DP16, loaded TP2 DP12."""
+    model = llama_tensors(layers, hidden, ffn, vocab)
+    states = CFG4_STATES[:n_states]
+    return Case("cfg4", BASE_SEED + 4, _specs(model, states),
+                zero_layout(model, states, 1, dp_s, replicate_norms=False),
+                zero_layout(model, states, tp_t, dp_t, replicate_norms=True))
+
+
+def cfg5(layers: int = 16, hidden: int = 4096, experts: int = 64, ffn: int = 1408,
+         n_small: int = 100_000, include_experts: bool = True) -> Case:
+    """bf16 stacked expert weights EP8 TP2 -> EP4 TP4 (16 buffers each side) plus `n_small`
+    small fp32 tensors under random 1-D shardings in 64 further buffers each side."""
+    seed = BASE_SEED + 5
+    specs: Dict[int, TensorSpec] = {}
+    saved, target = Layout(), Layout()
+    nb = 0
+    if include_experts:
+        ts = moe_tensors(layers, hidden, experts, ffn)
+        for i, (nm, shape, _) in enumerate(ts):
+            specs[i] = TensorSpec(i, nm, shape, torch.bfloat16, ("normal", 0.0, 0.02))
+        saved = moe_layout(ts, 8, 2, 2)
+        target = moe_layout(ts, 4, 4, 2)
+        nb = 16
+    if n_small:
+        sp, s2, t2 = small_tensor_case(n_small, seed, fqn_base=len(specs), buf_base=(nb, nb))
+        specs.update(sp)
+        saved.shards += s2.shards
+        saved.buf_bytes += s2.buf_bytes
+        target.shards += t2.shards
+        target.buf_bytes += t2.buf_bytes
+    return Case("cfg5", seed, specs, saved, target)
+
+
+# ----------------------------------------------------------------------------------------
+# randomised small cases (parity tests)
+# ----------------------------------------------------------------------------------------
+def _random_cuts(rng, n: int, max_cuts: int) -> List[int]:
+    k = int(rng.integers(0, max_cuts + 1))
+    return [0] + sorted(int(c) for c in rng.integers(0, n + 1, size=k)) + [n]
+
+
+def _grid_boxes(rng, shape, max_cuts: int):
+    """Partition a shape into a grid of boxes by cutting every dimension at random points."""
+    edges = [_random_cuts(rng, n, max_cuts) for n in shape]
+    boxes = [((), ())]
+    for e in edges:
+        boxes = [(o + (a,), l + (b - a,)) for (o, l) in boxes for a, b in zip(e[:-1], e[1:])]
+    return boxes
+
+
+def _permuted_strides(rng, lengths, pad: bool):
+    """Element strides of a buffer that stores the box with its dimensions in a random order
+    (optionally with padding between rows)."""
+    order = list(rng.permutation(len(lengths)))  # order[0] slowest ... order[-1] fastest
+    strides = [0] * len(lengths)
+    s = 1
+    for d in reversed(order):
+        strides[d] = s
+        s *= max(1, lengths[d]) + (int(rng.integers(0, 3)) if pad else 0)
+    return tuple(strides), s
+
+
+def _random_grid_layout(rng, specs, n_bufs: int, granule: int, max_cuts: int, p_strided: float) -> Layout:
+    pk = _Packer(n_bufs, granule)
+    lay = Layout()
+    for fqn, spec in specs.items():
+        e = spec.dtype.itemsize
+        for off, ln in _grid_boxes(rng, spec.shape, max_cuts):
+            part = Part(fqn, tuple(spec.shape), off, ln)
+            b = int(rng.integers(0, n_bufs))
+            if len(ln) >= 1 and part.volume > 0 and rng.random() < p_strided:
+                strides, span = _permuted_strides(rng, ln, pad=bool(rng.integers(0, 2)))
+                pk.align = max(granule, e)  # typed strided views need itemsize-aligned storage
+                lay.shards.append(regular(part, e, b, pk.take(b, span * e), strides))
+                pk.align = granule
+            else:
+                lay.shards.append(regular(part, e, b, pk.take(b, part.volume * e)))
+    lay.buf_bytes = pk.sizes()
+    return lay
+
+
+def _random_flat_layout(rng, specs, tp: int, dp: int, granule: int, pack_bufs: int) -> Layout:
+    """ZeRO-like: every tensor is first cut along one random dimension into `tp` (possibly
+    uneven) pieces; per piece index the pieces are flattened and concatenated in FQN order and
+    the concatenation is cut into `dp` even slices.  Slices are packed into `pack_bufs` buffers."""
+    pk = _Packer(pack_bufs, granule)
+    lay = Layout()
+    cuts = {}
+    for fqn, spec in specs.items():
+        if len(spec.shape) == 0:
+            cuts[fqn] = None
+            continue
+        d = int(rng.integers(0, len(spec.shape)))
+        n = spec.shape[d]
+        edges = [0] + sorted(int(c) for c in rng.integers(0, n + 1, size=tp - 1)) + [n]
+        cuts[fqn] = (d, edges)
+    e = next(iter(specs.values())).dtype.itemsize
+    for r in range(tp):
+        parts = []
+        for fqn, spec in specs.items():
+            if cuts[fqn] is None:
+                if r == 0:
+                    parts.append(Part(fqn, (), (), ()))
+                continue
+            d, edges = cuts[fqn]
+            off = [0] * len(spec.shape)
+            ln = list(spec.shape)
+            off[d], ln[d] = edges[r], edges[r + 1] - edges[r]
+            parts.append(Part(fqn, tuple(spec.shape), tuple(off), tuple(ln)))
+        parts = tuple(parts)
+        n = sum(p.volume for p in parts)
+        chunk = max(1, -(-n // dp))
+        for k in range(dp):
+            a, b = min(n, k * chunk), min(n, (k + 1) * chunk)
+            buf = int(rng.integers(0, pack_bufs))
+            lay.shards.append(Shard(parts, a, b, e, buf, pk.take(buf, (b - a) * e), None, r))
+    lay.buf_bytes = pk.sizes()
+    return lay
+
+
+RANDOM_DTYPES = (torch.uint8, torch.bfloat16, torch.float32, torch.float64)
+
+
+def random_case(seed: int, n_tensors: int = 5, max_elems: int = 3000, saved_mode: str = "grid",
+                target_mode: str = "grid", max_rank: int = 4, granules=(1, 2, 4, 8, 16, 256),
+                p_strided: float = 0.0, dtype: Optional[torch.dtype] = None) -> Case:
+    """Small random tensors (rank 0..max_rank, arbitrary bit patterns) under random saved and
+    target layouts.  'grid': boxes from random cuts in every dimension; 'flat': ZeRO-like slices
+    of concatenated pieces (single dtype for the whole case)."""
+    rng = np.random.default_rng(seed)
+    flat = "flat" in (saved_mode, target_mode)
+    one_dtype = dtype if dtype is not None else (RANDOM_DTYPES[int(rng.integers(0, len(RANDOM_DTYPES)))] if flat else None)
+    specs: Dict[int, TensorSpec] = {}
+    for i in range(n_tensors):
+        rank = int(rng.integers(0, max_rank + 1))
+        total = int(rng.integers(1, max_elems + 1))
+        shape = []
+        rest = total
+        for k in range(rank):
+            if k == rank - 1:
+                shape.append(max(1, rest))
+            else:
+                d = int(rng.integers(1, max(2, int(round(rest ** (1.0 / (rank - k)))) * 2)))
+                shape.append(d)
+                rest = max(1, rest // d)
+        rng.shuffle(shape)
+        dt = one_dtype or RANDOM_DTYPES[int(rng.integers(0, len(RANDOM_DTYPES)))]
+        specs[i] = TensorSpec(i, f"t{i}", tuple(int(s) for s in shape), dt, ("bits",))
+
+    def side(mode):
+        g = int(granules[int(rng.integers(0, len(granules)))])
+        if mode == "grid":
+            return _random_grid_layout(rng, specs, int(rng.integers(1, 5)), g, 3, p_strided)
+        return _random_flat_layout(rng, specs, int(rng.integers(1, 4)), int(rng.integers(1, 7)), g,
+                                   int(rng.integers(1, 4)))
+
+    return Case(f"random{seed}", seed, specs, side(saved_mode), side(target_mode))
