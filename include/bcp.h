@@ -1,0 +1,170 @@
+/*
+ * bcp -- load-time checkpoint resharding on one MI355X (gfx950): C-ABI boundary.
+ *
+ * The library takes saved tensor shards in the paper's parallelism-agnostic representation
+ * (Sec. 3.2 "Decoupled Checkpoint Representation": FQN + global shape, ShardMeta =
+ * (fqn, nD_offsets, nD_lengths), BasicMeta = itemsize/strides, ByteMeta = byte offset inside
+ * a storage blob) and builds the shards a different TP/PP/DP/EP layout asks for
+ * (Sec. 3.3 "Checkpoint Resharding Workflow", Step 2: matching segments between saved shards and
+ * the new sharding specification).  Storage I/O is outside: saved blobs are byte buffers that
+ * already sit in device memory.
+ *
+ * All functions are thread-compatible (no global state besides a thread-local error string),
+ * return a bcp_status and never throw.  "host" / "device" below says where a pointer must point.
+ */
+#ifndef BCP_H_
+#define BCP_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BCP_MAX_DIMS 8
+
+/* One stored shard (saved or target): ShardMeta + BasicMeta + ByteMeta of Sec. 3.2.
+ *
+ * The shard holds elements [flat_begin, flat_end) of the row-major flattening of the box
+ * (offsets, lengths) of tensor `fqn_id`.  flat range == [0, volume) is a regular shard; any other
+ * range is an irregular (ZeRO flat) shard, Sec. 3.2 "Decomposing irregular tensors".
+ * Storage: element j of that range sits at byte_offset + itemsize*j of buffer `buf` (packed),
+ * unless `strides` is non-zero, in which case the shard must be regular and the element with
+ * box-local coordinates y sits at byte_offset + itemsize * sum_k y[k]*strides[k].
+ * ndim == 0 is a scalar (volume 1).  Zero-volume shards are legal and produce no work. */
+typedef struct bcp_shard_meta {
+  int64_t fqn_id;                     /* >= 0; identifies the tensor (string table stays with the caller) */
+  int32_t ndim;                       /* 0..BCP_MAX_DIMS */
+  int32_t itemsize;                   /* bytes per element: 1, 2, 4, 8 or 16; dtype is opaque, no casting */
+  int64_t global_shape[BCP_MAX_DIMS]; /* shape before sharding */
+  int64_t offsets[BCP_MAX_DIMS];      /* nD_offsets */
+  int64_t lengths[BCP_MAX_DIMS];      /* nD_lengths */
+  int64_t flat_begin;                 /* element range inside the box, row-major */
+  int64_t flat_end;
+  int64_t strides[BCP_MAX_DIMS];      /* element strides; all zero == packed */
+  int64_t byte_offset;                /* where the first stored element sits in the buffer */
+  int32_t buf;                        /* index into src_blobs[] (saved) / dst_buffers[] (target) */
+  int32_t reserved;                   /* must be 0 */
+} bcp_shard_meta;
+
+typedef struct bcp_plan_s* bcp_plan_t; /* opaque; owns device-side region and tile tables */
+
+typedef enum bcp_status {
+  BCP_OK = 0,
+  BCP_ERR_INVALID_ARG = -1,     /* null pointer, negative count, bad ndim/itemsize/flat range/strides */
+  BCP_ERR_SHAPE_MISMATCH = -2,  /* records of one FQN disagree on ndim or global shape */
+  BCP_ERR_DTYPE_MISMATCH = -3,  /* records of one FQN disagree on itemsize */
+  BCP_ERR_OUT_OF_BOUNDS = -4,   /* offsets+lengths beyond the global shape, or flat range beyond the box */
+  BCP_ERR_SAVED_OVERLAP = -5,   /* two saved shards hold the same element (Sec. 4.1: one saver per shard) */
+  BCP_ERR_UNCOVERED = -6,       /* a target element no saved shard holds */
+  BCP_ERR_TOO_MANY_DIMS = -7,
+  BCP_ERR_OOM = -8,
+  BCP_ERR_HIP = -9,             /* a HIP runtime call failed; bcp_last_error() has its text */
+  BCP_ERR_NO_DEVICE = -10       /* no usable GPU */
+} bcp_status;
+
+/* flags of bcp_plan */
+#define BCP_PLAN_DEFAULT 0u
+#define BCP_ALLOW_UNCOVERED 1u      /* target elements without a saved source keep their bytes */
+#define BCP_SKIP_OVERLAP_CHECK 2u   /* trust the caller that saved shards are pairwise disjoint */
+
+typedef struct bcp_stats {
+  int64_t n_saved_boxes;   /* regular boxes after decomposing the saved records */
+  int64_t n_target_boxes;
+  int64_t n_pairs;         /* candidate (saved box, target box) pairs with equal FQN */
+  int64_t n_regions;       /* non-empty intersections == copy regions */
+  int64_t n_tiles;         /* work items of the copy kernel */
+  int64_t payload_bytes;   /* bytes the copy moves one way */
+  int64_t n_transposed;    /* regions taken by the LDS-staged path (inner strides disagree) */
+  int64_t max_src_buf;     /* largest buffer index used, -1 if none */
+  int64_t max_dst_buf;
+  int64_t region_dims_hist[BCP_MAX_DIMS + 1]; /* regions by number of dims after coalescing */
+  double plan_device_ms;   /* device time of the planner kernels (HIP events) */
+  double plan_wall_ms;     /* wall time of bcp_plan */
+} bcp_stats;
+
+/* Region as the copy kernel sees it (for inspection and tests; many region lists are valid). */
+typedef struct bcp_region_info {
+  int64_t src_base, dst_base;         /* byte offsets inside src_blobs[src_buf] / dst_buffers[dst_buf] */
+  int64_t run_bytes;                  /* contiguous inner run on both sides */
+  int64_t len[BCP_MAX_DIMS];          /* outer extents (rows), slowest first */
+  int64_t src_pitch[BCP_MAX_DIMS];    /* bytes */
+  int64_t dst_pitch[BCP_MAX_DIMS];
+  int32_t ndim;                       /* number of outer dims */
+  int32_t src_buf, dst_buf;
+  int32_t kind;                       /* 0: rows of contiguous runs, 1: LDS-staged transpose */
+  int64_t target_index;               /* index of the target record the region belongs to */
+  int64_t saved_index;                /* index of the saved record */
+} bcp_region_info;
+
+/* Step a1 (host helper): cut a flat ZeRO buffer at tensor boundaries.
+ * `params_in_order[i]` are regular records (flat range == whole box) whose row-major flattenings,
+ * concatenated in this order, form the flat buffer (Appendix A: TP-local shards are flattened and
+ * merged before being sharded by the DP degree).  The slice [A, B) of that concatenation, stored
+ * packed at `byte_offset` of buffer `buf`, is returned as one record per tensor it touches: same
+ * box, flat range = the part of the tensor inside the slice, byte_offset advanced accordingly.
+ * out (host) has room for *inout_n records; on return *inout_n is the number needed/written
+ * (BCP_ERR_INVALID_ARG with *inout_n set if the room was too small).  No GPU involved. */
+bcp_status bcp_meta_from_flat_slice(const bcp_shard_meta* params_in_order, int64_t n_params,
+                                    int64_t A, int64_t B, int32_t buf, int64_t byte_offset,
+                                    bcp_shard_meta* out, int64_t* inout_n);
+
+/* Step a2 (host mirror of the device decomposer, for inspection and tests): the regular boxes of
+ * one record, in ascending flat order; out_boxes[i] is a regular, packed record (global offsets and
+ * lengths, byte_offset of its first element).  At most 2*ndim-1 (min 1) boxes; *inout_n as above.
+ * Sec. 3.2 "Decomposing irregular tensors": an irregular shard becomes a series of regular ones. */
+bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, int64_t* inout_n);
+
+/* Build a copy plan on the current HIP device (Sec. 3.3 Step 2 on the GPU).
+ * saved/target: host arrays, borrowed for the duration of the call.  stream: hipStream_t
+ * (0 == default stream) the planner kernels run on; the call returns after they finished, so
+ * the plan is usable on any stream.  On success *out_plan owns device memory until
+ * bcp_plan_destroy.  Saved FQNs no target asks for are ignored.  A plan is immutable and may be
+ * replayed on any buffers that have the layout it was planned for. */
+bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved,
+                    const bcp_shard_meta* target, int64_t n_target,
+                    uint32_t flags, void* stream, bcp_plan_t* out_plan);
+
+/* Move the bytes: for every region, dst_buffers[dst_buf][...] = src_blobs[src_buf][...].
+ * src_blobs / dst_buffers: HOST arrays of DEVICE pointers (n_src > max_src_buf, n_dst >
+ * max_dst_buf), owned by the caller; buffers must stay valid until the work queued on `stream`
+ * completed and must not overlap each other.  Asynchronous: enqueues on `stream` (hipStream_t)
+ * and returns; errors detectable on the host are returned synchronously.  Calls on one plan must
+ * be ordered by the caller (same stream, or synchronised) because they share the plan's pointer
+ * tables and queue counter. */
+bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src,
+                       void* const* dst_buffers, int32_t n_dst, void* stream);
+
+bcp_status bcp_plan_stats(bcp_plan_t plan, bcp_stats* out);
+
+/* Copy up to `capacity` regions to out (host); *n_regions receives the plan's region count. */
+bcp_status bcp_plan_regions(bcp_plan_t plan, bcp_region_info* out, int64_t capacity, int64_t* n_regions);
+
+/* Smallest buffer sizes the plan is safe on: src_extent[i] / dst_extent[i] (host arrays of n_src /
+ * n_dst entries, at least max_*_buf + 1) receive one past the highest byte any region touches in
+ * src_blobs[i] / dst_buffers[i] (0 if unused).  bcp_reshard itself never sees buffer sizes, so a
+ * caller that is not sure its buffers match the planned layout checks here first. */
+bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t n_src,
+                                   int64_t* dst_extent, int32_t n_dst);
+
+bcp_status bcp_plan_destroy(bcp_plan_t plan);
+
+/* Launch configuration of the copy kernel (process-wide; takes effect at the next bcp_plan /
+ * bcp_reshard).  tile_bytes: payload per work item, a power of two in [4 KiB, 4 MiB], used by
+ * plans built afterwards.  persistent != 0: a fixed grid of wg_per_cu * CU-count workgroups pops
+ * tiles from an atomic queue; 0: one workgroup per tile.  Values <= 0 keep the current setting. */
+bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu);
+
+/* Plain device-to-device streaming copy with the same vector width and launch shape as the reshard
+ * kernel: the practical ceiling the bench reports beside it.  dst/src: device, 16-byte aligned. */
+bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream);
+
+const char* bcp_last_error(void); /* thread-local text of the last failure on this thread */
+const char* bcp_status_name(bcp_status s);
+int32_t bcp_abi_version(void);
+int64_t bcp_sizeof_shard_meta(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCP_H_ */

@@ -1,0 +1,247 @@
+"""Thin ctypes binding of libbcp.so (include/bcp.h).  Argument marshalling only: every step of
+the reshard path runs inside the library's kernels.  PyTorch appears here only as the owner of
+device memory and streams; there is no CPU fallback -- a missing library is an ImportError-like
+failure at first use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+MAX_DIMS = 8
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbcp.so")
+
+SHARD_META = np.dtype([
+    ("fqn_id", "<i8"), ("ndim", "<i4"), ("itemsize", "<i4"),
+    ("global_shape", "<i8", (MAX_DIMS,)), ("offsets", "<i8", (MAX_DIMS,)), ("lengths", "<i8", (MAX_DIMS,)),
+    ("flat_begin", "<i8"), ("flat_end", "<i8"), ("strides", "<i8", (MAX_DIMS,)),
+    ("byte_offset", "<i8"), ("buf", "<i4"), ("reserved", "<i4"),
+], align=True)
+
+STATS = np.dtype([
+    ("n_saved_boxes", "<i8"), ("n_target_boxes", "<i8"), ("n_pairs", "<i8"), ("n_regions", "<i8"),
+    ("n_tiles", "<i8"), ("payload_bytes", "<i8"), ("n_transposed", "<i8"), ("max_src_buf", "<i8"),
+    ("max_dst_buf", "<i8"), ("region_dims_hist", "<i8", (MAX_DIMS + 1,)),
+    ("plan_device_ms", "<f8"), ("plan_wall_ms", "<f8"),
+], align=True)
+
+REGION_INFO = np.dtype([
+    ("src_base", "<i8"), ("dst_base", "<i8"), ("run_bytes", "<i8"),
+    ("len", "<i8", (MAX_DIMS,)), ("src_pitch", "<i8", (MAX_DIMS,)), ("dst_pitch", "<i8", (MAX_DIMS,)),
+    ("ndim", "<i4"), ("src_buf", "<i4"), ("dst_buf", "<i4"), ("kind", "<i4"),
+    ("target_index", "<i8"), ("saved_index", "<i8"),
+], align=True)
+
+BCP_OK = 0
+BCP_ALLOW_UNCOVERED = 1
+BCP_SKIP_OVERLAP_CHECK = 2
+
+EXPORTS = [
+    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_plan", "bcp_reshard", "bcp_plan_stats",
+    "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy", "bcp_configure", "bcp_copy_baseline", "bcp_last_error",
+    "bcp_status_name", "bcp_abi_version", "bcp_sizeof_shard_meta",
+]
+
+
+class BcpError(RuntimeError):
+    def __init__(self, status: int, name: str, msg: str):
+        super().__init__(f"{name}: {msg}")
+        self.status = status
+        self.name = name
+
+
+_lib = None
+
+
+def lib():
+    """Load libbcp.so (built beforehand by paper_2407_20143_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2407_20143_amd.build); "
+                               "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32
+        L.bcp_meta_from_flat_slice.argtypes = [vp, i64, i64, i64, i32, i64, vp, ctypes.POINTER(i64)]
+        L.bcp_decompose.argtypes = [vp, vp, ctypes.POINTER(i64)]
+        L.bcp_plan.argtypes = [vp, i64, vp, i64, u32, vp, ctypes.POINTER(vp)]
+        L.bcp_reshard.argtypes = [vp, vp, i32, vp, i32, vp]
+        L.bcp_plan_stats.argtypes = [vp, vp]
+        L.bcp_plan_regions.argtypes = [vp, vp, i64, ctypes.POINTER(i64)]
+        L.bcp_plan_buffer_extents.argtypes = [vp, vp, i32, vp, i32]
+        L.bcp_plan_destroy.argtypes = [vp]
+        L.bcp_configure.argtypes = [i64, i32, i32]
+        L.bcp_copy_baseline.argtypes = [vp, vp, i64, vp]
+        for f in EXPORTS:
+            getattr(L, f).restype = ctypes.c_int
+        L.bcp_last_error.restype = ctypes.c_char_p
+        L.bcp_status_name.restype = ctypes.c_char_p
+        L.bcp_status_name.argtypes = [ctypes.c_int]
+        L.bcp_sizeof_shard_meta.restype = i64
+        if L.bcp_sizeof_shard_meta() != SHARD_META.itemsize:
+            raise RuntimeError("bcp_shard_meta layout mismatch between binding and library")
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != BCP_OK:
+        L = lib()
+        raise BcpError(status, L.bcp_status_name(status).decode(), L.bcp_last_error().decode())
+
+
+# ---- metadata marshalling ---------------------------------------------------------------------
+def _fill_record(r, part, itemsize, flat_begin, flat_end, buf, byte_offset, strides=None):
+    n = len(part.global_shape)
+    r["fqn_id"], r["ndim"], r["itemsize"] = part.fqn, n, itemsize
+    r["global_shape"][:n] = part.global_shape
+    r["offsets"][:n] = part.offsets
+    r["lengths"][:n] = part.lengths
+    r["flat_begin"], r["flat_end"] = flat_begin, flat_end
+    r["buf"], r["byte_offset"] = buf, byte_offset
+    if strides is not None:
+        r["strides"][:n] = strides
+
+
+def meta_from_flat_slice(params: np.ndarray, a: int, b: int, buf: int, byte_offset: int) -> np.ndarray:
+    """bcp_meta_from_flat_slice: records for slice [a, b) of the concatenation of `params`."""
+    L = lib()
+    n = ctypes.c_int64(0)
+    st = L.bcp_meta_from_flat_slice(params.ctypes.data, len(params), a, b, buf, byte_offset, None, ctypes.byref(n))
+    if st != BCP_OK and n.value == 0:
+        _check(st)
+    out = np.zeros(max(n.value, 1), dtype=SHARD_META)
+    cap = ctypes.c_int64(len(out))
+    _check(L.bcp_meta_from_flat_slice(params.ctypes.data, len(params), a, b, buf, byte_offset, out.ctypes.data,
+                                      ctypes.byref(cap)))
+    return out[:cap.value]
+
+
+def decompose(rec: np.ndarray) -> np.ndarray:
+    """bcp_decompose of one record (a length-1 SHARD_META array or a scalar of it)."""
+    L = lib()
+    rec = np.ascontiguousarray(np.atleast_1d(rec))
+    out = np.zeros(2 * MAX_DIMS, dtype=SHARD_META)
+    n = ctypes.c_int64(len(out))
+    _check(L.bcp_decompose(rec.ctypes.data, out.ctypes.data, ctypes.byref(n)))
+    return out[:n.value]
+
+
+def layout_to_meta(layout) -> np.ndarray:
+    """synth.Layout -> array of bcp_shard_meta.  Multi-part (flat ZeRO) shards go through
+    bcp_meta_from_flat_slice; everything else is a field-by-field copy."""
+    chunks: List[np.ndarray] = []
+    simple = [sh for sh in layout.shards if len(sh.parts) == 1]
+    arr = np.zeros(len(simple), dtype=SHARD_META)
+    for r, sh in zip(arr, simple):
+        _fill_record(r, sh.parts[0], sh.itemsize, sh.flat_begin, sh.flat_end, sh.buf, sh.byte_offset, sh.strides)
+    chunks.append(arr)
+    cache = {}
+    for sh in layout.shards:
+        if len(sh.parts) == 1:
+            continue
+        key = id(sh.parts)
+        if key not in cache:
+            params = np.zeros(len(sh.parts), dtype=SHARD_META)
+            for r, p in zip(params, sh.parts):
+                _fill_record(r, p, sh.itemsize, 0, p.volume, 0, 0)
+            cache[key] = params
+        chunks.append(meta_from_flat_slice(cache[key], sh.flat_begin, sh.flat_end, sh.buf, sh.byte_offset))
+    return np.concatenate(chunks) if chunks else np.zeros(0, dtype=SHARD_META)
+
+
+# ---- plan / reshard ----------------------------------------------------------------------------
+class Plan:
+    def __init__(self, handle):
+        self._h = handle
+        self._extents = None
+
+    def buffer_extents(self):
+        """(src, dst): per buffer, one past the highest byte the plan touches (cached)."""
+        if self._extents is None:
+            st = self.stats()
+            ns, nd = st["max_src_buf"] + 1, st["max_dst_buf"] + 1
+            s = np.zeros(max(ns, 1), dtype=np.int64)
+            d = np.zeros(max(nd, 1), dtype=np.int64)
+            _check(lib().bcp_plan_buffer_extents(self._h, s.ctypes.data, ns, d.ctypes.data, nd))
+            self._extents = (s[:ns], d[:nd])
+        return self._extents
+
+    def stats(self) -> dict:
+        out = np.zeros(1, dtype=STATS)
+        _check(lib().bcp_plan_stats(self._h, out.ctypes.data))
+        return {k: (out[0][k].tolist()) for k in STATS.names}
+
+    def regions(self) -> np.ndarray:
+        n = ctypes.c_int64(0)
+        _check(lib().bcp_plan_regions(self._h, None, 0, ctypes.byref(n)))
+        out = np.zeros(max(n.value, 1), dtype=REGION_INFO)
+        _check(lib().bcp_plan_regions(self._h, out.ctypes.data, len(out), ctypes.byref(n)))
+        return out[:n.value]
+
+    def destroy(self):
+        if self._h:
+            lib().bcp_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def plan(saved_meta: np.ndarray, target_meta: np.ndarray, flags: int = 0, stream=None) -> Plan:
+    """bcp_plan(saved_meta, target_meta) -> plan"""
+    saved_meta = np.ascontiguousarray(saved_meta, dtype=SHARD_META)
+    target_meta = np.ascontiguousarray(target_meta, dtype=SHARD_META)
+    h = ctypes.c_void_p()
+    _check(lib().bcp_plan(saved_meta.ctypes.data if len(saved_meta) else None, len(saved_meta),
+                          target_meta.ctypes.data if len(target_meta) else None, len(target_meta),
+                          flags, _stream_ptr(stream), ctypes.byref(h)))
+    return Plan(h)
+
+
+def _ptrs(bufs: Sequence) -> "ctypes.Array":
+    arr = (ctypes.c_void_p * max(len(bufs), 1))()
+    for i, b in enumerate(bufs):
+        arr[i] = b if isinstance(b, int) else b.data_ptr()
+    return arr
+
+
+def reshard(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, stream=None, check_sizes: bool = True) -> None:
+    """bcp_reshard(plan, src_blobs, dst_buffers, stream): asynchronous on `stream` (default: torch's current).
+    check_sizes: when the buffers are tensors, refuse buffers smaller than the plan's extents (the
+    extents are computed once per plan) -- an undersized buffer would otherwise be a GPU memory fault."""
+    if check_sizes:
+        se, de = p.buffer_extents()
+        for what, ext, bufs in (("src_blobs", se, src_blobs), ("dst_buffers", de, dst_buffers)):
+            for i, need in enumerate(ext):
+                if i < len(bufs) and not isinstance(bufs[i], int):
+                    have = bufs[i].numel() * bufs[i].element_size()
+                    if have < need:
+                        raise ValueError(f"{what}[{i}] holds {have} bytes, the plan touches {int(need)}")
+    _check(lib().bcp_reshard(p._h, _ptrs(src_blobs), len(src_blobs), _ptrs(dst_buffers), len(dst_buffers),
+                             _stream_ptr(stream)))
+
+
+def configure(tile_bytes: int = 0, persistent: int = -1, wg_per_cu: int = 0) -> None:
+    _check(lib().bcp_configure(tile_bytes, persistent, wg_per_cu))
+
+
+def copy_baseline(dst, src, nbytes: Optional[int] = None, stream=None) -> None:
+    n = nbytes if nbytes is not None else src.numel() * src.element_size()
+    _check(lib().bcp_copy_baseline(dst.data_ptr(), src.data_ptr(), n, _stream_ptr(stream)))

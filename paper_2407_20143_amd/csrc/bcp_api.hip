@@ -1,0 +1,414 @@
+// C-ABI layer: argument checks, plan object, pointer-table staging, host helpers (a1, a2 mirror).
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "bcp_internal.h"
+
+namespace bcp {
+
+namespace {
+thread_local std::string g_error;
+PlanConfig g_config;
+std::mutex g_config_mu;
+}  // namespace
+
+void set_error(const std::string& msg) { g_error = msg; }
+
+bcp_status hip_fail(hipError_t e, const char* what) {
+  g_error = std::string(what) + ": " + hipGetErrorString(e);
+  if (e == hipErrorOutOfMemory) return BCP_ERR_OOM;
+  if (e == hipErrorNoDevice || e == hipErrorInvalidDevice) return BCP_ERR_NO_DEVICE;
+  return BCP_ERR_HIP;
+}
+
+PlanConfig& config() { return g_config; }
+
+}  // namespace bcp
+
+using namespace bcp;
+
+// The pointer table of a reshard call travels host -> device through a small ring of pinned
+// staging slots, so an asynchronous call never reads a slot a later call already rewrote.
+constexpr int kSlots = 8;
+
+struct bcp_plan_s {
+  PlanDevice dev;
+  bcp_stats stats{};
+  int device = 0;
+  void* table_dev = nullptr;   // [queue counter | src pointers | dst pointers]
+  char* table_host = nullptr;  // pinned, kSlots slots
+  size_t table_bytes = 0;
+  int32_t n_src = 0, n_dst = 0;
+  hipEvent_t slot_done[kSlots]{};
+  bool slot_used[kSlots]{};
+  int next_slot = 0;
+  std::mutex mu;
+};
+
+extern "C" {
+
+const char* bcp_last_error(void) { return g_error.c_str(); }
+
+const char* bcp_status_name(bcp_status s) {
+  switch (s) {
+    case BCP_OK: return "BCP_OK";
+    case BCP_ERR_INVALID_ARG: return "BCP_ERR_INVALID_ARG";
+    case BCP_ERR_SHAPE_MISMATCH: return "BCP_ERR_SHAPE_MISMATCH";
+    case BCP_ERR_DTYPE_MISMATCH: return "BCP_ERR_DTYPE_MISMATCH";
+    case BCP_ERR_OUT_OF_BOUNDS: return "BCP_ERR_OUT_OF_BOUNDS";
+    case BCP_ERR_SAVED_OVERLAP: return "BCP_ERR_SAVED_OVERLAP";
+    case BCP_ERR_UNCOVERED: return "BCP_ERR_UNCOVERED";
+    case BCP_ERR_TOO_MANY_DIMS: return "BCP_ERR_TOO_MANY_DIMS";
+    case BCP_ERR_OOM: return "BCP_ERR_OOM";
+    case BCP_ERR_HIP: return "BCP_ERR_HIP";
+    case BCP_ERR_NO_DEVICE: return "BCP_ERR_NO_DEVICE";
+  }
+  return "BCP_ERR_UNKNOWN";
+}
+
+int32_t bcp_abi_version(void) { return 1; }
+int64_t bcp_sizeof_shard_meta(void) { return (int64_t)sizeof(bcp_shard_meta); }
+
+bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu) {
+  std::lock_guard<std::mutex> g(g_config_mu);
+  if (tile_bytes > 0) {
+    if (tile_bytes < 4096 || tile_bytes > (4 << 20) || (tile_bytes & (tile_bytes - 1))) {
+      set_error("tile_bytes must be a power of two in [4 KiB, 4 MiB]");
+      return BCP_ERR_INVALID_ARG;
+    }
+    g_config.tile_bytes = tile_bytes;
+  }
+  if (persistent >= 0) g_config.persistent = persistent ? 1 : 0;
+  if (wg_per_cu > 0) {
+    if (wg_per_cu > 64) {
+      set_error("wg_per_cu must be <= 64");
+      return BCP_ERR_INVALID_ARG;
+    }
+    g_config.wg_per_cu = wg_per_cu;
+  }
+  return BCP_OK;
+}
+
+// ---- a1: flat slice of a concatenation -> per-tensor records ----------------------------------
+bcp_status bcp_meta_from_flat_slice(const bcp_shard_meta* params, int64_t n_params, int64_t A, int64_t B,
+                                    int32_t buf, int64_t byte_offset, bcp_shard_meta* out, int64_t* inout_n) {
+  if (!inout_n || n_params < 0 || (n_params > 0 && !params) || A < 0 || B < A || buf < 0 || byte_offset < 0) {
+    set_error("bcp_meta_from_flat_slice: bad argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  const int64_t room = *inout_n;
+  int64_t written = 0, pos = 0;
+  for (int64_t i = 0; i < n_params; ++i) {
+    const bcp_shard_meta& p = params[i];
+    if (p.ndim < 0 || p.ndim > BCP_MAX_DIMS) {
+      set_error("bcp_meta_from_flat_slice: bad ndim in parameter " + std::to_string(i));
+      return p.ndim < 0 ? BCP_ERR_INVALID_ARG : BCP_ERR_TOO_MANY_DIMS;
+    }
+    int64_t vol = 1;
+    bool strided = false;
+    for (int k = 0; k < p.ndim; ++k) {
+      if (p.lengths[k] < 0) {
+        set_error("bcp_meta_from_flat_slice: negative length");
+        return BCP_ERR_INVALID_ARG;
+      }
+      vol *= p.lengths[k];
+      strided |= p.strides[k] != 0;
+    }
+    if (strided || p.flat_begin != 0 || p.flat_end != vol || p.itemsize != params[0].itemsize) {
+      set_error("bcp_meta_from_flat_slice: parameter " + std::to_string(i) +
+                " must be a regular packed record of the common itemsize");
+      return BCP_ERR_INVALID_ARG;
+    }
+    // the part of [A, B) inside this tensor's span [pos, pos + vol)
+    const int64_t lo = std::max(A, pos), hi = std::min(B, pos + vol);
+    if (lo < hi) {
+      if (out && written < room) {
+        bcp_shard_meta r = p;
+        r.flat_begin = lo - pos;
+        r.flat_end = hi - pos;
+        r.buf = buf;
+        r.byte_offset = byte_offset + (int64_t)p.itemsize * (lo - A);
+        out[written] = r;
+      }
+      ++written;
+    }
+    pos += vol;
+  }
+  if (B > pos) {
+    set_error("bcp_meta_from_flat_slice: slice ends beyond the concatenation");
+    return BCP_ERR_OUT_OF_BOUNDS;
+  }
+  *inout_n = written;
+  if (written > room || (written > 0 && !out)) {
+    set_error("bcp_meta_from_flat_slice: output array too small");
+    return BCP_ERR_INVALID_ARG;
+  }
+  return BCP_OK;
+}
+
+// ---- a2: host mirror of the device decomposer ---------------------------------------------------
+bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, int64_t* inout_n) {
+  if (!rec || !inout_n) {
+    set_error("bcp_decompose: null argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  if (rec->ndim < 0 || rec->ndim > BCP_MAX_DIMS) {
+    set_error("bcp_decompose: bad ndim");
+    return rec->ndim < 0 ? BCP_ERR_INVALID_ARG : BCP_ERR_TOO_MANY_DIMS;
+  }
+  int64_t len[kDims];
+  int n = rec->ndim;
+  int64_t vol = 1;
+  for (int k = 0; k < n; ++k) {
+    if (rec->lengths[k] < 0) {
+      set_error("bcp_decompose: negative length");
+      return BCP_ERR_INVALID_ARG;
+    }
+    len[k] = rec->lengths[k];
+    vol *= len[k];
+    if (rec->strides[k] != 0) {
+      set_error("bcp_decompose: strided records are regular by definition");
+      return BCP_ERR_INVALID_ARG;
+    }
+  }
+  if (n == 0) {
+    len[0] = 1;
+    n = 1;
+  }
+  if (rec->flat_begin < 0 || rec->flat_end < rec->flat_begin || rec->flat_end > vol) {
+    set_error("bcp_decompose: flat range outside the box");
+    return BCP_ERR_OUT_OF_BOUNDS;
+  }
+  LocalBox lb[kMaxBoxesPerRecord];
+  const int nb = decompose_flat_range(len, n, rec->flat_begin, rec->flat_end, lb);
+  const int64_t room = *inout_n;
+  *inout_n = nb;
+  if (nb > room || (nb > 0 && !out_boxes)) {
+    set_error("bcp_decompose: output array too small");
+    return BCP_ERR_INVALID_ARG;
+  }
+  for (int j = 0; j < nb; ++j) {
+    bcp_shard_meta b = *rec;
+    int64_t v = 1;
+    for (int k = 0; k < rec->ndim; ++k) {
+      b.offsets[k] = rec->offsets[k] + lb[j].off[k];
+      b.lengths[k] = lb[j].len[k];
+      v *= lb[j].len[k];
+    }
+    b.flat_begin = 0;
+    b.flat_end = v;
+    b.byte_offset = rec->byte_offset + (int64_t)rec->itemsize * (lb[j].flat_start - rec->flat_begin);
+    out_boxes[j] = b;
+  }
+  return BCP_OK;
+}
+
+// ---- plan ------------------------------------------------------------------------------------
+bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shard_meta* target, int64_t n_target,
+                    uint32_t flags, void* stream, bcp_plan_t* out_plan) {
+  const auto t0 = std::chrono::steady_clock::now();
+  if (!out_plan) {
+    set_error("bcp_plan: out_plan is null");
+    return BCP_ERR_INVALID_ARG;
+  }
+  *out_plan = nullptr;
+  if (n_saved < 0 || n_target < 0 || (n_saved > 0 && !saved) || (n_target > 0 && !target)) {
+    set_error("bcp_plan: null metadata array or negative count");
+    return BCP_ERR_INVALID_ARG;
+  }
+  if (flags & ~(BCP_ALLOW_UNCOVERED | BCP_SKIP_OVERLAP_CHECK)) {
+    set_error("bcp_plan: unknown flag");
+    return BCP_ERR_INVALID_ARG;
+  }
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+    set_error("bcp_plan: no HIP device available");
+    return BCP_ERR_NO_DEVICE;
+  }
+  bcp_plan_s* plan = new (std::nothrow) bcp_plan_s();
+  if (!plan) {
+    set_error("bcp_plan: host allocation failed");
+    return BCP_ERR_OOM;
+  }
+  bcp_status s = BCP_OK;
+  PlannerResult res;
+  do {
+    if (hipGetDevice(&plan->device) != hipSuccess) {
+      set_error("bcp_plan: hipGetDevice failed");
+      s = BCP_ERR_NO_DEVICE;
+      break;
+    }
+    s = run_planner(saved, n_saved, target, n_target, flags, (hipStream_t)stream, &res);
+    if (s != BCP_OK) break;
+    plan->dev = res.dev;
+    bcp_stats& st = plan->stats;
+    st.n_saved_boxes = res.n_saved_boxes;
+    st.n_target_boxes = res.n_target_boxes;
+    st.n_pairs = (int64_t)res.ctl.n_pairs;
+    st.n_regions = (int64_t)res.ctl.n_regions;
+    st.n_tiles = (int64_t)res.ctl.n_tiles;
+    st.payload_bytes = (int64_t)res.ctl.payload_bytes;
+    st.n_transposed = (int64_t)res.ctl.n_transposed;
+    st.max_src_buf = res.ctl.max_src_buf;
+    st.max_dst_buf = res.ctl.max_dst_buf;
+    for (int k = 0; k <= BCP_MAX_DIMS; ++k) st.region_dims_hist[k] = (int64_t)res.ctl.dims_hist[k];
+    st.plan_device_ms = res.device_ms;
+    plan->n_src = (int32_t)(st.max_src_buf + 1);
+    plan->n_dst = (int32_t)(st.max_dst_buf + 1);
+    plan->table_bytes = 8 + sizeof(void*) * (size_t)(plan->n_src + plan->n_dst);
+    hipError_t e = hipMalloc(&plan->table_dev, plan->table_bytes);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&plan->table_host, plan->table_bytes * kSlots, hipHostMallocDefault);
+    for (int i = 0; i < kSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&plan->slot_done[i], hipEventDisableTiming);
+    if (e != hipSuccess) {
+      s = hip_fail(e, "bcp_plan: pointer table allocation");
+      break;
+    }
+  } while (0);
+  if (s != BCP_OK) {
+    const std::string keep = g_error;
+    bcp_plan_destroy(plan);
+    g_error = keep;
+    return s;
+  }
+  plan->stats.plan_wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  *out_plan = plan;
+  return BCP_OK;
+}
+
+bcp_status bcp_plan_destroy(bcp_plan_t plan) {
+  if (!plan) return BCP_OK;
+  if (plan->dev.regions) (void)hipFree(plan->dev.regions);
+  if (plan->dev.tiles) (void)hipFree(plan->dev.tiles);
+  if (plan->table_dev) (void)hipFree(plan->table_dev);
+  if (plan->table_host) (void)hipHostFree(plan->table_host);
+  for (int i = 0; i < kSlots; ++i)
+    if (plan->slot_done[i]) (void)hipEventDestroy(plan->slot_done[i]);
+  delete plan;
+  return BCP_OK;
+}
+
+bcp_status bcp_plan_stats(bcp_plan_t plan, bcp_stats* out) {
+  if (!plan || !out) {
+    set_error("bcp_plan_stats: null argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  *out = plan->stats;
+  return BCP_OK;
+}
+
+bcp_status bcp_plan_regions(bcp_plan_t plan, bcp_region_info* out, int64_t capacity, int64_t* n_regions) {
+  if (!plan || !n_regions || capacity < 0 || (capacity > 0 && !out)) {
+    set_error("bcp_plan_regions: bad argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  *n_regions = plan->dev.n_regions;
+  const int64_t n = std::min(capacity, plan->dev.n_regions);
+  if (n == 0) return BCP_OK;
+  std::vector<Region> tmp((size_t)n);
+  BCP_HIP(hipMemcpy(tmp.data(), plan->dev.regions, sizeof(Region) * (size_t)n, hipMemcpyDeviceToHost));
+  for (int64_t i = 0; i < n; ++i) {
+    const Region& r = tmp[(size_t)i];
+    bcp_region_info& o = out[i];
+    std::memset(&o, 0, sizeof(o));
+    o.src_base = r.src_base;
+    o.dst_base = r.dst_base;
+    o.run_bytes = r.run_bytes;
+    for (int k = 0; k < BCP_MAX_DIMS; ++k) {
+      o.len[k] = r.len[k];
+      o.src_pitch[k] = r.spitch[k];
+      o.dst_pitch[k] = r.dpitch[k];
+    }
+    o.ndim = r.ndim;
+    o.src_buf = r.src_buf;
+    o.dst_buf = r.dst_buf;
+    o.kind = r.kind;
+    o.target_index = r.trec;
+    o.saved_index = r.srec;
+  }
+  return BCP_OK;
+}
+
+bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t n_src, int64_t* dst_extent,
+                                   int32_t n_dst) {
+  if (!plan || n_src < plan->n_src || n_dst < plan->n_dst || (n_src > 0 && !src_extent) || (n_dst > 0 && !dst_extent)) {
+    set_error("bcp_plan_buffer_extents: bad argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  for (int32_t i = 0; i < n_src; ++i) src_extent[i] = 0;
+  for (int32_t i = 0; i < n_dst; ++i) dst_extent[i] = 0;
+  const int64_t n = plan->dev.n_regions;
+  const int64_t chunk = 1 << 16;
+  std::vector<Region> tmp((size_t)std::min(n, chunk));
+  for (int64_t base = 0; base < n; base += chunk) {
+    const int64_t m = std::min(chunk, n - base);
+    BCP_HIP(hipMemcpy(tmp.data(), plan->dev.regions + base, sizeof(Region) * (size_t)m, hipMemcpyDeviceToHost));
+    for (int64_t i = 0; i < m; ++i) {
+      const Region& r = tmp[(size_t)i];
+      int64_t s_end = r.src_base + r.run_bytes, d_end = r.dst_base + r.run_bytes;
+      for (int k = 0; k < r.ndim; ++k) {
+        s_end += (r.len[k] - 1) * r.spitch[k];
+        d_end += (r.len[k] - 1) * r.dpitch[k];
+      }
+      src_extent[r.src_buf] = std::max(src_extent[r.src_buf], s_end);
+      dst_extent[r.dst_buf] = std::max(dst_extent[r.dst_buf], d_end);
+    }
+  }
+  return BCP_OK;
+}
+
+// ---- reshard ---------------------------------------------------------------------------------
+bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
+                       int32_t n_dst, void* stream) {
+  if (!plan) {
+    set_error("bcp_reshard: plan is null");
+    return BCP_ERR_INVALID_ARG;
+  }
+  if (plan->dev.n_tiles == 0) return BCP_OK;
+  if (!src_blobs || !dst_buffers || n_src < plan->n_src || n_dst < plan->n_dst) {
+    set_error("bcp_reshard: need at least " + std::to_string(plan->n_src) + " source and " +
+              std::to_string(plan->n_dst) + " destination buffers");
+    return BCP_ERR_INVALID_ARG;
+  }
+  for (int32_t i = 0; i < plan->n_src; ++i)
+    if (!src_blobs[i]) {
+      set_error("bcp_reshard: src_blobs[" + std::to_string(i) + "] is null");
+      return BCP_ERR_INVALID_ARG;
+    }
+  for (int32_t i = 0; i < plan->n_dst; ++i)
+    if (!dst_buffers[i]) {
+      set_error("bcp_reshard: dst_buffers[" + std::to_string(i) + "] is null");
+      return BCP_ERR_INVALID_ARG;
+    }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) {
+    set_error("bcp_reshard: the plan belongs to another device");
+    return BCP_ERR_INVALID_ARG;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  std::lock_guard<std::mutex> g(plan->mu);
+  const int slot = plan->next_slot;
+  plan->next_slot = (slot + 1) % kSlots;
+  if (plan->slot_used[slot]) BCP_HIP(hipEventSynchronize(plan->slot_done[slot]));
+  char* h = plan->table_host + plan->table_bytes * (size_t)slot;
+  std::memset(h, 0, 8);  // queue counter starts at zero
+  std::memcpy(h + 8, src_blobs, sizeof(void*) * (size_t)plan->n_src);
+  std::memcpy(h + 8 + sizeof(void*) * (size_t)plan->n_src, dst_buffers, sizeof(void*) * (size_t)plan->n_dst);
+  BCP_HIP(hipMemcpyAsync(plan->table_dev, h, plan->table_bytes, hipMemcpyHostToDevice, st));
+  BCP_HIP(hipEventRecord(plan->slot_done[slot], st));
+  plan->slot_used[slot] = true;
+  return launch_reshard(plan->dev, plan->table_dev, plan->n_src, st);
+}
+
+bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream) {
+  if (!dst || !src || nbytes < 0) {
+    set_error("bcp_copy_baseline: bad argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  return launch_copy_baseline(dst, src, nbytes, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,349 @@
+// The copy kernel: executes a plan's tiles.  Pure byte movement, HBM-bandwidth bound:
+// every payload byte is read once and written once; there is no contraction, hence no MFMA.
+//
+// A tile is at most tile_bytes of payload: a segment of one long row, or a few whole short
+// rows.  One 256-thread workgroup (4 wave64) per tile.  Per tile the kernel picks, wave-uniformly
+// and from the actual addresses, one of
+//   * 16-byte vector path   -- bases, run length and pitches all 16-byte aligned;
+//   * misaligned-run path   -- long runs whose source and destination disagree modulo 16 (ZeRO
+//                              slice boundaries): peel to a 16-byte aligned destination, then
+//                              unaligned 16-byte loads + aligned 16-byte stores;
+//   * granule path          -- short runs: 8/4/2/1-byte elements, flat over rows x run;
+//   * LDS-staged transpose  -- the source-contiguous and destination-contiguous dimensions
+//                              differ (strided shards): both global sides stay coalesced.
+// Workgroups either map 1:1 to tiles or, in persistent mode, pop tile indices from an atomic
+// queue until it runs dry.
+#include <algorithm>
+
+#include "bcp_internal.h"
+
+namespace bcp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kLdsBytes = 32 * 33 * 16;  // >= 64*65*4: transpose staging incl. one pad column
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+// Buffer pointers come out of a table in memory, so the compiler cannot tell their address space
+// and would emit flat accesses; they are device (global) memory by contract.
+#define BCP_GLOBAL __attribute__((address_space(1)))
+typedef const char BCP_GLOBAL* gsrc_t;
+typedef char BCP_GLOBAL* gdst_t;
+
+template <int G> struct Granule;
+template <> struct Granule<16> { typedef u32x4 type; };
+template <> struct Granule<8> { typedef u32x2 type; };
+template <> struct Granule<4> { typedef uint32_t type; };
+template <> struct Granule<2> { typedef uint16_t type; };
+template <> struct Granule<1> { typedef uint8_t type; };
+
+template <int G>
+__device__ __forceinline__ typename Granule<G>::type ld(gsrc_t p) {
+  return *(const typename Granule<G>::type BCP_GLOBAL*)p;
+}
+template <int G>
+__device__ __forceinline__ void st(gdst_t p, typename Granule<G>::type v) {
+  *(typename Granule<G>::type BCP_GLOBAL*)p = v;
+}
+template <int G>
+__device__ __forceinline__ typename Granule<G>::type lds_ld(const char* p) {
+  return *reinterpret_cast<const typename Granule<G>::type*>(p);
+}
+template <int G>
+__device__ __forceinline__ void lds_st(char* p, typename Granule<G>::type v) {
+  *reinterpret_cast<typename Granule<G>::type*>(p) = v;
+}
+
+struct __attribute__((packed, aligned(1))) Unaligned16 {
+  u32x4 v;
+};
+__device__ __forceinline__ u32x4 ld16_unaligned(gsrc_t p) { return ((const Unaligned16 BCP_GLOBAL*)p)->v; }
+
+// rows x run_g granules of G bytes; rows at pitches sp / dp.  `nt` threads cooperate, `tid` in [0, nt).
+template <int G>
+__device__ __forceinline__ void copy_rows(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
+                                          uint32_t run_g, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
+  typedef typename Granule<G>::type V;
+  if (nrows == 1) {
+    uint32_t i = tid;
+    for (; i + 3 * nt < run_g; i += 4 * nt) {
+      const V a = ld<G>(s + (size_t)i * G);
+      const V b = ld<G>(s + (size_t)(i + nt) * G);
+      const V c = ld<G>(s + (size_t)(i + 2 * nt) * G);
+      const V e = ld<G>(s + (size_t)(i + 3 * nt) * G);
+      st<G>(d + (size_t)i * G, a);
+      st<G>(d + (size_t)(i + nt) * G, b);
+      st<G>(d + (size_t)(i + 2 * nt) * G, c);
+      st<G>(d + (size_t)(i + 3 * nt) * G, e);
+    }
+    for (; i < run_g; i += nt) st<G>(d + (size_t)i * G, ld<G>(s + (size_t)i * G));
+    return;
+  }
+  const uint32_t total = nrows * run_g;
+  // (row, col) of granule tid, then advance by nt granules per step without dividing again
+  uint32_t row = tid / run_g, col = tid - row * run_g;
+  const uint32_t drow = nt / run_g, dcol = nt - drow * run_g;
+  uint32_t i = tid;
+  for (; i + 3 * nt < total; i += 4 * nt) {
+    V v[4];
+    int64_t so[4], dof[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      so[u] = (int64_t)row * sp + (int64_t)col * G;
+      dof[u] = (int64_t)row * dp + (int64_t)col * G;
+      col += dcol;
+      row += drow;
+      if (col >= run_g) {
+        col -= run_g;
+        ++row;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = ld<G>(s + so[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) st<G>(d + dof[u], v[u]);
+  }
+  for (; i < total; i += nt) {
+    st<G>(d + (int64_t)row * dp + (int64_t)col * G, ld<G>(s + (int64_t)row * sp + (int64_t)col * G));
+    col += dcol;
+    row += drow;
+    if (col >= run_g) {
+      col -= run_g;
+      ++row;
+    }
+  }
+}
+
+// one contiguous run whose two sides disagree modulo 16: byte head up to the destination's next
+// 16-byte boundary, aligned 16-byte stores fed by unaligned 16-byte loads, byte tail.  nt >= 16.
+__device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t run,
+                                                    uint32_t tid, uint32_t nt) {
+  uint32_t head = (uint32_t)(-(uintptr_t)d) & 15u;
+  if (head > run) head = run;
+  if (tid < head) d[tid] = s[tid];
+  const uint32_t body = (run - head) >> 4;
+  gsrc_t s2 = s + head;
+  gdst_t d2 = d + head;
+  uint32_t i = tid;
+  for (; i + 3 * nt < body; i += 4 * nt) {
+    const u32x4 a = ld16_unaligned(s2 + (size_t)i * 16);
+    const u32x4 b = ld16_unaligned(s2 + (size_t)(i + nt) * 16);
+    const u32x4 c = ld16_unaligned(s2 + (size_t)(i + 2 * nt) * 16);
+    const u32x4 e = ld16_unaligned(s2 + (size_t)(i + 3 * nt) * 16);
+    st<16>(d2 + (size_t)i * 16, a);
+    st<16>(d2 + (size_t)(i + nt) * 16, b);
+    st<16>(d2 + (size_t)(i + 2 * nt) * 16, c);
+    st<16>(d2 + (size_t)(i + 3 * nt) * 16, e);
+  }
+  for (; i < body; i += nt) st<16>(d2 + (size_t)i * 16, ld16_unaligned(s2 + (size_t)i * 16));
+  const uint32_t done = head + (body << 4);
+  const uint32_t tail = run - done;
+  if (tid < tail) d[done + tid] = s[done + tid];
+}
+
+template <int E>
+__device__ __forceinline__ void transpose_tile(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na,
+                                               uint32_t nb, int64_t spb, int64_t dpa, uint32_t td, char* lds) {
+  // source: element (a, b) at s + a*E + b*spb (contiguous along a)
+  // destination: element (a, b) at d + b*E + a*dpa (contiguous along b)
+  const uint32_t pitch = td + 1;  // LDS row pitch in elements
+  const uint32_t x = threadIdx.x % td, y0 = threadIdx.x / td, step = kThreads / td;
+  if (x < na)
+    for (uint32_t b = y0; b < nb; b += step) lds_st<E>(lds + (size_t)(b * pitch + x) * E, ld<E>(s + (size_t)x * E + (int64_t)b * spb));
+  __syncthreads();
+  if (x < nb)
+    for (uint32_t a = y0; a < na; a += step) st<E>(d + (size_t)x * E + (int64_t)a * dpa, lds_ld<E>(lds + (size_t)(x * pitch + a) * E));
+}
+
+__device__ __forceinline__ void process_tile(const Region* __restrict__ regions, Tile tile,
+                                             const char* const* __restrict__ src_ptrs,
+                                             char* const* __restrict__ dst_ptrs, char* lds) {
+  const Region& R = regions[tile.region];
+  gsrc_t s = (gsrc_t)src_ptrs[R.src_buf] + R.src_base;
+  gdst_t d = (gdst_t)dst_ptrs[R.dst_buf] + R.dst_base;
+  const int nd = R.ndim;
+  const uint32_t tpg = R.tiles_per_group;
+  uint32_t group = tile.local / tpg;
+  const uint32_t w = tile.local - group * tpg;
+
+  if (R.kind == kTranspose) {
+    for (int k = nd - 3; k >= 0; --k) {
+      const uint64_t L = (uint64_t)R.len[k];
+      const uint64_t c = group % L;
+      group = (uint32_t)(group / L);
+      s += c * R.spitch[k];
+      d += c * R.dpitch[k];
+    }
+    const uint32_t td = R.tdim;
+    const uint32_t ta = w / R.tiles_b, tb = w - ta * R.tiles_b;
+    const uint32_t a0 = ta * td, b0 = tb * td;
+    const uint32_t na = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 2] - a0);
+    const uint32_t nb = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 1] - b0);
+    const int64_t spa = R.spitch[nd - 2], spb = R.spitch[nd - 1];
+    const int64_t dpa = R.dpitch[nd - 2], dpb = R.dpitch[nd - 1];
+    s += (int64_t)a0 * spa + (int64_t)b0 * spb;
+    d += (int64_t)a0 * dpa + (int64_t)b0 * dpb;
+    const uint32_t e = (uint32_t)R.run_bytes;
+    const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
+    if ((al & (e - 1)) == 0) {
+      switch (e) {
+        case 1: transpose_tile<1>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 2: transpose_tile<2>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 4: transpose_tile<4>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 8: transpose_tile<8>(s, d, na, nb, spb, dpa, td, lds); break;
+        default: transpose_tile<16>(s, d, na, nb, spb, dpa, td, lds); break;
+      }
+    } else {  // elements not aligned to their own size: plain byte moves
+      const uint32_t total = na * nb * e;
+      for (uint32_t i = threadIdx.x; i < total; i += kThreads) {
+        const uint32_t el = i / e, by = i - el * e;
+        const uint32_t b = el / na, a = el - b * na;
+        d[(int64_t)a * dpa + (int64_t)b * dpb + by] = s[(int64_t)a * spa + (int64_t)b * spb + by];
+      }
+    }
+    return;
+  }
+
+  // kRows
+  for (int k = nd - 2; k >= 0; --k) {
+    const uint64_t L = (uint64_t)R.len[k];
+    const uint64_t c = group % L;
+    group = (uint32_t)(group / L);
+    s += c * R.spitch[k];
+    d += c * R.dpitch[k];
+  }
+  uint32_t nrows = 1;
+  uint32_t run;
+  int64_t sp = 0, dp = 0;
+  if (nd >= 1) {
+    sp = R.spitch[nd - 1];
+    dp = R.dpitch[nd - 1];
+  }
+  if (R.segs_per_row > 1 || (uint64_t)R.run_bytes >= R.tile_bytes) {
+    const uint32_t row = w / R.segs_per_row, seg = w - row * R.segs_per_row;
+    const int64_t off = (int64_t)seg * R.tile_bytes;
+    s += (int64_t)row * sp + off;
+    d += (int64_t)row * dp + off;
+    run = (uint32_t)min((int64_t)R.tile_bytes, R.run_bytes - off);
+  } else {
+    const uint64_t L0 = nd >= 1 ? (uint64_t)R.len[nd - 1] : 1;
+    const uint64_t row0 = (uint64_t)w * R.rows_per_tile;
+    nrows = (uint32_t)min((uint64_t)R.rows_per_tile, L0 - row0);
+    s += (int64_t)row0 * sp;
+    d += (int64_t)row0 * dp;
+    run = (uint32_t)R.run_bytes;
+  }
+  uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
+  if (nrows > 1) al |= (uintptr_t)sp | (uintptr_t)dp;
+  if ((al & 15u) == 0) {
+    copy_rows<16>(s, d, nrows, run >> 4, sp, dp, threadIdx.x, kThreads);
+  } else if (run >= 256) {
+    if (nrows == 1) {
+      copy_run_misaligned(s, d, run, threadIdx.x, kThreads);
+    } else {
+      const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+      for (uint32_t r = wave; r < nrows; r += kThreads / 64)
+        copy_run_misaligned(s + (int64_t)r * sp, d + (int64_t)r * dp, run, lane, 64);
+    }
+  } else if ((al & 7u) == 0) {
+    copy_rows<8>(s, d, nrows, run >> 3, sp, dp, threadIdx.x, kThreads);
+  } else if ((al & 3u) == 0) {
+    copy_rows<4>(s, d, nrows, run >> 2, sp, dp, threadIdx.x, kThreads);
+  } else if ((al & 1u) == 0) {
+    copy_rows<2>(s, d, nrows, run >> 1, sp, dp, threadIdx.x, kThreads);
+  } else {
+    copy_rows<1>(s, d, nrows, run, sp, dp, threadIdx.x, kThreads);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_reshard(const Region* __restrict__ regions,
+                                                      const Tile* __restrict__ tiles, uint32_t n_tiles,
+                                                      const char* const* __restrict__ src_ptrs,
+                                                      char* const* __restrict__ dst_ptrs,
+                                                      unsigned long long* queue, int persistent) {
+  __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
+  __shared__ uint32_t next_tile;
+  if (!persistent) {
+    const uint32_t t = blockIdx.x;
+    if (t < n_tiles) process_tile(regions, tiles[t], src_ptrs, dst_ptrs, lds);
+    return;
+  }
+  for (;;) {
+    if (threadIdx.x == 0) next_tile = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_tiles);
+    __syncthreads();
+    const uint32_t t = __builtin_amdgcn_readfirstlane(next_tile);
+    __syncthreads();  // everyone has read next_tile (and is done with lds) before it changes again
+    if (t >= n_tiles) return;  // uniform: the queue is monotonic, every workgroup ends here
+    process_tile(regions, tiles[t], src_ptrs, dst_ptrs, lds);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_copy_baseline(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                            uint64_t n_vec, uint32_t vec_per_block) {
+  const uint64_t base = (uint64_t)blockIdx.x * vec_per_block;
+  const uint64_t end = min(n_vec, base + vec_per_block);
+  uint64_t i = base + threadIdx.x;
+  for (; i + 3 * kThreads < end; i += 4 * kThreads) {
+    const u32x4 a = src[i], b = src[i + kThreads], c = src[i + 2 * kThreads], e = src[i + 3 * kThreads];
+    dst[i] = a;
+    dst[i + kThreads] = b;
+    dst[i + 2 * kThreads] = c;
+    dst[i + 3 * kThreads] = e;
+  }
+  for (; i < end; i += kThreads) dst[i] = src[i];
+}
+
+}  // namespace
+
+int device_cu_count() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return n;
+}
+
+bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, hipStream_t stream) {
+  if (plan.n_tiles == 0) return BCP_OK;
+  unsigned long long* queue = (unsigned long long*)table;
+  const char* const* src_ptrs = (const char* const*)((const char*)table + 8);
+  char* const* dst_ptrs = (char* const*)((const char*)table + 8 + sizeof(void*) * (size_t)n_src);
+  const PlanConfig& cfg = config();
+  unsigned grid;
+  if (cfg.persistent) {
+    const int cus = device_cu_count();
+    if (cus <= 0) {
+      set_error("cannot read the CU count");
+      return BCP_ERR_NO_DEVICE;
+    }
+    grid = (unsigned)std::min<int64_t>(plan.n_tiles, (int64_t)cus * cfg.wg_per_cu);
+  } else {
+    grid = (unsigned)plan.n_tiles;
+  }
+  hipLaunchKernelGGL(k_reshard, dim3(grid), dim3(kThreads), 0, stream, plan.regions, plan.tiles,
+                     (uint32_t)plan.n_tiles, src_ptrs, dst_ptrs, queue, cfg.persistent);
+  BCP_HIP(hipGetLastError());
+  return BCP_OK;
+}
+
+bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream) {
+  if (nbytes <= 0) return BCP_OK;
+  if ((((uintptr_t)dst | (uintptr_t)src) & 15u) || (nbytes & 15)) {
+    set_error("bcp_copy_baseline needs 16-byte aligned pointers and size");
+    return BCP_ERR_INVALID_ARG;
+  }
+  const uint64_t n_vec = (uint64_t)nbytes / 16;
+  const uint32_t vpb = (uint32_t)(config().tile_bytes / 16);
+  const uint64_t grid = (n_vec + vpb - 1) / vpb;
+  if (grid >= 0x7fffffffull) {
+    set_error("copy too large for one launch");
+    return BCP_ERR_INVALID_ARG;
+  }
+  hipLaunchKernelGGL(k_copy_baseline, dim3((unsigned)grid), dim3(kThreads), 0, stream, (u32x4*)dst, (const u32x4*)src,
+                     n_vec, vpb);
+  BCP_HIP(hipGetLastError());
+  return BCP_OK;
+}
+
+}  // namespace bcp

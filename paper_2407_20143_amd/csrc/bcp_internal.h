@@ -1,0 +1,122 @@
+// Internal data structures shared by the planner, the copy kernels and the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "bcp.h"
+#include "bcp_decompose.h"
+
+namespace bcp {
+
+static_assert(kDims == BCP_MAX_DIMS, "dimension limit");
+
+// A regular box of one stored record, in global coordinates, with where its elements live.
+struct Box {
+  int64_t fqn;
+  int64_t off[kDims];
+  int64_t len[kDims];
+  int64_t stride[kDims];  // element strides of the storage
+  int64_t byte_base;      // byte offset (in buffer `buf`) of the box's first element
+  int32_t rec;            // index of the record it came from (within its side)
+  int32_t ndim;           // >= 1 (scalars are stored as one dimension of extent 1)
+  int32_t itemsize;
+  int32_t buf;
+};
+
+enum RegionKind : int32_t { kRows = 0, kTranspose = 1 };
+
+// One copy region: `len[0..ndim)` rows (slowest first) of `run_bytes` contiguous bytes.
+// kTranspose: run_bytes == itemsize, len[ndim-2] runs along the source-contiguous dimension
+// (src pitch == itemsize) and len[ndim-1] along the destination-contiguous one.
+struct Region {
+  int64_t src_base, dst_base;
+  int64_t run_bytes;
+  int64_t len[kDims];
+  int64_t spitch[kDims];
+  int64_t dpitch[kDims];
+  int32_t ndim;
+  int32_t src_buf, dst_buf;
+  int32_t kind;
+  int32_t trec, srec;
+  // tiling (see tile_region)
+  uint32_t tile_bytes;       // payload budget per tile
+  uint32_t rows_per_tile;    // kRows, run < tile_bytes: rows of the last row dimension per tile
+  uint32_t segs_per_row;     // kRows, run >= tile_bytes: tiles per row
+  uint32_t tiles_per_group;  // tiles per index of the leading row dimensions
+  uint32_t tdim;             // kTranspose: tile edge in elements
+  uint32_t tiles_b;          // kTranspose: tiles along the last dimension
+  uint64_t n_tiles;
+};
+
+struct Tile {
+  uint32_t region;
+  uint32_t local;  // tile index inside the region
+};
+
+// Device control block: written by kernels, read back by the host between phases.
+struct Ctl {
+  unsigned long long err_key;  // min over (record index << 8 | code); ~0 == no error
+  unsigned long long max_saved_fqn;
+  unsigned long long n_pairs;
+  unsigned long long n_regions;
+  unsigned long long n_tiles;
+  unsigned long long payload_bytes;
+  unsigned long long n_transposed;
+  long long max_src_buf, max_dst_buf;
+  unsigned long long dims_hist[kDims + 1];
+};
+
+// device error codes carried in err_key's low byte (mapped to bcp_status on the host)
+enum DevErr : unsigned {
+  kErrInvalid = 1,
+  kErrTooManyDims = 2,
+  kErrBounds = 3,
+  kErrShape = 4,
+  kErrDtype = 5,
+  kErrOverlap = 6,
+  kErrUncovered = 7,
+};
+
+struct PlanConfig {
+  int64_t tile_bytes = 64 * 1024;
+  int32_t persistent = 0;
+  int32_t wg_per_cu = 8;
+};
+PlanConfig& config();
+
+void set_error(const std::string& msg);
+bcp_status hip_fail(hipError_t e, const char* what);
+
+#define BCP_HIP(expr)                                   \
+  do {                                                  \
+    hipError_t e_ = (expr);                             \
+    if (e_ != hipSuccess) return hip_fail(e_, #expr);   \
+  } while (0)
+
+// ---- planner (bcp_planner.hip) -------------------------------------------------------------
+struct PlanDevice {
+  Region* regions = nullptr;
+  Tile* tiles = nullptr;
+  int64_t n_regions = 0;
+  int64_t n_tiles = 0;
+};
+
+struct PlannerResult {
+  PlanDevice dev;
+  Ctl ctl;
+  int64_t n_saved_boxes = 0, n_target_boxes = 0;
+  float device_ms = 0.f;
+};
+
+bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shard_meta* target,
+                       int64_t n_target, uint32_t flags, hipStream_t stream, PlannerResult* out);
+
+// ---- copy (bcp_copy.hip) ---------------------------------------------------------------------
+// table: device block [queue counter (8 bytes) | src pointers | dst pointers]
+bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, hipStream_t stream);
+bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream);
+int device_cu_count();
+
+}  // namespace bcp

@@ -1,0 +1,765 @@
+// GPU planner: from saved / target shard records to copy regions and tiles.
+//
+// Sec. 3.3 Step 2 of the paper ("identifying matching segments between the saved tensor shards
+// and the sharding specification of new shards") run as data-parallel kernels:
+//   1. validate every record and count the regular boxes it decomposes into (Sec. 3.2
+//      "Decomposing irregular tensors"), exclusive scan, emit the boxes;
+//   2. sort the saved boxes by FQN (LSD radix sort, 4-bit digits, stable);
+//   3. per target box, find its FQN's run of saved boxes; scan the candidate-pair counts;
+//   4. one thread per candidate pair: intersect the two boxes; wave ballot + prefix to compact
+//      the non-empty intersections into a dense, deterministic region list;
+//   5. normalise each region (drop unit dims, merge dims contiguous on both sides), tile it,
+//      scan the tile counts and write the tile table; check coverage and saved disjointness.
+#include <algorithm>
+#include <vector>
+
+#include "bcp_internal.h"
+
+namespace bcp {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kScanItems = 4;  // items per thread in the device-wide scan
+
+using ull = unsigned long long;
+
+__device__ inline unsigned lane_id() { return threadIdx.x & 63u; }
+
+template <typename T>
+__device__ inline T wave_inclusive_scan(T v) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    T o = __shfl_up(v, d, 64);
+    if (lane_id() >= (unsigned)d) v += o;
+  }
+  return v;
+}
+
+// Exclusive scan of one value per thread over a 256-thread block; *total gets the block sum.
+// lds: at least 4 entries.
+template <typename T>
+__device__ inline T block_exclusive_scan(T v, T* total, T* lds) {
+  const T inc = wave_inclusive_scan(v);
+  const unsigned w = threadIdx.x >> 6;
+  if (lane_id() == 63) lds[w] = inc;
+  __syncthreads();
+  T woff = 0, tot = 0;
+#pragma unroll
+  for (unsigned i = 0; i < kBlock / 64; ++i) {
+    const T c = lds[i];
+    if (i < w) woff += c;
+    tot += c;
+  }
+  __syncthreads();
+  *total = tot;
+  return woff + inc - v;
+}
+
+// ---- device-wide exclusive scan: out[i] = sum(in[0..i)), out[n] = total --------------------
+template <typename Tin, typename T>
+__global__ __launch_bounds__(kBlock) void k_scan_reduce(const Tin* in, int64_t n, T* part) {
+  __shared__ T lds[4];
+  const int64_t base = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanItems;
+  T s = 0;
+  for (int i = 0; i < kScanItems; ++i)
+    if (base + i < n) s += (T)in[base + i];
+  T tot;
+  block_exclusive_scan(s, &tot, lds);
+  if (threadIdx.x == 0) part[blockIdx.x] = tot;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void k_scan_parts(T* part, int64_t nb) {
+  __shared__ T lds[4];
+  T carry = 0;
+  for (int64_t base = 0; base < nb; base += kBlock) {
+    const int64_t i = base + threadIdx.x;
+    const T v = i < nb ? part[i] : (T)0;
+    T tot;
+    const T ex = block_exclusive_scan(v, &tot, lds);
+    if (i < nb) part[i] = carry + ex;
+    carry += tot;
+  }
+}
+
+template <typename Tin, typename T>
+__global__ __launch_bounds__(kBlock) void k_scan_final(const Tin* in, int64_t n, const T* part, T* out) {
+  __shared__ T lds[4];
+  const int64_t base = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanItems;
+  T v[kScanItems];
+  T s = 0;
+  for (int i = 0; i < kScanItems; ++i) {
+    v[i] = base + i < n ? (T)in[base + i] : (T)0;
+    s += v[i];
+  }
+  T tot;
+  T run = block_exclusive_scan(s, &tot, lds) + part[blockIdx.x];
+  for (int i = 0; i < kScanItems; ++i) {
+    if (base + i < n) out[base + i] = run;
+    run += v[i];
+  }
+  // the thread that owns the last element also writes the grand total
+  if (base < n && base + kScanItems >= n) out[n] = run;
+}
+
+template <typename T>
+__global__ void k_set_one(T* p, T v) {
+  *p = v;
+}
+
+struct Arena {
+  std::vector<void*> ptrs;
+  ~Arena() {
+    for (void* p : ptrs) (void)hipFree(p);
+  }
+  template <typename T>
+  hipError_t alloc(T** p, size_t count) {
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T));
+    if (e == hipSuccess) {
+      ptrs.push_back(q);
+      *p = (T*)q;
+    }
+    return e;
+  }
+  void release(void* p) {  // ownership leaves the arena
+    ptrs.erase(std::remove(ptrs.begin(), ptrs.end(), p), ptrs.end());
+  }
+};
+
+inline unsigned blocks_for(int64_t n, int per_block = kBlock) {
+  return (unsigned)std::max<int64_t>(1, (n + per_block - 1) / per_block);
+}
+
+// in and out may alias when Tin == T.  out has n+1 entries.
+template <typename Tin, typename T>
+bcp_status device_scan(const Tin* in, T* out, int64_t n, Arena& arena, hipStream_t st) {
+  if (n <= 0) {
+    hipLaunchKernelGGL(k_set_one<T>, dim3(1), dim3(1), 0, st, out, (T)0);
+    BCP_HIP(hipGetLastError());
+    return BCP_OK;
+  }
+  const unsigned nb = blocks_for(n, kBlock * kScanItems);
+  T* part = nullptr;
+  BCP_HIP(arena.alloc(&part, nb));
+  hipLaunchKernelGGL((k_scan_reduce<Tin, T>), dim3(nb), dim3(kBlock), 0, st, in, n, part);
+  hipLaunchKernelGGL((k_scan_parts<T>), dim3(1), dim3(kBlock), 0, st, part, (int64_t)nb);
+  hipLaunchKernelGGL((k_scan_final<Tin, T>), dim3(nb), dim3(kBlock), 0, st, in, n, part, out);
+  BCP_HIP(hipGetLastError());
+  return BCP_OK;
+}
+
+// ---- step 1: validate, count and emit boxes --------------------------------------------------
+__device__ inline void report(Ctl* ctl, int64_t record, unsigned code) {
+  atomicMin(&ctl->err_key, ((ull)record << 8) | code);
+}
+
+__device__ inline unsigned validate_record(const bcp_shard_meta& r) {
+  if (r.ndim < 0) return kErrInvalid;
+  if (r.ndim > kDims) return kErrTooManyDims;
+  const int e = r.itemsize;
+  if (!(e == 1 || e == 2 || e == 4 || e == 8 || e == 16)) return kErrInvalid;
+  if (r.fqn_id < 0 || r.buf < 0 || r.byte_offset < 0 || r.reserved != 0) return kErrInvalid;
+  int64_t vol = 1;
+  bool strided = false;
+  for (int k = 0; k < r.ndim; ++k) {
+    if (r.global_shape[k] < 0 || r.offsets[k] < 0 || r.lengths[k] < 0 || r.strides[k] < 0) return kErrInvalid;
+    if (r.offsets[k] > r.global_shape[k] || r.lengths[k] > r.global_shape[k] - r.offsets[k]) return kErrBounds;
+    if (r.lengths[k] != 0 && vol > (int64_t)(0x3fffffffffffffffLL / r.lengths[k])) return kErrInvalid;
+    vol *= r.lengths[k];
+    strided |= r.strides[k] != 0;
+  }
+  if (r.flat_begin < 0 || r.flat_end < r.flat_begin) return kErrInvalid;
+  if (r.flat_end > vol) return kErrBounds;
+  if (strided) {
+    if (!(r.flat_begin == 0 && r.flat_end == vol)) return kErrInvalid;  // flat shards are packed
+    for (int k = 0; k < r.ndim; ++k)
+      if (r.lengths[k] > 1 && r.strides[k] == 0) return kErrInvalid;
+  }
+  return 0;
+}
+
+__device__ inline int local_shape(const bcp_shard_meta& r, int64_t* len) {
+  if (r.ndim == 0) {
+    len[0] = 1;
+    return 1;
+  }
+  for (int k = 0; k < r.ndim; ++k) len[k] = r.lengths[k];
+  return r.ndim;
+}
+
+__global__ __launch_bounds__(kBlock) void k_validate_count(const bcp_shard_meta* recs, int64_t n_saved,
+                                                           int64_t n_total, uint32_t* nboxes, Ctl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_total) return;
+  const bcp_shard_meta& r = recs[i];
+  const unsigned code = validate_record(r);
+  if (code) {
+    report(ctl, i, code);
+    nboxes[i] = 0;
+    return;
+  }
+  int64_t len[kDims];
+  const int n = local_shape(r, len);
+  const int nb = decompose_flat_range(len, n, r.flat_begin, r.flat_end, nullptr);
+  nboxes[i] = (uint32_t)nb;
+  if (i < n_saved && nb) atomicMax(&ctl->max_saved_fqn, (ull)r.fqn_id);
+}
+
+__global__ __launch_bounds__(kBlock) void k_emit_boxes(const bcp_shard_meta* recs, int64_t n_saved, int64_t n_total,
+                                                       const uint32_t* box_start, Box* boxes) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_total) return;
+  const uint32_t first = box_start[i];
+  const int nb = (int)(box_start[i + 1] - first);
+  if (nb == 0) return;
+  const bcp_shard_meta& r = recs[i];
+  int64_t len[kDims];
+  const int n = local_shape(r, len);
+  LocalBox lb[kMaxBoxesPerRecord];
+  decompose_flat_range(len, n, r.flat_begin, r.flat_end, lb);
+  bool strided = false;
+  for (int k = 0; k < r.ndim; ++k) strided |= r.strides[k] != 0;
+  for (int j = 0; j < nb; ++j) {
+    Box& b = boxes[first + j];
+    b.fqn = r.fqn_id;
+    b.rec = (int32_t)(i < n_saved ? i : i - n_saved);
+    b.ndim = n;
+    b.itemsize = r.itemsize;
+    b.buf = r.buf;
+    for (int k = 0; k < kDims; ++k) {
+      b.off[k] = (k < r.ndim ? r.offsets[k] : 0) + (k < n ? lb[j].off[k] : 0);
+      b.len[k] = k < n ? lb[j].len[k] : 1;
+      b.stride[k] = 0;
+    }
+    if (strided) {
+      for (int k = 0; k < n; ++k) b.stride[k] = r.strides[k];
+      b.byte_base = r.byte_offset;
+    } else {
+      int64_t s = 1;
+      for (int k = n - 1; k >= 0; --k) {
+        b.stride[k] = s;
+        s *= b.len[k];
+      }
+      b.byte_base = r.byte_offset + (int64_t)r.itemsize * (lb[j].flat_start - r.flat_begin);
+    }
+  }
+}
+
+// ---- step 2: stable LSD radix sort of (fqn, box index), 4 bits per pass ------------------------
+__global__ __launch_bounds__(kBlock) void k_sort_init(const Box* boxes, int64_t n, uint64_t* keys, uint32_t* idx) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  keys[i] = (uint64_t)boxes[i].fqn;
+  idx[i] = (uint32_t)i;
+}
+
+__global__ __launch_bounds__(kBlock) void k_radix_hist(const uint64_t* keys, int64_t n, int shift, uint32_t* hist,
+                                                       unsigned nblk) {
+  __shared__ uint32_t h[16];
+  if (threadIdx.x < 16) h[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) atomicAdd(&h[(keys[i] >> shift) & 15u], 1u);
+  __syncthreads();
+  if (threadIdx.x < 16) hist[threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+__global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint64_t* keys_in, const uint32_t* idx_in, int64_t n,
+                                                          int shift, const uint32_t* hist_scan, unsigned nblk,
+                                                          uint64_t* keys_out, uint32_t* idx_out) {
+  __shared__ uint32_t wc[kBlock / 64][16];
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool valid = i < n;
+  const uint64_t key = valid ? keys_in[i] : 0;
+  const unsigned d = valid ? (unsigned)((key >> shift) & 15u) : 16u;
+  const unsigned w = threadIdx.x >> 6;
+  const ull lt = (1ull << lane_id()) - 1ull;
+  uint32_t rank = 0;
+  for (unsigned b = 0; b < 16; ++b) {
+    const ull m = __ballot(d == b);
+    if (d == b) rank = (uint32_t)__popcll(m & lt);
+    if (lane_id() == 0) wc[w][b] = (uint32_t)__popcll(m);
+  }
+  __syncthreads();
+  if (valid) {
+    uint32_t base = hist_scan[d * nblk + blockIdx.x];
+    for (unsigned v = 0; v < w; ++v) base += wc[v][d];
+    keys_out[base + rank] = key;
+    idx_out[base + rank] = idx_in[i];
+  }
+}
+
+// ---- step 3: candidate pairs per target box -----------------------------------------------------
+__device__ inline int64_t lower_bound_u64(const uint64_t* a, int64_t n, uint64_t v) {
+  int64_t lo = 0, hi = n;
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (a[mid] < v) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+__device__ inline int64_t upper_bound_u64(const uint64_t* a, int64_t n, uint64_t v) {
+  int64_t lo = 0, hi = n;
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (a[mid] <= v) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ inline unsigned same_tensor(const bcp_shard_meta& a, const bcp_shard_meta& b) {
+  if (a.ndim != b.ndim) return kErrShape;
+  for (int k = 0; k < a.ndim; ++k)
+    if (a.global_shape[k] != b.global_shape[k]) return kErrShape;
+  if (a.itemsize != b.itemsize) return kErrDtype;
+  return 0;
+}
+
+__global__ __launch_bounds__(kBlock) void k_pair_count(const Box* boxes, int64_t nbs, int64_t nbt,
+                                                       const uint64_t* skeys, const uint32_t* sidx,
+                                                       const bcp_shard_meta* recs, int64_t n_saved,
+                                                       uint32_t* grp_lo, uint64_t* pair_cnt, Ctl* ctl) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t >= nbt) return;
+  const Box& tb = boxes[nbs + t];
+  const int64_t lo = lower_bound_u64(skeys, nbs, (uint64_t)tb.fqn);
+  const int64_t hi = upper_bound_u64(skeys, nbs, (uint64_t)tb.fqn);
+  grp_lo[t] = (uint32_t)lo;
+  pair_cnt[t] = (uint64_t)(hi - lo);
+  if (hi > lo) {
+    const Box& sb = boxes[sidx[lo]];
+    const unsigned code = same_tensor(recs[sb.rec], recs[n_saved + tb.rec]);
+    if (code) report(ctl, n_saved + tb.rec, code);
+  }
+}
+
+__device__ inline bool boxes_intersect(const Box& a, const Box& b) {
+  for (int k = 0; k < a.ndim; ++k) {
+    const int64_t lo = max(a.off[k], b.off[k]);
+    const int64_t hi = min(a.off[k] + a.len[k], b.off[k] + b.len[k]);
+    if (lo >= hi) return false;
+  }
+  return true;
+}
+
+// saved boxes of one FQN must agree on the tensor and be pairwise disjoint (one saver per element,
+// Sec. 4.1 "Balancing saving workload"): every sorted position checks itself against the rest of
+// its FQN's run.
+__global__ __launch_bounds__(kBlock) void k_saved_check(const Box* boxes, int64_t nbs, const uint64_t* skeys,
+                                                        const uint32_t* sidx, const bcp_shard_meta* recs,
+                                                        int check_overlap, Ctl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= nbs) return;
+  const Box& a = boxes[sidx[i]];
+  if (i + 1 < nbs && skeys[i + 1] == skeys[i]) {
+    const Box& nx = boxes[sidx[i + 1]];
+    const unsigned code = same_tensor(recs[a.rec], recs[nx.rec]);
+    if (code) {
+      report(ctl, nx.rec, code);
+      return;
+    }
+  }
+  if (!check_overlap) return;
+  for (int64_t j = i + 1; j < nbs && skeys[j] == skeys[i]; ++j) {
+    const Box& b = boxes[sidx[j]];
+    if (a.ndim == b.ndim && boxes_intersect(a, b)) {
+      report(ctl, max(a.rec, b.rec), kErrOverlap);
+      return;
+    }
+  }
+}
+
+// ---- steps 4+5: intersect, compact, normalise, tile --------------------------------------------
+__device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_bytes, Region* R, int64_t* volume) {
+  const int n = t.ndim;
+  if (s.ndim != n) return false;  // reported as a shape mismatch elsewhere
+  const int64_t e = t.itemsize;
+  int64_t L[kDims], ss[kDims], ds[kDims];
+  int m = 0;
+  int64_t soff = 0, doff = 0, vol = 1;
+  for (int k = 0; k < n; ++k) {
+    const int64_t lo = max(s.off[k], t.off[k]);
+    const int64_t hi = min(s.off[k] + s.len[k], t.off[k] + t.len[k]);
+    if (lo >= hi) return false;
+    soff += (lo - s.off[k]) * s.stride[k];
+    doff += (lo - t.off[k]) * t.stride[k];
+    const int64_t len = hi - lo;
+    vol *= len;
+    if (len == 1) continue;  // unit dimensions carry no stride
+    if (m > 0 && ss[m - 1] == len * s.stride[k] && ds[m - 1] == len * t.stride[k]) {
+      L[m - 1] *= len;  // contiguous with the previous dimension on both sides: merge
+      ss[m - 1] = s.stride[k];
+      ds[m - 1] = t.stride[k];
+    } else {
+      L[m] = len;
+      ss[m] = s.stride[k];
+      ds[m] = t.stride[k];
+      ++m;
+    }
+  }
+  if (!R) return true;
+  *volume = vol;
+  R->src_base = s.byte_base + soff * e;
+  R->dst_base = t.byte_base + doff * e;
+  R->src_buf = s.buf;
+  R->dst_buf = t.buf;
+  R->srec = s.rec;
+  R->trec = t.rec;
+  R->tile_bytes = tile_bytes;
+  R->rows_per_tile = 1;
+  R->segs_per_row = 1;
+  R->tdim = 0;
+  R->tiles_b = 0;
+  for (int k = 0; k < kDims; ++k) {
+    R->len[k] = 1;
+    R->spitch[k] = 0;
+    R->dpitch[k] = 0;
+  }
+  int a = -1, b = -1;
+  if (m > 0 && !(ss[m - 1] == 1 && ds[m - 1] == 1)) {
+    for (int k = 0; k < m; ++k) {
+      if (ss[k] == 1) a = k;
+      if (ds[k] == 1) b = k;
+    }
+  }
+  if (a >= 0 && b >= 0 && a != b && L[a] >= 4 && L[b] >= 4) {
+    // source-contiguous and destination-contiguous dimensions differ: LDS-staged transpose
+    R->kind = kTranspose;
+    R->run_bytes = e;
+    int nd = 0;
+    for (int k = 0; k < m; ++k) {
+      if (k == a || k == b) continue;
+      R->len[nd] = L[k];
+      R->spitch[nd] = ss[k] * e;
+      R->dpitch[nd] = ds[k] * e;
+      ++nd;
+    }
+    const int order[2] = {a, b};
+    for (int q = 0; q < 2; ++q) {
+      R->len[nd] = L[order[q]];
+      R->spitch[nd] = ss[order[q]] * e;
+      R->dpitch[nd] = ds[order[q]] * e;
+      ++nd;
+    }
+    R->ndim = nd;
+    const uint32_t td = e <= 4 ? 64u : 32u;
+    R->tdim = td;
+    const uint64_t ta = ((uint64_t)L[a] + td - 1) / td, tb = ((uint64_t)L[b] + td - 1) / td;
+    uint64_t groups = 1;
+    for (int k = 0; k < nd - 2; ++k) groups *= (uint64_t)R->len[k];
+    R->tiles_b = (uint32_t)min(tb, (uint64_t)0xffffffffu);
+    const uint64_t tpg = ta * tb;
+    R->tiles_per_group = (uint32_t)min(tpg, (uint64_t)0xffffffffu);
+    R->n_tiles = (tpg >> 32) ? ~0ull : groups * tpg;
+    return true;
+  }
+  R->kind = kRows;
+  int nd;
+  if (m > 0 && ss[m - 1] == 1 && ds[m - 1] == 1) {
+    R->run_bytes = L[m - 1] * e;
+    nd = m - 1;
+  } else {
+    R->run_bytes = e;
+    nd = m;
+  }
+  for (int k = 0; k < nd; ++k) {
+    R->len[k] = L[k];
+    R->spitch[k] = ss[k] * e;
+    R->dpitch[k] = ds[k] * e;
+  }
+  R->ndim = nd;
+  const uint64_t L0 = nd > 0 ? (uint64_t)L[nd - 1] : 1;
+  uint64_t groups = 1;
+  for (int k = 0; k < nd - 1; ++k) groups *= (uint64_t)L[k];
+  uint64_t tpg;
+  if ((uint64_t)R->run_bytes >= tile_bytes) {
+    const uint64_t segs = ((uint64_t)R->run_bytes + tile_bytes - 1) / tile_bytes;
+    R->segs_per_row = (uint32_t)min(segs, (uint64_t)0xffffffffu);
+    tpg = (segs >> 32) ? ~0ull : L0 * segs;
+  } else {
+    uint64_t rpt = tile_bytes / (uint64_t)R->run_bytes;
+    if (rpt > L0) rpt = L0;
+    R->rows_per_tile = (uint32_t)rpt;
+    tpg = (L0 + rpt - 1) / rpt;
+  }
+  R->tiles_per_group = (uint32_t)min(tpg, (uint64_t)0xffffffffu);
+  R->n_tiles = (tpg >> 32) ? ~0ull : groups * tpg;
+  return true;
+}
+
+// One thread per candidate pair.  WRITE == false: count the non-empty intersections per block.
+// WRITE == true: write them densely at blk_off[block] + rank inside the block (rank from wave
+// ballots and a popcount below the lane, then a prefix over the block's waves), so the region
+// list is ordered by (target box, saved box in FQN-sorted order) and reproducible.
+template <bool WRITE>
+__global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs, int64_t nbt, const uint32_t* sidx,
+                                                  const uint32_t* grp_lo, const uint64_t* pair_start, uint64_t n_pairs,
+                                                  uint32_t* blk_cnt, const uint32_t* blk_off, uint32_t tile_bytes,
+                                                  Region* regions, uint64_t* tile_cnt, ull* cov, Ctl* ctl) {
+  __shared__ uint32_t wcnt[kBlock / 64];
+  const uint64_t p = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  bool hit = false;
+  const Box* sb = nullptr;
+  const Box* tb = nullptr;
+  if (p < n_pairs) {
+    // target box whose pair range contains p: last t with pair_start[t] <= p
+    const int64_t t = upper_bound_u64(pair_start, nbt + 1, p) - 1;
+    const uint64_t k = p - pair_start[t];
+    tb = &boxes[nbs + t];
+    sb = &boxes[sidx[grp_lo[t] + k]];
+    hit = build_region(*sb, *tb, tile_bytes, nullptr, nullptr);
+  }
+  const ull m = __ballot(hit);
+  const unsigned w = threadIdx.x >> 6;
+  if (lane_id() == 0) wcnt[w] = (uint32_t)__popcll(m);
+  __syncthreads();
+  if (!WRITE) {
+    if (threadIdx.x == 0) {
+      uint32_t s = 0;
+      for (unsigned i = 0; i < kBlock / 64; ++i) s += wcnt[i];
+      blk_cnt[blockIdx.x] = s;
+    }
+    return;
+  }
+  if (!hit) return;
+  uint32_t pos = blk_off[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane_id()) - 1ull));
+  for (unsigned i = 0; i < w; ++i) pos += wcnt[i];
+  Region R;
+  int64_t vol = 0;
+  build_region(*sb, *tb, tile_bytes, &R, &vol);
+  regions[pos] = R;
+  tile_cnt[pos] = R.n_tiles;
+  atomicAdd(&cov[tb->rec], (ull)vol);
+  atomicAdd(&ctl->payload_bytes, (ull)vol * (ull)tb->itemsize);
+  atomicAdd(&ctl->dims_hist[R.ndim + (R.kind == kRows && R.run_bytes > tb->itemsize ? 1 : 0)], 1ull);
+  if (R.kind == kTranspose) atomicAdd(&ctl->n_transposed, 1ull);
+  atomicMax(&ctl->max_src_buf, (long long)R.src_buf);
+  atomicMax(&ctl->max_dst_buf, (long long)R.dst_buf);
+  if (R.n_tiles == ~0ull) report(ctl, 0, kErrInvalid);
+}
+
+__global__ __launch_bounds__(kBlock) void k_coverage(const bcp_shard_meta* recs, int64_t n_saved, int64_t n_target,
+                                                     const ull* cov, int allow_uncovered, Ctl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_target) return;
+  const bcp_shard_meta& r = recs[n_saved + i];
+  const ull want = (ull)(r.flat_end - r.flat_begin);
+  if (cov[i] > want) report(ctl, n_saved + i, kErrOverlap);
+  else if (cov[i] < want && !allow_uncovered) report(ctl, n_saved + i, kErrUncovered);
+}
+
+__global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_start, int64_t n_regions, uint64_t n_tiles,
+                                                       Tile* tiles) {
+  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_tiles) return;
+  const int64_t r = upper_bound_u64(tile_start, n_regions + 1, i) - 1;
+  tiles[i].region = (uint32_t)r;
+  tiles[i].local = (uint32_t)(i - tile_start[r]);
+}
+
+bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
+  if (ctl.err_key == ~0ull) return BCP_OK;
+  const unsigned code = (unsigned)(ctl.err_key & 0xff);
+  const int64_t rec = (int64_t)(ctl.err_key >> 8);
+  const bool is_saved = rec < n_saved;
+  const std::string who = std::string(is_saved ? "saved" : "target") + " record " +
+                          std::to_string(is_saved ? rec : rec - n_saved);
+  switch (code) {
+    case kErrInvalid: set_error(who + ": invalid field (ndim, itemsize, fqn_id, buf, offsets, flat range or strides)"); return BCP_ERR_INVALID_ARG;
+    case kErrTooManyDims: set_error(who + ": ndim exceeds BCP_MAX_DIMS"); return BCP_ERR_TOO_MANY_DIMS;
+    case kErrBounds: set_error(who + ": box or flat range outside the tensor"); return BCP_ERR_OUT_OF_BOUNDS;
+    case kErrShape: set_error(who + ": ndim / global shape differs from other records of its FQN"); return BCP_ERR_SHAPE_MISMATCH;
+    case kErrDtype: set_error(who + ": itemsize differs from other records of its FQN"); return BCP_ERR_DTYPE_MISMATCH;
+    case kErrOverlap: set_error(who + ": saved shards overlap (an element has two savers)"); return BCP_ERR_SAVED_OVERLAP;
+    case kErrUncovered: set_error(who + ": no saved shard holds some of its elements"); return BCP_ERR_UNCOVERED;
+  }
+  set_error("unknown device error");
+  return BCP_ERR_INVALID_ARG;
+}
+
+}  // namespace
+
+bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shard_meta* target,
+                       int64_t n_target, uint32_t flags, hipStream_t st, PlannerResult* out) {
+  Arena arena;
+  const int64_t n_total = n_saved + n_target;
+  const uint32_t tile_bytes = (uint32_t)config().tile_bytes;
+  out->dev = PlanDevice{};
+  out->n_saved_boxes = out->n_target_boxes = 0;
+  out->device_ms = 0.f;
+
+  Ctl init{};
+  init.err_key = ~0ull;
+  init.max_src_buf = init.max_dst_buf = -1;
+  out->ctl = init;
+  if (n_target == 0) return BCP_OK;
+  if (n_total >= (int64_t)1 << 31) {
+    set_error("too many records");
+    return BCP_ERR_INVALID_ARG;
+  }
+
+  hipEvent_t ev0, ev1;
+  BCP_HIP(hipEventCreate(&ev0));
+  BCP_HIP(hipEventCreate(&ev1));
+  struct EvGuard {
+    hipEvent_t a, b;
+    ~EvGuard() {
+      (void)hipEventDestroy(a);
+      (void)hipEventDestroy(b);
+    }
+  } evg{ev0, ev1};
+
+  bcp_shard_meta* recs = nullptr;
+  Ctl* ctl = nullptr;
+  uint32_t* box_start = nullptr;
+  BCP_HIP(arena.alloc(&recs, (size_t)n_total));
+  BCP_HIP(arena.alloc(&ctl, 1));
+  BCP_HIP(arena.alloc(&box_start, (size_t)n_total + 1));
+  if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, hipMemcpyHostToDevice, st));
+  BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, hipMemcpyHostToDevice, st));
+  BCP_HIP(hipMemcpyAsync(ctl, &init, sizeof(Ctl), hipMemcpyHostToDevice, st));
+  BCP_HIP(hipEventRecord(ev0, st));
+
+  // 1. validate + count boxes, scan
+  hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total)), dim3(kBlock), 0, st, recs, n_saved, n_total, box_start, ctl);
+  BCP_HIP(hipGetLastError());
+  if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, arena, st)) return s;
+  Ctl h{};
+  uint32_t nb_host[2] = {0, 0};
+  BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipMemcpyAsync(&nb_host[0], box_start + n_saved, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipMemcpyAsync(&nb_host[1], box_start + n_total, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipStreamSynchronize(st));
+  if (bcp_status s = device_error(h, n_saved)) return s;
+  const int64_t nbs = nb_host[0], nbt = (int64_t)nb_host[1] - nb_host[0], nbx = nb_host[1];
+  out->n_saved_boxes = nbs;
+  out->n_target_boxes = nbt;
+  if (nbt == 0) {
+    out->ctl = h;
+    return BCP_OK;
+  }
+
+  Box* boxes = nullptr;
+  BCP_HIP(arena.alloc(&boxes, (size_t)nbx));
+  hipLaunchKernelGGL(k_emit_boxes, dim3(blocks_for(n_total)), dim3(kBlock), 0, st, recs, n_saved, n_total, box_start, boxes);
+  BCP_HIP(hipGetLastError());
+
+  // 2. sort saved boxes by fqn
+  uint64_t *keys_a = nullptr, *keys_b = nullptr;
+  uint32_t *idx_a = nullptr, *idx_b = nullptr;
+  BCP_HIP(arena.alloc(&keys_a, (size_t)nbs));
+  BCP_HIP(arena.alloc(&keys_b, (size_t)nbs));
+  BCP_HIP(arena.alloc(&idx_a, (size_t)nbs));
+  BCP_HIP(arena.alloc(&idx_b, (size_t)nbs));
+  if (nbs > 0) {
+    const unsigned nblk = blocks_for(nbs);
+    hipLaunchKernelGGL(k_sort_init, dim3(nblk), dim3(kBlock), 0, st, boxes, nbs, keys_a, idx_a);
+    BCP_HIP(hipGetLastError());
+    int bits = 0;
+    while (bits < 64 && (h.max_saved_fqn >> bits) != 0) ++bits;
+    if (nbs > 1 && bits > 0) {
+      uint32_t* hist = nullptr;
+      BCP_HIP(arena.alloc(&hist, (size_t)16 * nblk + 1));
+      for (int shift = 0; shift < bits; shift += 4) {
+        hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(kBlock), 0, st, keys_a, nbs, shift, hist, nblk);
+        BCP_HIP(hipGetLastError());
+        if (bcp_status s = device_scan<uint32_t, uint32_t>(hist, hist, (int64_t)16 * nblk, arena, st)) return s;
+        hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(kBlock), 0, st, keys_a, idx_a, nbs, shift, hist, nblk, keys_b, idx_b);
+        BCP_HIP(hipGetLastError());
+        std::swap(keys_a, keys_b);
+        std::swap(idx_a, idx_b);
+      }
+    }
+  }
+
+  // 3. candidate pairs
+  uint32_t* grp_lo = nullptr;
+  uint64_t* pair_start = nullptr;
+  BCP_HIP(arena.alloc(&grp_lo, (size_t)nbt));
+  BCP_HIP(arena.alloc(&pair_start, (size_t)nbt + 1));
+  hipLaunchKernelGGL(k_pair_count, dim3(blocks_for(nbt)), dim3(kBlock), 0, st, boxes, nbs, nbt, keys_a, idx_a, recs, n_saved, grp_lo, pair_start, ctl);
+  BCP_HIP(hipGetLastError());
+  if (bcp_status s = device_scan<uint64_t, uint64_t>(pair_start, pair_start, nbt, arena, st)) return s;
+  if (nbs > 0) {
+    hipLaunchKernelGGL(k_saved_check, dim3(blocks_for(nbs)), dim3(kBlock), 0, st, boxes, nbs, keys_a, idx_a, recs,
+                       (flags & BCP_SKIP_OVERLAP_CHECK) ? 0 : 1, ctl);
+    BCP_HIP(hipGetLastError());
+  }
+  uint64_t n_pairs = 0;
+  BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipMemcpyAsync(&n_pairs, pair_start + nbt, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipStreamSynchronize(st));
+  if (bcp_status s = device_error(h, n_saved)) return s;
+  if (n_pairs >= (1ull << 40)) {
+    set_error("too many candidate pairs");
+    return BCP_ERR_OOM;
+  }
+
+  // 4. count, then write the non-empty intersections
+  ull* cov = nullptr;
+  BCP_HIP(arena.alloc(&cov, (size_t)n_target));
+  BCP_HIP(hipMemsetAsync(cov, 0, sizeof(ull) * (size_t)n_target, st));
+  uint32_t n_regions = 0;
+  Region* regions = nullptr;
+  uint64_t* tile_start = nullptr;
+  if (n_pairs > 0) {
+    const unsigned nblk = blocks_for((int64_t)n_pairs);
+    uint32_t* blk = nullptr;
+    BCP_HIP(arena.alloc(&blk, (size_t)nblk + 1));
+    hipLaunchKernelGGL((k_pairs<false>), dim3(nblk), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
+                       n_pairs, blk, blk, tile_bytes, (Region*)nullptr, (uint64_t*)nullptr, cov, ctl);
+    BCP_HIP(hipGetLastError());
+    if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk, arena, st)) return s;
+    BCP_HIP(hipMemcpyAsync(&n_regions, blk + nblk, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    BCP_HIP(hipStreamSynchronize(st));
+    BCP_HIP(arena.alloc(&regions, (size_t)n_regions));
+    BCP_HIP(arena.alloc(&tile_start, (size_t)n_regions + 1));
+    if (n_regions > 0) {
+      hipLaunchKernelGGL((k_pairs<true>), dim3(nblk), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
+                         n_pairs, blk, blk, tile_bytes, regions, tile_start, cov, ctl);
+      BCP_HIP(hipGetLastError());
+    }
+  } else {
+    BCP_HIP(arena.alloc(&tile_start, 1));
+  }
+  hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
+                     (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);
+  BCP_HIP(hipGetLastError());
+  if (bcp_status s = device_scan<uint64_t, uint64_t>(tile_start, tile_start, n_regions, arena, st)) return s;
+  uint64_t n_tiles = 0;
+  BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipMemcpyAsync(&n_tiles, tile_start + n_regions, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipStreamSynchronize(st));
+  if (bcp_status s = device_error(h, n_saved)) return s;
+  if (n_tiles >= 0xffffffffull) {
+    set_error("too many tiles; raise tile_bytes with bcp_configure");
+    return BCP_ERR_OOM;
+  }
+
+  // 5. tile table
+  Tile* tiles = nullptr;
+  BCP_HIP(arena.alloc(&tiles, (size_t)n_tiles));
+  if (n_tiles > 0) {
+    hipLaunchKernelGGL(k_fill_tiles, dim3(blocks_for((int64_t)n_tiles)), dim3(kBlock), 0, st, tile_start,
+                       (int64_t)n_regions, n_tiles, tiles);
+    BCP_HIP(hipGetLastError());
+  }
+  BCP_HIP(hipEventRecord(ev1, st));
+  BCP_HIP(hipStreamSynchronize(st));
+  BCP_HIP(hipEventElapsedTime(&out->device_ms, ev0, ev1));
+
+  h.n_pairs = n_pairs;
+  h.n_regions = n_regions;
+  h.n_tiles = n_tiles;
+  out->ctl = h;
+  out->dev.regions = regions;
+  out->dev.tiles = tiles;
+  out->dev.n_regions = n_regions;
+  out->dev.n_tiles = (int64_t)n_tiles;
+  if (regions) arena.release(regions);
+  arena.release(tiles);
+  return BCP_OK;
+}
+
+}  // namespace bcp

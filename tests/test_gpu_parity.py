@@ -1,0 +1,262 @@
+"""GPU parity: the HIP path (through the C-ABI) against the CPU oracle, byte for byte, on the
+same seeded inputs.  Sizes here are ones the oracle finishes in seconds while still spanning
+several tiles and ragged tails; full-size configurations live in test_gpu_full_size.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2407_20143_amd import binding, synth
+from paper_2407_20143_amd.synth import Case, Layout, Part, Shard, TensorSpec, regular
+
+pytestmark = pytest.mark.gpu
+
+POISON = 0xA5
+
+
+@pytest.fixture(autouse=True)
+def _default_config():
+    binding.configure(tile_bytes=65536, persistent=0, wg_per_cu=8)
+    yield
+    binding.configure(tile_bytes=65536, persistent=0, wg_per_cu=8)
+
+
+def gpu_reshard(case: Case, src_cpu, flags=0, dst_init=None):
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    p = binding.plan(sm, tm, flags=flags)
+    dsrc = [b.cuda() for b in src_cpu]
+    if dst_init is None:
+        ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    else:
+        ddst = [torch.as_tensor(b).cuda() for b in dst_init]
+    binding.reshard(p, dsrc, ddst)
+    torch.cuda.synchronize()
+    return [t.cpu().numpy() for t in ddst], p
+
+
+def assert_same(got, want, what):
+    assert len(got) == len(want)
+    for i, (g, w) in enumerate(zip(got, want)):
+        if not np.array_equal(g, w):
+            bad = np.flatnonzero(g != w)
+            raise AssertionError(f"{what}: buffer {i}: {bad.size} of {g.size} bytes differ, first at {bad[0]}")
+
+
+def check_case(case: Case, also_closed_form=True):
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    got, p = gpu_reshard(case, src)
+    assert_same(got, want, case.name + " vs oracle")
+    if also_closed_form:
+        exp = [b.numpy() for b in synth.materialize(case.target, case.tensors, case.seed, poison=POISON)]
+        assert_same(got, exp, case.name + " vs library slicing")
+    st = p.stats()
+    assert st["payload_bytes"] == case.target.payload_bytes()
+    p.destroy()
+    return st
+
+
+@pytest.mark.parametrize("modes", [("grid", "grid"), ("grid", "flat"), ("flat", "grid"), ("flat", "flat")])
+@pytest.mark.parametrize("seed", range(8))
+def test_random_layouts(seed, modes):
+    check_case(synth.random_case(100 + seed, n_tensors=8, max_elems=20000, saved_mode=modes[0], target_mode=modes[1]))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_strided(seed):
+    check_case(synth.random_case(200 + seed, n_tensors=6, max_elems=30000, p_strided=0.6, granules=(4, 8, 16)))
+
+
+@pytest.mark.parametrize("dtype", [torch.uint8, torch.bfloat16, torch.float32, torch.float64])
+@pytest.mark.parametrize("seed", range(3))
+def test_random_flat_single_dtype_odd_offsets(seed, dtype):
+    """ZeRO-like slices at byte offsets of every alignment class (granule 1 or 2 for small types)."""
+    check_case(synth.random_case(300 + seed, n_tensors=6, max_elems=50000, saved_mode="flat", target_mode="flat",
+                                 granules=(1, 2), dtype=dtype))
+
+
+def test_cfg1_small_and_strided():
+    st = check_case(synth.cfg1(256, 192))
+    assert st["n_pairs"] == 8 and st["n_regions"] == 8
+    st = check_case(synth.cfg1(256, 192, strided_target=True))
+    assert st["n_transposed"] == 8
+
+
+def test_cfg1_full_size():
+    st = check_case(synth.cfg1())
+    assert st["n_pairs"] == 8 and st["n_regions"] == 8 and st["payload_bytes"] == 4 << 20
+
+
+def test_cfg1_full_size_strided_target():
+    st = check_case(synth.cfg1(strided_target=True))
+    assert st["n_transposed"] == 8
+
+
+def test_cfg2_scaled():
+    st = check_case(synth.cfg2(layers=4, hidden=256, ffn=688, vocab=4000))
+    # per split tensor 4 saved x 2 target boxes -> 8 pairs, 4 regions; replicated: 1 x 2
+    n_split, n_rep = 2 + 4 * 7, 1 + 4 * 2
+    assert st["n_pairs"] == 8 * n_split + 2 * n_rep
+    assert st["n_regions"] == 4 * n_split + 2 * n_rep
+
+
+def test_cfg3_scaled_and_rank_share():
+    check_case(synth.cfg3(layers=4, hidden=256, ffn=688, vocab=4000))
+    check_case(synth.cfg3(layers=4, hidden=256, ffn=688, vocab=4000, rank_share=True))
+
+
+def test_cfg4_scaled_ragged():
+    # 16 -> 12 slices with a ragged tail, TP1 -> TP2; sizes chosen so slices cross tensor
+    # boundaries at element offsets of every residue modulo 4 elements
+    case = synth.cfg4(layers=3, hidden=136, ffn=344, vocab=1000, dp_s=16, dp_t=12)
+    n = sum(s.numel for s in case.saved.shards) // 3
+    assert n % 12 != 0
+    check_case(case)
+
+
+def test_cfg5_scaled():
+    check_case(synth.cfg5(layers=2, hidden=256, experts=16, ffn=88, n_small=3000))
+
+
+def test_round_trip_on_gpu():
+    case = synth.random_case(400, n_tensors=8, max_elems=20000, saved_mode="flat", target_mode="grid")
+    src = synth.materialize(case.saved, case.tensors, case.seed, poison=POISON)
+    mid, p1 = gpu_reshard(case, src)
+    back_case = Case("back", case.seed, case.tensors, case.target, case.saved)
+    back, p2 = gpu_reshard(back_case, [torch.from_numpy(m) for m in mid])
+    assert_same(back, [b.numpy() for b in src], "A->B->A")
+    p1.destroy()
+    p2.destroy()
+
+
+@pytest.mark.parametrize("tile_bytes,persistent,wg", [(4096, 0, 8), (16384, 1, 2), (65536, 1, 8), (1 << 20, 0, 8),
+                                                      (1 << 20, 1, 16)])
+def test_launch_configurations(tile_bytes, persistent, wg):
+    binding.configure(tile_bytes=tile_bytes, persistent=persistent, wg_per_cu=wg)
+    check_case(synth.cfg2(layers=2, hidden=512, ffn=1376, vocab=3000))
+    check_case(synth.random_case(500, n_tensors=8, max_elems=40000, saved_mode="flat", target_mode="grid", p_strided=0.3,
+                                 granules=(4, 16)))
+
+
+def test_plan_replay_on_other_buffers():
+    case = synth.cfg2(layers=2, hidden=128, ffn=344, vocab=1000)
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    p = binding.plan(sm, tm)
+    for seed in (1, 2, 3):
+        src = synth.materialize(case.saved, case.tensors, seed)
+        want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+        dsrc = [b.cuda() for b in src]
+        ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+        binding.reshard(p, dsrc, ddst)
+        torch.cuda.synchronize()
+        assert_same([t.cpu().numpy() for t in ddst], want, f"replay {seed}")
+    p.destroy()
+
+
+def test_reshard_on_side_stream():
+    case = synth.cfg1(512, 256)
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        got, p = gpu_reshard(case, src)
+    assert_same(got, want, "side stream")
+    p.destroy()
+
+
+# ---- edge cases ------------------------------------------------------------------------------------
+def test_empty_inputs():
+    p = binding.plan(np.zeros(0, dtype=binding.SHARD_META), np.zeros(0, dtype=binding.SHARD_META))
+    assert p.stats()["n_regions"] == 0
+    binding.reshard(p, [], [])
+    p.destroy()
+    # zero-volume shards on both sides and a scalar tensor
+    spec = {0: TensorSpec(0, "w", (6, 4), torch.float32, ("bits",)), 1: TensorSpec(1, "s", (), torch.float64, ("bits",))}
+    full = Part(0, (6, 4), (0, 0), (6, 4))
+    saved = Layout([regular(full, 4, 0, 0), regular(Part(0, (6, 4), (6, 0), (0, 4)), 4, 0, 96),
+                    regular(Part(1, (), (), ()), 8, 0, 96)], [104])
+    target = Layout([regular(Part(0, (6, 4), (0, 0), (6, 2)), 4, 0, 0), regular(Part(0, (6, 4), (0, 2), (6, 2)), 4, 0, 48),
+                     regular(Part(0, (6, 4), (3, 4), (2, 0)), 4, 0, 96), regular(Part(1, (), (), ()), 8, 0, 96)], [104])
+    check_case(Case("edge", 3, spec, saved, target))
+
+
+def test_unused_saved_tensor_is_ignored_and_uncovered_flag():
+    spec = {0: TensorSpec(0, "w", (8, 4), torch.float32, ("bits",)), 1: TensorSpec(1, "u", (5,), torch.float32, ("bits",))}
+    full = Part(0, (8, 4), (0, 0), (8, 4))
+    saved = Layout([regular(Part(0, (8, 4), (0, 0), (4, 4)), 4, 0, 0), regular(Part(1, (5,), (0,), (5,)), 4, 0, 64)], [84])
+    target = Layout([regular(full, 4, 0, 0)], [128])
+    case = Case("uncov", 4, spec, saved, target)
+    src = synth.materialize(saved, spec, 4)
+    with pytest.raises(binding.BcpError) as e:
+        gpu_reshard(case, src)
+    assert e.value.name == "BCP_ERR_UNCOVERED"
+    got, p = gpu_reshard(case, src, flags=binding.BCP_ALLOW_UNCOVERED)
+    want = oracle.reshard(saved, target, src, poison=POISON, allow_uncovered=True)
+    assert_same(got, want, "allow_uncovered")
+    p.destroy()
+
+
+def _plan_error(saved: Layout, target: Layout, mutate=None):
+    sm, tm = binding.layout_to_meta(saved), binding.layout_to_meta(target)
+    if mutate:
+        mutate(sm, tm)
+    with pytest.raises(binding.BcpError) as e:
+        binding.plan(sm, tm)
+    return e.value.name
+
+
+def test_error_statuses():
+    full = Part(0, (8, 4), (0, 0), (8, 4))
+    ok_s = Layout([regular(full, 4, 0, 0)], [128])
+    ok_t = Layout([regular(full, 4, 0, 0)], [128])
+    over = Layout([regular(Part(0, (8, 4), (0, 0), (5, 4)), 4, 0, 0), regular(Part(0, (8, 4), (4, 0), (4, 4)), 4, 1, 0)], [80, 64])
+    assert _plan_error(over, ok_t) == "BCP_ERR_SAVED_OVERLAP"
+    assert _plan_error(ok_s, Layout([regular(Part(0, (4, 8), (0, 0), (4, 8)), 4, 0, 0)], [128])) == "BCP_ERR_SHAPE_MISMATCH"
+    assert _plan_error(ok_s, Layout([regular(full, 2, 0, 0)], [64])) == "BCP_ERR_DTYPE_MISMATCH"
+
+    def oob(sm, tm):
+        tm["offsets"][0, 0] = 4
+    assert _plan_error(ok_s, ok_t, oob) == "BCP_ERR_OUT_OF_BOUNDS"
+
+    def dims(sm, tm):
+        tm["ndim"][0] = 9
+    assert _plan_error(ok_s, ok_t, dims) == "BCP_ERR_TOO_MANY_DIMS"
+
+    def item(sm, tm):
+        sm["itemsize"][0] = 3
+    assert _plan_error(ok_s, ok_t, item) == "BCP_ERR_INVALID_ARG"
+
+    def flat(sm, tm):
+        tm["flat_end"][0] = 33
+    assert _plan_error(ok_s, ok_t, flat) == "BCP_ERR_OUT_OF_BOUNDS"
+    # too few buffers at reshard time
+    p = binding.plan(binding.layout_to_meta(over.__class__([over.shards[0]], [80])),
+                     binding.layout_to_meta(Layout([regular(Part(0, (8, 4), (0, 0), (5, 4)), 4, 2, 0)], [0, 0, 80])))
+    with pytest.raises(binding.BcpError) as e:
+        binding.reshard(p, [torch.zeros(80, dtype=torch.uint8, device="cuda")],
+                        [torch.zeros(80, dtype=torch.uint8, device="cuda")])
+    assert e.value.name == "BCP_ERR_INVALID_ARG"
+    p.destroy()
+
+
+# ---- the region list: unpinned by design (many lists are valid), only its invariants ----------------
+def test_region_invariants():
+    case = synth.cfg4(layers=2, hidden=64, ffn=96, vocab=200, dp_s=16, dp_t=12, n_states=1)
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    p = binding.plan(sm, tm)
+    regs = p.regions()
+    st = p.stats()
+    assert len(regs) == st["n_regions"]
+    vol = np.array([int(r["run_bytes"]) * int(np.prod(r["len"][:r["ndim"]])) for r in regs])
+    assert vol.sum() == st["payload_bytes"] == case.target.payload_bytes()
+    # per target record the region bytes add up to the record's bytes
+    per = np.zeros(len(tm), dtype=np.int64)
+    np.add.at(per, regs["target_index"], vol)
+    assert np.array_equal(per, (tm["flat_end"] - tm["flat_begin"]) * tm["itemsize"])
+    # destination byte intervals of contiguous regions never overlap inside one buffer
+    for b in range(len(case.target.buf_bytes)):
+        iv = sorted((int(r["dst_base"]), int(r["dst_base"]) + int(r["run_bytes"])) for r in regs
+                    if r["dst_buf"] == b and r["ndim"] == 0)
+        for (a0, a1), (b0, _) in zip(iv[:-1], iv[1:]):
+            assert a1 <= b0
+    p.destroy()

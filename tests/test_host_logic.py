@@ -1,0 +1,178 @@
+"""CPU-only tests of the library's host side: the C-ABI exports every function include/bcp.h
+declares, the flat-slice helper (step a1) and the decomposer (step a2, same code the planner
+kernel runs) behave as Sec. 3.2 "Decomposing irregular tensors" says, and compute entry points
+fail loudly without a GPU.  No compute call is made here."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_20143_amd import binding, synth
+from paper_2407_20143_amd.binding import SHARD_META
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "bcp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bcp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert "bcp_plan" in names and "bcp_reshard" in names and len(names) >= 10
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in include/bcp.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_struct_layout_matches():
+    assert binding.lib().bcp_sizeof_shard_meta() == SHARD_META.itemsize == 304
+
+
+def rec(shape, flat_begin, flat_end, offsets=None, gshape=None, itemsize=4, byte_offset=0, buf=0, fqn=0):
+    r = np.zeros(1, dtype=SHARD_META)
+    n = len(shape)
+    r["fqn_id"], r["ndim"], r["itemsize"] = fqn, n, itemsize
+    r["lengths"][0, :n] = shape
+    r["offsets"][0, :n] = offsets if offsets is not None else [0] * n
+    r["global_shape"][0, :n] = gshape if gshape is not None else shape
+    r["flat_begin"], r["flat_end"], r["byte_offset"], r["buf"] = flat_begin, flat_end, byte_offset, buf
+    return r
+
+
+def boxes_of(r):
+    out = binding.decompose(r)
+    n = int(r["ndim"][0])
+    return [(tuple(int(v) for v in b["offsets"][:n]), tuple(int(v) for v in b["lengths"][:n]), int(b["byte_offset"]))
+            for b in out]
+
+
+def _parse_boxes(s):
+    out = []
+    for tok in s.split():
+        o, l = tok.split("+")
+        out.append((tuple(int(v) for v in o.strip("()").split(",")), tuple(int(v) for v in l.strip("()").split(","))))
+    return out
+
+
+def test_paper_example_decomposes_into_two_boxes(golden_irregular):
+    g = golden_irregular
+    b0 = boxes_of(rec((3, 2), 0, 3))
+    b1 = boxes_of(rec((3, 2), 3, 6))
+    assert len(b0) == int(g["B_rank0_box_count"])
+    assert [(o, l) for o, l, _ in b0] == _parse_boxes(g["B_rank0_boxes"])
+    assert [(o, l) for o, l, _ in b1] == _parse_boxes(g["B_rank1_boxes"])
+    assert [b for _, _, b in b0] == [0, 8]
+    assert [b for _, _, b in b1] == [0, 4]
+
+
+def test_flat_slice_helper_on_paper_example(golden_irregular):
+    cut = int(golden_irregular["flat_cut"])
+    params = np.concatenate([rec((2,), 0, 2, fqn=0), rec((3, 2), 0, 6, fqn=1), rec((2,), 0, 2, fqn=2)])
+    r0 = binding.meta_from_flat_slice(params, 0, cut, 0, 0)
+    r1 = binding.meta_from_flat_slice(params, cut, 10, 1, 0)
+    assert [(int(r["fqn_id"]), int(r["flat_begin"]), int(r["flat_end"]), int(r["byte_offset"])) for r in r0] == \
+        [(0, 0, 2, 0), (1, 0, 3, 8)]
+    assert [(int(r["fqn_id"]), int(r["flat_begin"]), int(r["flat_end"]), int(r["byte_offset"])) for r in r1] == \
+        [(1, 3, 6, 0), (2, 0, 2, 12)]
+    # empty slice, slice beyond the end
+    assert len(binding.meta_from_flat_slice(params, 4, 4, 0, 0)) == 0
+    with pytest.raises(binding.BcpError) as e:
+        binding.meta_from_flat_slice(params, 0, 11, 0, 0)
+    assert e.value.name == "BCP_ERR_OUT_OF_BOUNDS"
+
+
+def _check_decomposition(shape, a, b, offsets):
+    n = len(shape)
+    got = boxes_of(rec(shape, a, b, offsets=offsets, gshape=[s + o + 1 for s, o in zip(shape, offsets)],
+                       byte_offset=1000))
+    assert len(got) <= max(1, 2 * n - 1)
+    if a == b:
+        assert got == []
+        return
+    pos = a
+    for off, ln, byte in got:
+        assert all(l >= 1 for l in ln)
+        local = [o - oo for o, oo in zip(off, offsets)]
+        assert all(0 <= lo and lo + l <= s for lo, l, s in zip(local, ln, shape))
+        idx = np.ravel_multi_index(np.meshgrid(*[np.arange(lo, lo + l) for lo, l in zip(local, ln)], indexing="ij"),
+                                   shape).ravel()
+        # the box is one contiguous ascending run of flat positions, right after the previous box
+        assert np.array_equal(idx, np.arange(pos, pos + idx.size)), (shape, a, b, got)
+        assert byte == 1000 + 4 * (pos - a)
+        pos += idx.size
+    assert pos == b
+
+
+def test_decomposer_brute_force_small_shapes():
+    count = 0
+    for n in (1, 2, 3):
+        for shape in itertools.product(range(1, 5), repeat=n):
+            vol = int(np.prod(shape))
+            offsets = [(3 * k + 1) % 4 for k in range(n)]
+            for a in range(vol + 1):
+                for b in range(a, vol + 1):
+                    _check_decomposition(shape, a, b, offsets)
+                    count += 1
+    assert count > 10000
+
+
+def test_decomposer_random_high_rank():
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        n = int(rng.integers(4, 9))
+        shape = [int(v) for v in rng.integers(1, 4, size=n)]
+        vol = int(np.prod(shape))
+        a = int(rng.integers(0, vol + 1))
+        b = int(rng.integers(a, vol + 1))
+        _check_decomposition(shape, a, b, [int(v) for v in rng.integers(0, 3, size=n)])
+
+
+def test_decomposer_scalar_and_errors():
+    r = rec((), 0, 1)
+    assert len(binding.decompose(r)) == 1
+    with pytest.raises(binding.BcpError):
+        binding.decompose(rec((3, 2), 2, 7))
+    bad = rec((3, 2), 0, 6)
+    bad["ndim"] = 9
+    with pytest.raises(binding.BcpError) as e:
+        binding.decompose(bad)
+    assert e.value.name == "BCP_ERR_TOO_MANY_DIMS"
+
+
+def test_layout_to_meta_flat_case_counts():
+    """cfg4-shaped layout: every record of a slice stays inside one tensor; per slice the byte
+    offsets are a running sum; the element total is preserved."""
+    case = synth.cfg4(layers=2, hidden=24, ffn=40, vocab=52)
+    for lay in (case.saved, case.target):
+        meta = binding.layout_to_meta(lay)
+        assert int((meta["flat_end"] - meta["flat_begin"]).sum()) == sum(s.numel for s in lay.shards)
+        for b in range(len(lay.buf_bytes)):
+            m = meta[meta["buf"] == b]
+            off = 0
+            for r in m:
+                assert int(r["byte_offset"]) == off
+                off += int(r["flat_end"] - r["flat_begin"]) * int(r["itemsize"])
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="checks the no-GPU failure mode")
+def test_compute_calls_fail_loudly_without_a_gpu():
+    m = np.zeros(1, dtype=SHARD_META)
+    with pytest.raises(binding.BcpError) as e:
+        binding.plan(m, m, stream=0)
+    assert e.value.name == "BCP_ERR_NO_DEVICE"
+
+
+def test_configure_rejects_bad_values():
+    with pytest.raises(binding.BcpError):
+        binding.configure(tile_bytes=5000)
+    with pytest.raises(binding.BcpError):
+        binding.configure(wg_per_cu=1000)
+    binding.configure(tile_bytes=65536, persistent=0, wg_per_cu=8)
