@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the load-time reshard hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic checkpoint already resident in HBM:
+bcp_plan (decompose flat shards, intersect saved and target boxes, compact, tile) followed by
+bcp_reshard (the batched strided copy).  The default workload is the 7B-shaped decoder with bf16
+weights and three fp32 Adam states, saved TP4 PP2 and loaded TP2 PP4, all eight target ranks
+(94.3 GB read + 94.3 GB written per step).
+
+Prints ONE JSON line: whole-step throughput in GB/s (bytes read + bytes written), the copy
+kernel's HBM roofline figures measured with HIP events on the launch stream, and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
+
+
+def build_case(name: str):
+    from paper_2407_20143_amd import synth
+    if name == "cfg1":
+        return synth.cfg1(), "fp32 [1024,1024], 2 row shards -> 4 column shards (cache resident)"
+    if name == "cfg2":
+        return synth.cfg2(), "24-layer h2048 bf16 decoder, TP4PP2 -> TP2PP4, all target shards"
+    if name == "cfg3":
+        return synth.cfg3(), "7B decoder bf16 + 3 fp32 Adam states, TP4PP2 -> TP2PP4, all 8 target ranks"
+    if name == "cfg3_rank0":
+        return synth.cfg3(rank_share=True), "7B decoder bf16 + 3 fp32 Adam states, TP4PP2 -> TP2PP4, target rank (pp0,tp0)"
+    if name == "cfg4":
+        return synth.cfg4(), "7B fp32 optimizer states, ZeRO flat DP16 -> TP2 x DP12"
+    if name == "cfg4_1state":
+        return synth.cfg4(n_states=1), "7B fp32 optimizer state (one of three), ZeRO flat DP16 -> TP2 x DP12"
+    if name == "cfg5_experts":
+        return synth.cfg5(n_small=0), "MoE expert weights bf16, EP8TP2 -> EP4TP4"
+    if name == "cfg5_small":
+        return synth.cfg5(include_experts=False), "100k small fp32 tensors under random 1-D shardings"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(workload: str):
+    """The oracle, as it stands, on a bounded sample of the workload (host cores of this machine)."""
+    import torch
+    from oracle import oracle
+    from paper_2407_20143_amd import synth
+    if workload.startswith("cfg3"):
+        model = synth.llama_tensors(1, 4096, 11008, 32000)[1:10]  # the nine tensors of one decoder layer
+        states = synth.CFG3_STATES
+        case = synth.Case("sample", synth.BASE_SEED + 3, synth._specs(model, states),
+                          synth.megatron_layout(model, states, 1, 4, 1, replicate_norms=False),
+                          synth.megatron_layout(model, states, 1, 2, 1, replicate_norms=True))
+        what = "one decoder layer (9 tensors x 4 states, 2.83 GB one way) of the 7B workload, TP4 -> TP2"
+    elif workload.startswith("cfg4"):
+        case = synth.cfg4(layers=1, n_states=1)
+        what = "embedding + one decoder layer + lm_head of one fp32 state, ZeRO flat DP16 -> TP2 x DP12"
+    elif workload == "cfg2":
+        case = synth.cfg2(layers=4)
+        what = "4 of 24 layers plus embedding and lm_head of the cfg2 workload"
+    elif workload == "cfg5_experts":
+        case = synth.cfg5(layers=1, n_small=0)
+        what = "one of 16 MoE layers of expert weights"
+    elif workload == "cfg5_small":
+        case = synth.cfg5(include_experts=False, n_small=20000)
+        what = "20000 of the 100000 small tensors"
+    else:
+        case = synth.cfg1()
+        what = "the whole cfg1 workload"
+    dev = "cuda" if torch.cuda.is_available() else "cpu"
+    src = [b.cpu() for b in synth.materialize(case.saved, case.tensors, case.seed, device=dev)]
+    threads = min(os.cpu_count() or 1, 16)
+    t0 = time.perf_counter()
+    oracle.reshard(case.saved, case.target, src, threads=threads)
+    dt = time.perf_counter() - t0
+    payload = case.target.payload_bytes()
+    return {"value": round(2 * payload / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": what, "seconds": round(dt, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--tile-bytes", type=int, default=0)
+    ap.add_argument("--persistent", type=int, default=-1)
+    ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reshard-only", action="store_true",
+                    help="extra timing loop of bcp_reshard alone on a prebuilt plan (reported beside the step numbers)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the reshard path has no multi-GPU part (run with --gpus 1)")
+
+    import torch
+    from paper_2407_20143_amd import binding, synth
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    binding.lib()
+    binding.configure(tile_bytes=args.tile_bytes, persistent=args.persistent, wg_per_cu=args.wg_per_cu)
+
+    case, desc = build_case(args.workload)
+    t0 = time.perf_counter()
+    small = args.workload == "cfg5_small"
+    src = synth.materialize(case.saved, case.tensors, case.seed, device="cpu" if small else "cuda")
+    if small:
+        src = [b.cuda() for b in src]
+    dst = [torch.empty(n, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t0
+    saved_meta, target_meta = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    payload = case.target.payload_bytes()
+    stream = torch.cuda.current_stream()
+
+    def step():
+        p = binding.plan(saved_meta, target_meta, stream=stream)
+        binding.reshard(p, src, dst, stream=stream, check_sizes=False)
+        return p
+
+    # one checked pass first: buffer sizes against the plan's extents
+    p = binding.plan(saved_meta, target_meta, stream=stream)
+    binding.reshard(p, src, dst, stream=stream, check_sizes=True)
+    stats = p.stats()
+    assert stats["payload_bytes"] == payload
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        step().destroy()
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    plan_ms = []
+    plans = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        tp = time.perf_counter()
+        pl = binding.plan(saved_meta, target_meta, stream=stream)
+        plan_ms.append((time.perf_counter() - tp) * 1e3)
+        ev[i][0].record(stream)
+        binding.reshard(pl, src, dst, stream=stream, check_sizes=False)
+        ev[i][1].record(stream)
+        plans.append(pl)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    for pl in plans:
+        pl.destroy()
+    kern_ms = [a.elapsed_time(b) for a, b in ev]
+    ms_per_step = dt * 1e3 / args.steps
+    kern_avg = sum(kern_ms) / len(kern_ms)
+    value = 2 * payload / (ms_per_step * 1e-3) / 1e9
+    achieved = 2 * payload / (kern_avg * 1e-3) / 1e9
+
+    extra = {}
+    if args.reshard_only:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            binding.reshard(p, src, dst, stream=stream, check_sizes=False)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        extra["reshard_only_ms"] = round(e0.elapsed_time(e1) / args.steps, 4)
+
+    # practical ceiling: a plain streaming copy of the same launch shape, and the runtime's own D2D copy
+    n_copy = min(max(b.numel() for b in src), max(b.numel() for b in dst)) // 16 * 16
+    big_s = max(src, key=lambda b: b.numel())
+    big_d = max(dst, key=lambda b: b.numel())
+    ceil = {}
+    if n_copy >= 1 << 20:
+        for name, fn in (("copy_kernel", lambda: binding.copy_baseline(big_d, big_s, n_copy, stream=stream)),
+                         ("hipMemcpyDtoD", lambda: big_d[:n_copy].copy_(big_s[:n_copy]))):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(5):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ceil[name + "_GBps"] = round(2 * n_copy * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        ceil["copy_bytes"] = n_copy
+        # leave dst as a reshard produced it
+        binding.reshard(p, src, dst, stream=stream, check_sizes=False)
+        torch.cuda.synchronize()
+    p.destroy()
+
+    out = {
+        "metric": "reshard GB/s (read+written), plan + copy per step",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "payload_GB_one_way": round(payload / 1e9, 3),
+                   "tile_bytes": args.tile_bytes or "default", "persistent": args.persistent,
+                   "wg_per_cu": args.wg_per_cu or "default"},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "plan_build_ms": {"wall_avg": round(sum(plan_ms) / len(plan_ms), 4), "wall_min": round(min(plan_ms), 4),
+                          "device": round(stats["plan_device_ms"], 4)},
+        "reshard_kernel_ms": {"avg": round(kern_avg, 4), "min": round(min(kern_ms), 4), "max": round(max(kern_ms), 4)},
+        "plan": {k: stats[k] for k in ("n_saved_boxes", "n_target_boxes", "n_pairs", "n_regions", "n_tiles",
+                                       "n_transposed")},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "k_reshard", "bytes_per_launch": 2 * payload},
+        "ceiling": ceil,
+        "input_generation_s": round(t_gen, 1),
+    }
+    out.update(extra)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -109,8 +109,9 @@ def test_cfg4_scaled_ragged():
     # 16 -> 12 slices with a ragged tail, TP1 -> TP2; sizes chosen so slices cross tensor
     # boundaries at element offsets of every residue modulo 4 elements
     case = synth.cfg4(layers=3, hidden=136, ffn=344, vocab=1000, dp_s=16, dp_t=12)
-    n = sum(s.numel for s in case.saved.shards) // 3
-    assert n % 12 != 0
+    ns = sum(s.numel for s in case.saved.shards if s.group == 0)
+    nt = sum(s.numel for s in case.target.shards if s.group == 0)
+    assert ns % 16 != 0 and nt % 12 != 0
     check_case(case)
 
 
