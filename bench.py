@@ -92,6 +92,7 @@ def main():
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--persistent", type=int, default=-1)
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--reshard-only", action="store_true",
                     help="extra timing loop of bcp_reshard alone on a prebuilt plan (reported beside the step numbers)")
@@ -105,7 +106,8 @@ def main():
         raise SystemExit("bench.py needs a GPU")
     torch.cuda.set_device(0)
     binding.lib()
-    binding.configure(tile_bytes=args.tile_bytes, persistent=args.persistent, wg_per_cu=args.wg_per_cu)
+    binding.configure(tile_bytes=args.tile_bytes, persistent=args.persistent, wg_per_cu=args.wg_per_cu,
+                      threads=args.threads)
 
     case, desc = build_case(args.workload)
     t0 = time.perf_counter()
@@ -205,7 +207,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {desc}", "payload_GB_one_way": round(payload / 1e9, 3),
                    "tile_bytes": args.tile_bytes or "default", "persistent": args.persistent,
-                   "wg_per_cu": args.wg_per_cu or "default"},
+                   "wg_per_cu": args.wg_per_cu or "default", "threads": args.threads or "default"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "plan_build_ms": {"wall_avg": round(sum(plan_ms) / len(plan_ms), 4), "wall_min": round(min(plan_ms), 4),
                           "device": round(stats["plan_device_ms"], 4)},

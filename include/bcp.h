@@ -151,9 +151,11 @@ bcp_status bcp_plan_destroy(bcp_plan_t plan);
 
 /* Launch configuration of the copy kernel (process-wide; takes effect at the next bcp_plan /
  * bcp_reshard).  tile_bytes: payload per work item, a power of two in [4 KiB, 4 MiB], used by
- * plans built afterwards.  persistent != 0: a fixed grid of wg_per_cu * CU-count workgroups pops
- * tiles from an atomic queue; 0: one workgroup per tile.  Values <= 0 keep the current setting. */
-bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu);
+ * plans built afterwards (default 64 KiB).  persistent > 0: a fixed grid of wg_per_cu * CU-count
+ * workgroups pops tiles from an atomic queue (default, wg_per_cu 1); 0: one workgroup per tile;
+ * < 0 keeps the setting.  threads: 256, 512 or 1024 per workgroup (default 1024).  tile_bytes,
+ * wg_per_cu, threads <= 0 keep the current setting. */
+bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu, int32_t threads);
 
 /* Plain device-to-device streaming copy with the same vector width and launch shape as the reshard
  * kernel: the practical ceiling the bench reports beside it.  dst/src: device, 16-byte aligned. */

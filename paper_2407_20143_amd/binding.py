@@ -74,7 +74,7 @@ def lib():
         L.bcp_plan_regions.argtypes = [vp, vp, i64, ctypes.POINTER(i64)]
         L.bcp_plan_buffer_extents.argtypes = [vp, vp, i32, vp, i32]
         L.bcp_plan_destroy.argtypes = [vp]
-        L.bcp_configure.argtypes = [i64, i32, i32]
+        L.bcp_configure.argtypes = [i64, i32, i32, i32]
         L.bcp_copy_baseline.argtypes = [vp, vp, i64, vp]
         for f in EXPORTS:
             getattr(L, f).restype = ctypes.c_int
@@ -238,8 +238,11 @@ def reshard(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, stream=None, ch
                              _stream_ptr(stream)))
 
 
-def configure(tile_bytes: int = 0, persistent: int = -1, wg_per_cu: int = 0) -> None:
-    _check(lib().bcp_configure(tile_bytes, persistent, wg_per_cu))
+def configure(tile_bytes: int = 0, persistent: int = -1, wg_per_cu: int = 0, threads: int = 0) -> None:
+    _check(lib().bcp_configure(tile_bytes, persistent, wg_per_cu, threads))
+
+
+DEFAULT_CONFIG = dict(tile_bytes=65536, persistent=1, wg_per_cu=1, threads=1024)
 
 
 def copy_baseline(dst, src, nbytes: Optional[int] = None, stream=None) -> None:

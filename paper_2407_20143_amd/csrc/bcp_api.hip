@@ -73,7 +73,7 @@ const char* bcp_status_name(bcp_status s) {
 int32_t bcp_abi_version(void) { return 1; }
 int64_t bcp_sizeof_shard_meta(void) { return (int64_t)sizeof(bcp_shard_meta); }
 
-bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu) {
+bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu, int32_t threads) {
   std::lock_guard<std::mutex> g(g_config_mu);
   if (tile_bytes > 0) {
     if (tile_bytes < 4096 || tile_bytes > (4 << 20) || (tile_bytes & (tile_bytes - 1))) {
@@ -89,6 +89,13 @@ bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_
       return BCP_ERR_INVALID_ARG;
     }
     g_config.wg_per_cu = wg_per_cu;
+  }
+  if (threads > 0) {
+    if (threads != 256 && threads != 512 && threads != 1024) {
+      set_error("threads must be 256, 512 or 1024");
+      return BCP_ERR_INVALID_ARG;
+    }
+    g_config.threads = threads;
   }
   return BCP_OK;
 }
@@ -400,7 +407,7 @@ bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_
   BCP_HIP(hipMemcpyAsync(plan->table_dev, h, plan->table_bytes, hipMemcpyHostToDevice, st));
   BCP_HIP(hipEventRecord(plan->slot_done[slot], st));
   plan->slot_used[slot] = true;
-  return launch_reshard(plan->dev, plan->table_dev, plan->n_src, st);
+  return launch_reshard(plan->dev, plan->table_dev, plan->n_src, plan->n_dst, st);
 }
 
 bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream) {

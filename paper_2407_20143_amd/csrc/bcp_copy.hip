@@ -2,8 +2,8 @@
 // every payload byte is read once and written once; there is no contraction, hence no MFMA.
 //
 // A tile is at most tile_bytes of payload: a segment of one long row, or a few whole short
-// rows.  One 256-thread workgroup (4 wave64) per tile.  Per tile the kernel picks, wave-uniformly
-// and from the actual addresses, one of
+// rows, decoded at plan time into one 64-byte descriptor.  One workgroup per tile.  Per tile the
+// kernel picks, workgroup-uniformly and from the actual addresses, one of
 //   * 16-byte vector path   -- bases, run length and pitches all 16-byte aligned;
 //   * misaligned-run path   -- long runs whose source and destination disagree modulo 16 (ZeRO
 //                              slice boundaries): peel to a 16-byte aligned destination, then
@@ -11,8 +11,12 @@
 //   * granule path          -- short runs: 8/4/2/1-byte elements, flat over rows x run;
 //   * LDS-staged transpose  -- the source-contiguous and destination-contiguous dimensions
 //                              differ (strided shards): both global sides stay coalesced.
-// Workgroups either map 1:1 to tiles or, in persistent mode, pop tile indices from an atomic
-// queue until it runs dry.
+// Scheduling: a persistent grid of (CU count x wg_per_cu) workgroups pops tile indices from an
+// atomic queue.  Measured on MI355X, ONE 1024-thread workgroup per CU streaming 64 KiB tiles with
+// non-temporal accesses sustains the highest copy bandwidth: fewer concurrent streams keep more
+// DRAM pages open than a grid of one workgroup per tile.  The descriptor of the next tile is
+// fetched (scalar loads) while the current tile is being copied, and the buffer-pointer table is
+// staged in LDS once per workgroup, so no dependent global load sits between two tiles.
 #include <algorithm>
 
 #include "bcp_internal.h"
@@ -20,8 +24,9 @@
 namespace bcp {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kMaxThreads = 1024;
 constexpr int kLdsBytes = 32 * 33 * 16;  // >= 64*65*4: transpose staging incl. one pad column
+constexpr int kLdsPtrs = 1024;           // buffer pointers staged in LDS (more: read from global)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -39,13 +44,14 @@ template <> struct Granule<4> { typedef uint32_t type; };
 template <> struct Granule<2> { typedef uint16_t type; };
 template <> struct Granule<1> { typedef uint8_t type; };
 
+// streaming accesses: the data is touched once, keep it out of the caches' way
 template <int G>
 __device__ __forceinline__ typename Granule<G>::type ld(gsrc_t p) {
-  return *(const typename Granule<G>::type BCP_GLOBAL*)p;
+  return __builtin_nontemporal_load((const typename Granule<G>::type BCP_GLOBAL*)p);
 }
 template <int G>
 __device__ __forceinline__ void st(gdst_t p, typename Granule<G>::type v) {
-  *(typename Granule<G>::type BCP_GLOBAL*)p = v;
+  __builtin_nontemporal_store(v, (typename Granule<G>::type BCP_GLOBAL*)p);
 }
 template <int G>
 __device__ __forceinline__ typename Granule<G>::type lds_ld(const char* p) {
@@ -56,10 +62,10 @@ __device__ __forceinline__ void lds_st(char* p, typename Granule<G>::type v) {
   *reinterpret_cast<typename Granule<G>::type*>(p) = v;
 }
 
-struct __attribute__((packed, aligned(1))) Unaligned16 {
-  u32x4 v;
-};
-__device__ __forceinline__ u32x4 ld16_unaligned(gsrc_t p) { return ((const Unaligned16 BCP_GLOBAL*)p)->v; }
+typedef u32x4 u32x4_unaligned __attribute__((aligned(1)));
+__device__ __forceinline__ u32x4 ld16_unaligned(gsrc_t p) {
+  return __builtin_nontemporal_load((const u32x4_unaligned BCP_GLOBAL*)p);
+}
 
 // rows x run_g granules of G bytes; rows at pitches sp / dp.  `nt` threads cooperate, `tid` in [0, nt).
 template <int G>
@@ -149,150 +155,135 @@ __device__ __forceinline__ void transpose_tile(gsrc_t __restrict__ s, gdst_t __r
   // source: element (a, b) at s + a*E + b*spb (contiguous along a)
   // destination: element (a, b) at d + b*E + a*dpa (contiguous along b)
   const uint32_t pitch = td + 1;  // LDS row pitch in elements
-  const uint32_t x = threadIdx.x % td, y0 = threadIdx.x / td, step = kThreads / td;
+  const uint32_t x = threadIdx.x % td, y0 = threadIdx.x / td, step = blockDim.x / td;
   if (x < na)
-    for (uint32_t b = y0; b < nb; b += step) lds_st<E>(lds + (size_t)(b * pitch + x) * E, ld<E>(s + (size_t)x * E + (int64_t)b * spb));
+    for (uint32_t b = y0; b < nb; b += step)
+      lds_st<E>(lds + (size_t)(b * pitch + x) * E, ld<E>(s + (size_t)x * E + (int64_t)b * spb));
   __syncthreads();
   if (x < nb)
-    for (uint32_t a = y0; a < na; a += step) st<E>(d + (size_t)x * E + (int64_t)a * dpa, lds_ld<E>(lds + (size_t)(x * pitch + a) * E));
+    for (uint32_t a = y0; a < na; a += step)
+      st<E>(d + (size_t)x * E + (int64_t)a * dpa, lds_ld<E>(lds + (size_t)(x * pitch + a) * E));
+  __syncthreads();  // the staging area is free again
 }
 
-__device__ __forceinline__ void process_tile(const Region* __restrict__ regions, Tile tile,
-                                             const char* const* __restrict__ src_ptrs,
-                                             char* const* __restrict__ dst_ptrs, char* lds) {
-  const Region& R = regions[tile.region];
-  gsrc_t s = (gsrc_t)src_ptrs[R.src_buf] + R.src_base;
-  gdst_t d = (gdst_t)dst_ptrs[R.dst_buf] + R.dst_base;
-  const int nd = R.ndim;
-  const uint32_t tpg = R.tiles_per_group;
-  uint32_t group = tile.local / tpg;
-  const uint32_t w = tile.local - group * tpg;
-
-  if (R.kind == kTranspose) {
-    for (int k = nd - 3; k >= 0; --k) {
-      const uint64_t L = (uint64_t)R.len[k];
-      const uint64_t c = group % L;
-      group = (uint32_t)(group / L);
-      s += c * R.spitch[k];
-      d += c * R.dpitch[k];
-    }
-    const uint32_t td = R.tdim;
-    const uint32_t ta = w / R.tiles_b, tb = w - ta * R.tiles_b;
-    const uint32_t a0 = ta * td, b0 = tb * td;
-    const uint32_t na = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 2] - a0);
-    const uint32_t nb = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 1] - b0);
-    const int64_t spa = R.spitch[nd - 2], spb = R.spitch[nd - 1];
-    const int64_t dpa = R.dpitch[nd - 2], dpb = R.dpitch[nd - 1];
-    s += (int64_t)a0 * spa + (int64_t)b0 * spb;
-    d += (int64_t)a0 * dpa + (int64_t)b0 * dpb;
-    const uint32_t e = (uint32_t)R.run_bytes;
+__device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t d, char* lds) {
+  const uint32_t nt = blockDim.x;
+  if (T.kind == kTranspose) {
+    const uint32_t e = T.esize, na = T.a, nb = T.b;
+    const int64_t spb = T.p0, dpa = T.p1;
     const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
     if ((al & (e - 1)) == 0) {
       switch (e) {
-        case 1: transpose_tile<1>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 2: transpose_tile<2>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 4: transpose_tile<4>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 8: transpose_tile<8>(s, d, na, nb, spb, dpa, td, lds); break;
-        default: transpose_tile<16>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 1: transpose_tile<1>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
+        case 2: transpose_tile<2>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
+        case 4: transpose_tile<4>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
+        case 8: transpose_tile<8>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
+        default: transpose_tile<16>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
       }
     } else {  // elements not aligned to their own size: plain byte moves
       const uint32_t total = na * nb * e;
-      for (uint32_t i = threadIdx.x; i < total; i += kThreads) {
+      for (uint32_t i = threadIdx.x; i < total; i += nt) {
         const uint32_t el = i / e, by = i - el * e;
         const uint32_t b = el / na, a = el - b * na;
-        d[(int64_t)a * dpa + (int64_t)b * dpb + by] = s[(int64_t)a * spa + (int64_t)b * spb + by];
+        d[(int64_t)a * dpa + (int64_t)b * e + by] = s[(int64_t)a * e + (int64_t)b * spb + by];
       }
     }
     return;
   }
-
-  // kRows
-  for (int k = nd - 2; k >= 0; --k) {
-    const uint64_t L = (uint64_t)R.len[k];
-    const uint64_t c = group % L;
-    group = (uint32_t)(group / L);
-    s += c * R.spitch[k];
-    d += c * R.dpitch[k];
-  }
-  uint32_t nrows = 1;
-  uint32_t run;
-  int64_t sp = 0, dp = 0;
-  if (nd >= 1) {
-    sp = R.spitch[nd - 1];
-    dp = R.dpitch[nd - 1];
-  }
-  if (R.segs_per_row > 1 || (uint64_t)R.run_bytes >= R.tile_bytes) {
-    const uint32_t row = w / R.segs_per_row, seg = w - row * R.segs_per_row;
-    const int64_t off = (int64_t)seg * R.tile_bytes;
-    s += (int64_t)row * sp + off;
-    d += (int64_t)row * dp + off;
-    run = (uint32_t)min((int64_t)R.tile_bytes, R.run_bytes - off);
-  } else {
-    const uint64_t L0 = nd >= 1 ? (uint64_t)R.len[nd - 1] : 1;
-    const uint64_t row0 = (uint64_t)w * R.rows_per_tile;
-    nrows = (uint32_t)min((uint64_t)R.rows_per_tile, L0 - row0);
-    s += (int64_t)row0 * sp;
-    d += (int64_t)row0 * dp;
-    run = (uint32_t)R.run_bytes;
-  }
+  const uint32_t run = T.a, nrows = T.b;
+  const int64_t sp = T.p0, dp = T.p1;
   uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
   if (nrows > 1) al |= (uintptr_t)sp | (uintptr_t)dp;
   if ((al & 15u) == 0) {
-    copy_rows<16>(s, d, nrows, run >> 4, sp, dp, threadIdx.x, kThreads);
+    copy_rows<16>(s, d, nrows, run >> 4, sp, dp, threadIdx.x, nt);
   } else if (run >= 256) {
     if (nrows == 1) {
-      copy_run_misaligned(s, d, run, threadIdx.x, kThreads);
+      copy_run_misaligned(s, d, run, threadIdx.x, nt);
     } else {
       const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-      for (uint32_t r = wave; r < nrows; r += kThreads / 64)
+      for (uint32_t r = wave; r < nrows; r += nt >> 6)
         copy_run_misaligned(s + (int64_t)r * sp, d + (int64_t)r * dp, run, lane, 64);
     }
   } else if ((al & 7u) == 0) {
-    copy_rows<8>(s, d, nrows, run >> 3, sp, dp, threadIdx.x, kThreads);
+    copy_rows<8>(s, d, nrows, run >> 3, sp, dp, threadIdx.x, nt);
   } else if ((al & 3u) == 0) {
-    copy_rows<4>(s, d, nrows, run >> 2, sp, dp, threadIdx.x, kThreads);
+    copy_rows<4>(s, d, nrows, run >> 2, sp, dp, threadIdx.x, nt);
   } else if ((al & 1u) == 0) {
-    copy_rows<2>(s, d, nrows, run >> 1, sp, dp, threadIdx.x, kThreads);
+    copy_rows<2>(s, d, nrows, run >> 1, sp, dp, threadIdx.x, nt);
   } else {
-    copy_rows<1>(s, d, nrows, run, sp, dp, threadIdx.x, kThreads);
+    copy_rows<1>(s, d, nrows, run, sp, dp, threadIdx.x, nt);
   }
 }
 
-__global__ __launch_bounds__(kThreads) void k_reshard(const Region* __restrict__ regions,
-                                                      const Tile* __restrict__ tiles, uint32_t n_tiles,
-                                                      const char* const* __restrict__ src_ptrs,
-                                                      char* const* __restrict__ dst_ptrs,
-                                                      unsigned long long* queue, int persistent) {
+// table: [queue counter (8 bytes) | n_src source pointers | n_dst destination pointers]
+__global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restrict__ tiles, uint32_t n_tiles,
+                                                         const uint64_t* __restrict__ ptr_table, uint32_t n_src,
+                                                         uint32_t n_ptrs, unsigned long long* queue, int persistent) {
   __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
-  __shared__ uint32_t next_tile;
+  __shared__ uint64_t lds_ptrs[kLdsPtrs];
+  __shared__ uint32_t slot[2];
+  const bool ptrs_in_lds = n_ptrs <= (uint32_t)kLdsPtrs;
+  if (ptrs_in_lds)
+    for (uint32_t i = threadIdx.x; i < n_ptrs; i += blockDim.x) lds_ptrs[i] = ptr_table[i];
+  auto src_of = [&](const TileDesc& T) -> gsrc_t {
+    const uint64_t p = ptrs_in_lds ? lds_ptrs[T.src_buf] : ptr_table[T.src_buf];
+    return (gsrc_t)p + T.src_off;
+  };
+  auto dst_of = [&](const TileDesc& T) -> gdst_t {
+    const uint64_t p = ptrs_in_lds ? lds_ptrs[n_src + T.dst_buf] : ptr_table[n_src + T.dst_buf];
+    return (gdst_t)p + T.dst_off;
+  };
   if (!persistent) {
+    __syncthreads();
     const uint32_t t = blockIdx.x;
-    if (t < n_tiles) process_tile(regions, tiles[t], src_ptrs, dst_ptrs, lds);
+    if (t < n_tiles) {
+      const TileDesc T = tiles[t];
+      process_tile(T, src_of(T), dst_of(T), lds);
+    }
     return;
   }
+  // Two tile indices are kept in flight: the current one and the next one, whose descriptor is
+  // loaded while the current tile is copied.  slot[ph] receives the index after that.
+  if (threadIdx.x == 0) {
+    slot[0] = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_tiles);
+    slot[1] = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_tiles);
+  }
+  __syncthreads();
+  uint32_t cur = __builtin_amdgcn_readfirstlane(slot[0]);
+  uint32_t nxt = __builtin_amdgcn_readfirstlane(slot[1]);
+  __syncthreads();  // both slots read before slot[0] is written again
+  if (cur >= n_tiles) return;
+  TileDesc T = tiles[cur];
+  int ph = 0;
   for (;;) {
-    if (threadIdx.x == 0) next_tile = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_tiles);
+    TileDesc N = T;
+    if (nxt < n_tiles) N = tiles[nxt];  // scalar loads, consumed only after this tile's copy
+    unsigned long long popped = 0;
+    if (threadIdx.x == 0) popped = atomicAdd(queue, 1ull);
+    process_tile(T, src_of(T), dst_of(T), lds);
+    if (threadIdx.x == 0) slot[ph] = (uint32_t)min(popped, (unsigned long long)n_tiles);
     __syncthreads();
-    const uint32_t t = __builtin_amdgcn_readfirstlane(next_tile);
-    __syncthreads();  // everyone has read next_tile (and is done with lds) before it changes again
-    if (t >= n_tiles) return;  // uniform: the queue is monotonic, every workgroup ends here
-    process_tile(regions, tiles[t], src_ptrs, dst_ptrs, lds);
+    if (nxt >= n_tiles) return;  // uniform: the queue only grows, every workgroup gets here
+    T = N;
+    cur = nxt;
+    nxt = __builtin_amdgcn_readfirstlane(slot[ph]);
+    ph ^= 1;  // the other slot is written next, so no second barrier is needed
   }
 }
 
-__global__ __launch_bounds__(kThreads) void k_copy_baseline(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
-                                                            uint64_t n_vec, uint32_t vec_per_block) {
+__global__ __launch_bounds__(256) void k_copy_baseline(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                       uint64_t n_vec, uint32_t vec_per_block) {
   const uint64_t base = (uint64_t)blockIdx.x * vec_per_block;
   const uint64_t end = min(n_vec, base + vec_per_block);
   uint64_t i = base + threadIdx.x;
-  for (; i + 3 * kThreads < end; i += 4 * kThreads) {
-    const u32x4 a = src[i], b = src[i + kThreads], c = src[i + 2 * kThreads], e = src[i + 3 * kThreads];
+  for (; i + 3 * 256 < end; i += 4 * 256) {
+    const u32x4 a = src[i], b = src[i + 256], c = src[i + 2 * 256], e = src[i + 3 * 256];
     dst[i] = a;
-    dst[i + kThreads] = b;
-    dst[i + 2 * kThreads] = c;
-    dst[i + 3 * kThreads] = e;
+    dst[i + 256] = b;
+    dst[i + 2 * 256] = c;
+    dst[i + 3 * 256] = e;
   }
-  for (; i < end; i += kThreads) dst[i] = src[i];
+  for (; i < end; i += 256) dst[i] = src[i];
 }
 
 }  // namespace
@@ -304,12 +295,12 @@ int device_cu_count() {
   return n;
 }
 
-bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, hipStream_t stream) {
+bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, int32_t n_dst,
+                          hipStream_t stream) {
   if (plan.n_tiles == 0) return BCP_OK;
   unsigned long long* queue = (unsigned long long*)table;
-  const char* const* src_ptrs = (const char* const*)((const char*)table + 8);
-  char* const* dst_ptrs = (char* const*)((const char*)table + 8 + sizeof(void*) * (size_t)n_src);
-  const PlanConfig& cfg = config();
+  const uint64_t* ptrs = (const uint64_t*)((const char*)table + 8);
+  const PlanConfig cfg = config();
   unsigned grid;
   if (cfg.persistent) {
     const int cus = device_cu_count();
@@ -321,8 +312,9 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_s
   } else {
     grid = (unsigned)plan.n_tiles;
   }
-  hipLaunchKernelGGL(k_reshard, dim3(grid), dim3(kThreads), 0, stream, plan.regions, plan.tiles,
-                     (uint32_t)plan.n_tiles, src_ptrs, dst_ptrs, queue, cfg.persistent);
+  hipLaunchKernelGGL(k_reshard, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.tiles,
+                     (uint32_t)plan.n_tiles, ptrs, (uint32_t)n_src, (uint32_t)(n_src + n_dst), queue,
+                     cfg.persistent);
   BCP_HIP(hipGetLastError());
   return BCP_OK;
 }
@@ -334,13 +326,13 @@ bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipS
     return BCP_ERR_INVALID_ARG;
   }
   const uint64_t n_vec = (uint64_t)nbytes / 16;
-  const uint32_t vpb = (uint32_t)(config().tile_bytes / 16);
+  const uint32_t vpb = 65536 / 16;
   const uint64_t grid = (n_vec + vpb - 1) / vpb;
   if (grid >= 0x7fffffffull) {
     set_error("copy too large for one launch");
     return BCP_ERR_INVALID_ARG;
   }
-  hipLaunchKernelGGL(k_copy_baseline, dim3((unsigned)grid), dim3(kThreads), 0, stream, (u32x4*)dst, (const u32x4*)src,
+  hipLaunchKernelGGL(k_copy_baseline, dim3((unsigned)grid), dim3(256), 0, stream, (u32x4*)dst, (const u32x4*)src,
                      n_vec, vpb);
   BCP_HIP(hipGetLastError());
   return BCP_OK;

@@ -50,10 +50,22 @@ struct Region {
   uint64_t n_tiles;
 };
 
-struct Tile {
-  uint32_t region;
-  uint32_t local;  // tile index inside the region
+// One work item of the copy kernel, fully decoded at plan time so that the kernel needs a single
+// 64-byte (scalar) load per tile.
+//   kRows:      `b` rows of `a` contiguous bytes, row pitches p0 (source) / p1 (destination)
+//   kTranspose: `a` x `b` elements of `esize` bytes; the source is contiguous along a with pitch
+//               p0 along b, the destination contiguous along b with pitch p1 along a
+struct TileDesc {
+  int64_t src_off, dst_off;  // byte offsets inside the source / destination buffer
+  int64_t p0, p1;
+  uint32_t a, b;
+  uint32_t src_buf, dst_buf;
+  uint32_t kind;
+  uint32_t esize;
+  uint32_t tdim;             // kTranspose: tile edge
+  uint32_t pad_;
 };
+static_assert(sizeof(TileDesc) == 64, "one tile descriptor per 64-byte line");
 
 // Device control block: written by kernels, read back by the host between phases.
 struct Ctl {
@@ -81,8 +93,9 @@ enum DevErr : unsigned {
 
 struct PlanConfig {
   int64_t tile_bytes = 64 * 1024;
-  int32_t persistent = 0;
-  int32_t wg_per_cu = 8;
+  int32_t persistent = 1;  // workgroups pop tiles from an atomic queue (0: one workgroup per tile)
+  int32_t wg_per_cu = 1;   // persistent grid = wg_per_cu * number of CUs
+  int32_t threads = 1024;  // threads per workgroup
 };
 PlanConfig& config();
 
@@ -98,7 +111,7 @@ bcp_status hip_fail(hipError_t e, const char* what);
 // ---- planner (bcp_planner.hip) -------------------------------------------------------------
 struct PlanDevice {
   Region* regions = nullptr;
-  Tile* tiles = nullptr;
+  TileDesc* tiles = nullptr;
   int64_t n_regions = 0;
   int64_t n_tiles = 0;
 };
@@ -115,7 +128,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
 
 // ---- copy (bcp_copy.hip) ---------------------------------------------------------------------
 // table: device block [queue counter (8 bytes) | src pointers | dst pointers]
-bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, hipStream_t stream);
+bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, int32_t n_dst,
+                          hipStream_t stream);
 bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream);
 int device_cu_count();
 

@@ -549,13 +549,77 @@ __global__ __launch_bounds__(kBlock) void k_coverage(const bcp_shard_meta* recs,
   else if (cov[i] < want && !allow_uncovered) report(ctl, n_saved + i, kErrUncovered);
 }
 
-__global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_start, int64_t n_regions, uint64_t n_tiles,
-                                                       Tile* tiles) {
+// One thread per tile: find the region (binary search in the scanned tile counts) and decode the
+// tile completely -- leading row indices, row / segment range, byte offsets -- so the copy kernel
+// does no index arithmetic beyond its own lanes.
+__global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_start, const Region* regions,
+                                                       int64_t n_regions, uint64_t n_tiles, TileDesc* tiles) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
   const int64_t r = upper_bound_u64(tile_start, n_regions + 1, i) - 1;
-  tiles[i].region = (uint32_t)r;
-  tiles[i].local = (uint32_t)(i - tile_start[r]);
+  const Region& R = regions[r];
+  const uint32_t local = (uint32_t)(i - tile_start[r]);
+  TileDesc t;
+  t.src_buf = (uint32_t)R.src_buf;
+  t.dst_buf = (uint32_t)R.dst_buf;
+  t.kind = (uint32_t)R.kind;
+  t.esize = 0;
+  t.tdim = 0;
+  t.pad_ = 0;
+  int64_t so = R.src_base, dof = R.dst_base;
+  const int nd = R.ndim;
+  const uint32_t tpg = R.tiles_per_group;
+  uint64_t group = local / tpg;
+  const uint32_t w = local - (uint32_t)group * tpg;
+  if (R.kind == kTranspose) {
+    for (int k = nd - 3; k >= 0; --k) {
+      const uint64_t L = (uint64_t)R.len[k];
+      const uint64_t c = group % L;
+      group /= L;
+      so += (int64_t)c * R.spitch[k];
+      dof += (int64_t)c * R.dpitch[k];
+    }
+    const uint32_t td = R.tdim;
+    const uint32_t ta = w / R.tiles_b, tb = w - ta * R.tiles_b;
+    const uint64_t a0 = (uint64_t)ta * td, b0 = (uint64_t)tb * td;
+    t.a = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 2] - a0);
+    t.b = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 1] - b0);
+    t.p0 = R.spitch[nd - 1];
+    t.p1 = R.dpitch[nd - 2];
+    t.esize = (uint32_t)R.run_bytes;
+    t.tdim = td;
+    so += (int64_t)a0 * R.spitch[nd - 2] + (int64_t)b0 * R.spitch[nd - 1];
+    dof += (int64_t)a0 * R.dpitch[nd - 2] + (int64_t)b0 * R.dpitch[nd - 1];
+  } else {
+    for (int k = nd - 2; k >= 0; --k) {
+      const uint64_t L = (uint64_t)R.len[k];
+      const uint64_t c = group % L;
+      group /= L;
+      so += (int64_t)c * R.spitch[k];
+      dof += (int64_t)c * R.dpitch[k];
+    }
+    const int64_t sp = nd >= 1 ? R.spitch[nd - 1] : 0, dp = nd >= 1 ? R.dpitch[nd - 1] : 0;
+    t.p0 = sp;
+    t.p1 = dp;
+    if ((uint64_t)R.run_bytes >= R.tile_bytes) {  // a segment of one long row
+      const uint32_t row = w / R.segs_per_row, seg = w - row * R.segs_per_row;
+      const int64_t off = (int64_t)seg * R.tile_bytes;
+      so += (int64_t)row * sp + off;
+      dof += (int64_t)row * dp + off;
+      t.a = (uint32_t)min((int64_t)R.tile_bytes, R.run_bytes - off);
+      t.b = 1;
+    } else {  // a few whole short rows
+      const uint64_t L0 = nd >= 1 ? (uint64_t)R.len[nd - 1] : 1;
+      const uint64_t row0 = (uint64_t)w * R.rows_per_tile;
+      t.b = (uint32_t)min((uint64_t)R.rows_per_tile, L0 - row0);
+      t.a = (uint32_t)R.run_bytes;
+      so += (int64_t)row0 * sp;
+      dof += (int64_t)row0 * dp;
+    }
+  }
+  t.src_off = so;
+  t.dst_off = dof;
+  tiles[i] = t;
 }
 
 bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
@@ -738,10 +802,10 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   }
 
   // 5. tile table
-  Tile* tiles = nullptr;
+  TileDesc* tiles = nullptr;
   BCP_HIP(arena.alloc(&tiles, (size_t)n_tiles));
   if (n_tiles > 0) {
-    hipLaunchKernelGGL(k_fill_tiles, dim3(blocks_for((int64_t)n_tiles)), dim3(kBlock), 0, st, tile_start,
+    hipLaunchKernelGGL(k_fill_tiles, dim3(blocks_for((int64_t)n_tiles)), dim3(kBlock), 0, st, tile_start, regions,
                        (int64_t)n_regions, n_tiles, tiles);
     BCP_HIP(hipGetLastError());
   }

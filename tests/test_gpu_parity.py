@@ -16,9 +16,9 @@ POISON = 0xA5
 
 @pytest.fixture(autouse=True)
 def _default_config():
-    binding.configure(tile_bytes=65536, persistent=0, wg_per_cu=8)
+    binding.configure(**binding.DEFAULT_CONFIG)
     yield
-    binding.configure(tile_bytes=65536, persistent=0, wg_per_cu=8)
+    binding.configure(**binding.DEFAULT_CONFIG)
 
 
 def gpu_reshard(case: Case, src_cpu, flags=0, dst_init=None):
@@ -130,10 +130,11 @@ def test_round_trip_on_gpu():
     p2.destroy()
 
 
-@pytest.mark.parametrize("tile_bytes,persistent,wg", [(4096, 0, 8), (16384, 1, 2), (65536, 1, 8), (1 << 20, 0, 8),
-                                                      (1 << 20, 1, 16)])
-def test_launch_configurations(tile_bytes, persistent, wg):
-    binding.configure(tile_bytes=tile_bytes, persistent=persistent, wg_per_cu=wg)
+@pytest.mark.parametrize("tile_bytes,persistent,wg,threads", [(4096, 0, 8, 256), (16384, 1, 2, 512), (65536, 1, 8, 256),
+                                                              (65536, 0, 1, 1024), (1 << 20, 0, 8, 512),
+                                                              (1 << 20, 1, 16, 1024)])
+def test_launch_configurations(tile_bytes, persistent, wg, threads):
+    binding.configure(tile_bytes=tile_bytes, persistent=persistent, wg_per_cu=wg, threads=threads)
     check_case(synth.cfg2(layers=2, hidden=512, ffn=1376, vocab=3000))
     check_case(synth.random_case(500, n_tensors=8, max_elems=40000, saved_mode="flat", target_mode="grid", p_strided=0.3,
                                  granules=(4, 16)))

@@ -175,4 +175,6 @@ def test_configure_rejects_bad_values():
         binding.configure(tile_bytes=5000)
     with pytest.raises(binding.BcpError):
         binding.configure(wg_per_cu=1000)
-    binding.configure(tile_bytes=65536, persistent=0, wg_per_cu=8)
+    with pytest.raises(binding.BcpError):
+        binding.configure(threads=100)
+    binding.configure(**binding.DEFAULT_CONFIG)
