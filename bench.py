@@ -213,7 +213,7 @@ def main():
                           "device": round(stats["plan_device_ms"], 4)},
         "reshard_kernel_ms": {"avg": round(kern_avg, 4), "min": round(min(kern_ms), 4), "max": round(max(kern_ms), 4)},
         "plan": {k: stats[k] for k in ("n_saved_boxes", "n_target_boxes", "n_pairs", "n_regions", "n_tiles",
-                                       "n_transposed")},
+                                       "n_batches", "n_transposed")},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "kernel": "k_reshard", "bytes_per_launch": 2 * payload},

@@ -81,6 +81,7 @@ typedef struct bcp_stats {
   int64_t region_dims_hist[BCP_MAX_DIMS + 1]; /* regions by number of dims after coalescing */
   double plan_device_ms;   /* device time of the planner kernels (HIP events) */
   double plan_wall_ms;     /* wall time of bcp_plan */
+  int64_t n_batches;       /* queue items of the copy kernel: one big tile or a run of small ones */
 } bcp_stats;
 
 /* Region as the copy kernel sees it (for inspection and tests; many region lists are valid). */

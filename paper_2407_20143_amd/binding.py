@@ -26,7 +26,7 @@ STATS = np.dtype([
     ("n_saved_boxes", "<i8"), ("n_target_boxes", "<i8"), ("n_pairs", "<i8"), ("n_regions", "<i8"),
     ("n_tiles", "<i8"), ("payload_bytes", "<i8"), ("n_transposed", "<i8"), ("max_src_buf", "<i8"),
     ("max_dst_buf", "<i8"), ("region_dims_hist", "<i8", (MAX_DIMS + 1,)),
-    ("plan_device_ms", "<f8"), ("plan_wall_ms", "<f8"),
+    ("plan_device_ms", "<f8"), ("plan_wall_ms", "<f8"), ("n_batches", "<i8"),
 ], align=True)
 
 REGION_INFO = np.dtype([

@@ -264,6 +264,7 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     st.max_dst_buf = res.ctl.max_dst_buf;
     for (int k = 0; k <= BCP_MAX_DIMS; ++k) st.region_dims_hist[k] = (int64_t)res.ctl.dims_hist[k];
     st.plan_device_ms = res.device_ms;
+    st.n_batches = res.dev.n_batches;
     plan->n_src = (int32_t)(st.max_src_buf + 1);
     plan->n_dst = (int32_t)(st.max_dst_buf + 1);
     plan->table_bytes = 8 + sizeof(void*) * (size_t)(plan->n_src + plan->n_dst);
@@ -290,6 +291,7 @@ bcp_status bcp_plan_destroy(bcp_plan_t plan) {
   if (!plan) return BCP_OK;
   if (plan->dev.regions) (void)hipFree(plan->dev.regions);
   if (plan->dev.tiles) (void)hipFree(plan->dev.tiles);
+  if (plan->dev.heads) (void)hipFree(plan->dev.heads);
   if (plan->table_dev) (void)hipFree(plan->table_dev);
   if (plan->table_host) (void)hipHostFree(plan->table_host);
   for (int i = 0; i < kSlots; ++i)

@@ -11,12 +11,14 @@
 //   * granule path          -- short runs: 8/4/2/1-byte elements, flat over rows x run;
 //   * LDS-staged transpose  -- the source-contiguous and destination-contiguous dimensions
 //                              differ (strided shards): both global sides stay coalesced.
-// Scheduling: a persistent grid of (CU count x wg_per_cu) workgroups pops tile indices from an
-// atomic queue.  Measured on MI355X, ONE 1024-thread workgroup per CU streaming 64 KiB tiles with
-// non-temporal accesses sustains the highest copy bandwidth: fewer concurrent streams keep more
-// DRAM pages open than a grid of one workgroup per tile.  The descriptor of the next tile is
-// fetched (scalar loads) while the current tile is being copied, and the buffer-pointer table is
-// staged in LDS once per workgroup, so no dependent global load sits between two tiles.
+// Scheduling: a persistent grid of (CU count x wg_per_cu) workgroups pops batch indices from an
+// atomic queue; a batch is one big tile (whole workgroup) or a run of small tiles whose waves
+// each take tiles of their own, so 100k tiny tensors do not cost one queue pop each.  Measured on
+// MI355X, ONE 1024-thread workgroup per CU streaming 64 KiB tiles with non-temporal accesses
+// sustains the highest copy bandwidth: fewer concurrent streams keep more DRAM pages open than a
+// grid of one workgroup per tile.  The head descriptor of the next batch is fetched (scalar loads)
+// while the current batch is being copied, and the buffer-pointer table is staged in LDS once per
+// workgroup, so no dependent global load sits between two batches.
 #include <algorithm>
 
 #include "bcp_internal.h"
@@ -62,29 +64,38 @@ __device__ __forceinline__ void lds_st(char* p, typename Granule<G>::type v) {
   *reinterpret_cast<typename Granule<G>::type*>(p) = v;
 }
 
+
 typedef u32x4 u32x4_unaligned __attribute__((aligned(1)));
-__device__ __forceinline__ u32x4 ld16_unaligned(gsrc_t p) {
+template <> struct Granule<-16> { typedef u32x4 type; };
+template <>
+__device__ __forceinline__ u32x4 ld<-16>(gsrc_t p) {
   return __builtin_nontemporal_load((const u32x4_unaligned BCP_GLOBAL*)p);
 }
+template <>
+__device__ __forceinline__ void st<-16>(gdst_t p, u32x4 v) {
+  __builtin_nontemporal_store(v, (u32x4_unaligned BCP_GLOBAL*)p);
+}
 
-// rows x run_g granules of G bytes; rows at pitches sp / dp.  `nt` threads cooperate, `tid` in [0, nt).
-template <int G>
+// rows x run_g granules of |GG| bytes (GG == -16: 16-byte granules at unaligned addresses); rows at
+// pitches sp / dp.  `nt` threads cooperate, `tid` in [0, nt).
+template <int GG>
 __device__ __forceinline__ void copy_rows(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
                                           uint32_t run_g, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
-  typedef typename Granule<G>::type V;
+  constexpr int G = GG < 0 ? -GG : GG;
+  typedef typename Granule<GG>::type V;
   if (nrows == 1) {
     uint32_t i = tid;
     for (; i + 3 * nt < run_g; i += 4 * nt) {
-      const V a = ld<G>(s + (size_t)i * G);
-      const V b = ld<G>(s + (size_t)(i + nt) * G);
-      const V c = ld<G>(s + (size_t)(i + 2 * nt) * G);
-      const V e = ld<G>(s + (size_t)(i + 3 * nt) * G);
-      st<G>(d + (size_t)i * G, a);
-      st<G>(d + (size_t)(i + nt) * G, b);
-      st<G>(d + (size_t)(i + 2 * nt) * G, c);
-      st<G>(d + (size_t)(i + 3 * nt) * G, e);
+      const V a = ld<GG>(s + (size_t)i * G);
+      const V b = ld<GG>(s + (size_t)(i + nt) * G);
+      const V c = ld<GG>(s + (size_t)(i + 2 * nt) * G);
+      const V e = ld<GG>(s + (size_t)(i + 3 * nt) * G);
+      st<GG>(d + (size_t)i * G, a);
+      st<GG>(d + (size_t)(i + nt) * G, b);
+      st<GG>(d + (size_t)(i + 2 * nt) * G, c);
+      st<GG>(d + (size_t)(i + 3 * nt) * G, e);
     }
-    for (; i < run_g; i += nt) st<G>(d + (size_t)i * G, ld<G>(s + (size_t)i * G));
+    for (; i < run_g; i += nt) st<GG>(d + (size_t)i * G, ld<GG>(s + (size_t)i * G));
     return;
   }
   const uint32_t total = nrows * run_g;
@@ -107,12 +118,12 @@ __device__ __forceinline__ void copy_rows(gsrc_t __restrict__ s, gdst_t __restri
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = ld<G>(s + so[u]);
+    for (int u = 0; u < 4; ++u) v[u] = ld<GG>(s + so[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) st<G>(d + dof[u], v[u]);
+    for (int u = 0; u < 4; ++u) st<GG>(d + dof[u], v[u]);
   }
   for (; i < total; i += nt) {
-    st<G>(d + (int64_t)row * dp + (int64_t)col * G, ld<G>(s + (int64_t)row * sp + (int64_t)col * G));
+    st<GG>(d + (int64_t)row * dp + (int64_t)col * G, ld<GG>(s + (int64_t)row * sp + (int64_t)col * G));
     col += dcol;
     row += drow;
     if (col >= run_g) {
@@ -134,16 +145,16 @@ __device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_
   gdst_t d2 = d + head;
   uint32_t i = tid;
   for (; i + 3 * nt < body; i += 4 * nt) {
-    const u32x4 a = ld16_unaligned(s2 + (size_t)i * 16);
-    const u32x4 b = ld16_unaligned(s2 + (size_t)(i + nt) * 16);
-    const u32x4 c = ld16_unaligned(s2 + (size_t)(i + 2 * nt) * 16);
-    const u32x4 e = ld16_unaligned(s2 + (size_t)(i + 3 * nt) * 16);
+    const u32x4 a = ld<-16>(s2 + (size_t)i * 16);
+    const u32x4 b = ld<-16>(s2 + (size_t)(i + nt) * 16);
+    const u32x4 c = ld<-16>(s2 + (size_t)(i + 2 * nt) * 16);
+    const u32x4 e = ld<-16>(s2 + (size_t)(i + 3 * nt) * 16);
     st<16>(d2 + (size_t)i * 16, a);
     st<16>(d2 + (size_t)(i + nt) * 16, b);
     st<16>(d2 + (size_t)(i + 2 * nt) * 16, c);
     st<16>(d2 + (size_t)(i + 3 * nt) * 16, e);
   }
-  for (; i < body; i += nt) st<16>(d2 + (size_t)i * 16, ld16_unaligned(s2 + (size_t)i * 16));
+  for (; i < body; i += nt) st<16>(d2 + (size_t)i * 16, ld<-16>(s2 + (size_t)i * 16));
   const uint32_t done = head + (body << 4);
   const uint32_t tail = run - done;
   if (tid < tail) d[done + tid] = s[done + tid];
@@ -166,23 +177,42 @@ __device__ __forceinline__ void transpose_tile(gsrc_t __restrict__ s, gdst_t __r
   __syncthreads();  // the staging area is free again
 }
 
-__device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t d, char* lds) {
-  const uint32_t nt = blockDim.x;
-  if (T.kind == kTranspose) {
-    const uint32_t e = T.esize, na = T.a, nb = T.b;
+// rows of `run` bytes where 16-byte alignment does not hold everywhere: unaligned 16-byte vectors
+// over all rows at once, then the (run mod 16) tail bytes of every row.
+__device__ __forceinline__ void copy_rows_unaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
+                                                    uint32_t run, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
+  const uint32_t body = run >> 4, tail = run & 15u;
+  if (body) copy_rows<-16>(s, d, nrows, body, sp, dp, tid, nt);
+  if (tail) {
+    const uint32_t total = nrows * tail;
+    const size_t off = (size_t)body << 4;
+    for (uint32_t i = tid; i < total; i += nt) {
+      const uint32_t r = i / tail, b = i - r * tail;
+      d[(int64_t)r * dp + off + b] = s[(int64_t)r * sp + off + b];
+    }
+  }
+}
+
+// `nt` threads (tid in [0, nt)) copy one tile: the whole workgroup (WG == true, may use the LDS
+// staging area and barriers) or a single wave (WG == false, no barriers).
+template <bool WG>
+__device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t d, char* lds, uint32_t tid,
+                                             uint32_t nt) {
+  if ((T.kind & 0xffu) == kTranspose) {
+    const uint32_t e = (T.kind >> 8) & 0xffu, td = T.kind >> 16, na = T.a, nb = T.b;
     const int64_t spb = T.p0, dpa = T.p1;
     const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
-    if ((al & (e - 1)) == 0) {
+    if (WG && (al & (e - 1)) == 0) {
       switch (e) {
-        case 1: transpose_tile<1>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
-        case 2: transpose_tile<2>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
-        case 4: transpose_tile<4>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
-        case 8: transpose_tile<8>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
-        default: transpose_tile<16>(s, d, na, nb, spb, dpa, T.tdim, lds); break;
+        case 1: transpose_tile<1>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 2: transpose_tile<2>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 4: transpose_tile<4>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 8: transpose_tile<8>(s, d, na, nb, spb, dpa, td, lds); break;
+        default: transpose_tile<16>(s, d, na, nb, spb, dpa, td, lds); break;
       }
-    } else {  // elements not aligned to their own size: plain byte moves
+    } else {  // single wave, or elements not aligned to their own size: plain byte moves
       const uint32_t total = na * nb * e;
-      for (uint32_t i = threadIdx.x; i < total; i += nt) {
+      for (uint32_t i = tid; i < total; i += nt) {
         const uint32_t el = i / e, by = i - el * e;
         const uint32_t b = el / na, a = el - b * na;
         d[(int64_t)a * dpa + (int64_t)b * e + by] = s[(int64_t)a * e + (int64_t)b * spb + by];
@@ -195,28 +225,24 @@ __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t
   uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
   if (nrows > 1) al |= (uintptr_t)sp | (uintptr_t)dp;
   if ((al & 15u) == 0) {
-    copy_rows<16>(s, d, nrows, run >> 4, sp, dp, threadIdx.x, nt);
-  } else if (run >= 256) {
-    if (nrows == 1) {
-      copy_run_misaligned(s, d, run, threadIdx.x, nt);
-    } else {
-      const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-      for (uint32_t r = wave; r < nrows; r += nt >> 6)
-        copy_run_misaligned(s + (int64_t)r * sp, d + (int64_t)r * dp, run, lane, 64);
-    }
+    copy_rows<16>(s, d, nrows, run >> 4, sp, dp, tid, nt);
+  } else if (run >= 64) {
+    if (nrows == 1) copy_run_misaligned(s, d, run, tid, nt);
+    else copy_rows_unaligned(s, d, nrows, run, sp, dp, tid, nt);
   } else if ((al & 7u) == 0) {
-    copy_rows<8>(s, d, nrows, run >> 3, sp, dp, threadIdx.x, nt);
+    copy_rows<8>(s, d, nrows, run >> 3, sp, dp, tid, nt);
   } else if ((al & 3u) == 0) {
-    copy_rows<4>(s, d, nrows, run >> 2, sp, dp, threadIdx.x, nt);
+    copy_rows<4>(s, d, nrows, run >> 2, sp, dp, tid, nt);
   } else if ((al & 1u) == 0) {
-    copy_rows<2>(s, d, nrows, run >> 1, sp, dp, threadIdx.x, nt);
+    copy_rows<2>(s, d, nrows, run >> 1, sp, dp, tid, nt);
   } else {
-    copy_rows<1>(s, d, nrows, run, sp, dp, threadIdx.x, nt);
+    copy_rows<1>(s, d, nrows, run, sp, dp, tid, nt);
   }
 }
 
 // table: [queue counter (8 bytes) | n_src source pointers | n_dst destination pointers]
-__global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restrict__ tiles, uint32_t n_tiles,
+__global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restrict__ heads, uint32_t n_batches,
+                                                         const TileDesc* __restrict__ tiles,
                                                          const uint64_t* __restrict__ ptr_table, uint32_t n_src,
                                                          uint32_t n_ptrs, unsigned long long* queue, int persistent) {
   __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
@@ -233,38 +259,48 @@ __global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restr
     const uint64_t p = ptrs_in_lds ? lds_ptrs[n_src + T.dst_buf] : ptr_table[n_src + T.dst_buf];
     return (gdst_t)p + T.dst_off;
   };
+  // one batch: a single tile for the whole workgroup, or several small tiles dealt to the waves
+  auto run_batch = [&](const TileDesc& H) {
+    if (H.count == 1) {
+      process_tile<true>(H, src_of(H), dst_of(H), lds, threadIdx.x, blockDim.x);
+    } else {
+      const uint32_t wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6, lane = threadIdx.x & 63u;
+      for (uint32_t j = wave; j < H.count; j += n_waves) {
+        const uint32_t t = __builtin_amdgcn_readfirstlane(H.first + j);
+        const TileDesc T = tiles[t];
+        process_tile<false>(T, src_of(T), dst_of(T), lds, lane, 64);
+      }
+    }
+  };
   if (!persistent) {
     __syncthreads();
-    const uint32_t t = blockIdx.x;
-    if (t < n_tiles) {
-      const TileDesc T = tiles[t];
-      process_tile(T, src_of(T), dst_of(T), lds);
-    }
+    const uint32_t b = blockIdx.x;
+    if (b < n_batches) run_batch(heads[b]);
     return;
   }
-  // Two tile indices are kept in flight: the current one and the next one, whose descriptor is
-  // loaded while the current tile is copied.  slot[ph] receives the index after that.
+  // Two batch indices are kept in flight: the current one and the next one, whose head descriptor
+  // is loaded while the current batch is copied.  slot[ph] receives the index after that.
   if (threadIdx.x == 0) {
-    slot[0] = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_tiles);
-    slot[1] = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_tiles);
+    slot[0] = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_batches);
+    slot[1] = (uint32_t)min(atomicAdd(queue, 1ull), (unsigned long long)n_batches);
   }
   __syncthreads();
   uint32_t cur = __builtin_amdgcn_readfirstlane(slot[0]);
   uint32_t nxt = __builtin_amdgcn_readfirstlane(slot[1]);
   __syncthreads();  // both slots read before slot[0] is written again
-  if (cur >= n_tiles) return;
-  TileDesc T = tiles[cur];
+  if (cur >= n_batches) return;
+  TileDesc H = heads[cur];
   int ph = 0;
   for (;;) {
-    TileDesc N = T;
-    if (nxt < n_tiles) N = tiles[nxt];  // scalar loads, consumed only after this tile's copy
+    TileDesc N = H;
+    if (nxt < n_batches) N = heads[nxt];  // scalar loads, consumed only after this batch's copy
     unsigned long long popped = 0;
     if (threadIdx.x == 0) popped = atomicAdd(queue, 1ull);
-    process_tile(T, src_of(T), dst_of(T), lds);
-    if (threadIdx.x == 0) slot[ph] = (uint32_t)min(popped, (unsigned long long)n_tiles);
+    run_batch(H);
+    if (threadIdx.x == 0) slot[ph] = (uint32_t)min(popped, (unsigned long long)n_batches);
     __syncthreads();
-    if (nxt >= n_tiles) return;  // uniform: the queue only grows, every workgroup gets here
-    T = N;
+    if (nxt >= n_batches) return;  // uniform: the queue only grows, every workgroup gets here
+    H = N;
     cur = nxt;
     nxt = __builtin_amdgcn_readfirstlane(slot[ph]);
     ph ^= 1;  // the other slot is written next, so no second barrier is needed
@@ -297,7 +333,7 @@ int device_cu_count() {
 
 bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, int32_t n_dst,
                           hipStream_t stream) {
-  if (plan.n_tiles == 0) return BCP_OK;
+  if (plan.n_batches == 0) return BCP_OK;
   unsigned long long* queue = (unsigned long long*)table;
   const uint64_t* ptrs = (const uint64_t*)((const char*)table + 8);
   const PlanConfig cfg = config();
@@ -308,12 +344,12 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_s
       set_error("cannot read the CU count");
       return BCP_ERR_NO_DEVICE;
     }
-    grid = (unsigned)std::min<int64_t>(plan.n_tiles, (int64_t)cus * cfg.wg_per_cu);
+    grid = (unsigned)std::min<int64_t>(plan.n_batches, (int64_t)cus * cfg.wg_per_cu);
   } else {
-    grid = (unsigned)plan.n_tiles;
+    grid = (unsigned)plan.n_batches;
   }
-  hipLaunchKernelGGL(k_reshard, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.tiles,
-                     (uint32_t)plan.n_tiles, ptrs, (uint32_t)n_src, (uint32_t)(n_src + n_dst), queue,
+  hipLaunchKernelGGL(k_reshard, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.heads,
+                     (uint32_t)plan.n_batches, plan.tiles, ptrs, (uint32_t)n_src, (uint32_t)(n_src + n_dst), queue,
                      cfg.persistent);
   BCP_HIP(hipGetLastError());
   return BCP_OK;

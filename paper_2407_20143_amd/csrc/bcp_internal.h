@@ -55,17 +55,25 @@ struct Region {
 //   kRows:      `b` rows of `a` contiguous bytes, row pitches p0 (source) / p1 (destination)
 //   kTranspose: `a` x `b` elements of `esize` bytes; the source is contiguous along a with pitch
 //               p0 along b, the destination contiguous along b with pitch p1 along a
+//
+// The queue of the copy kernel hands out BATCHES: one big tile, or a run of consecutive small
+// tiles (each below kSmallTileBytes, together about one tile budget) that the waves of a
+// workgroup share.  `heads[batch]` is a copy of the batch's first tile descriptor with `first`
+// and `count` filled in, so the kernel still needs one descriptor load per queue pop.
 struct TileDesc {
   int64_t src_off, dst_off;  // byte offsets inside the source / destination buffer
   int64_t p0, p1;
   uint32_t a, b;
   uint32_t src_buf, dst_buf;
-  uint32_t kind;
-  uint32_t esize;
-  uint32_t tdim;             // kTranspose: tile edge
+  uint32_t kind;             // RegionKind | esize << 8 | tile edge (kTranspose) << 16
+  uint32_t first;            // heads[] only: index of the batch's first tile
+  uint32_t count;            // heads[] only: tiles in the batch
   uint32_t pad_;
 };
 static_assert(sizeof(TileDesc) == 64, "one tile descriptor per 64-byte line");
+
+constexpr uint32_t kSmallTileBytes = 16 * 1024;  // tiles below this may share a batch
+constexpr uint32_t kMinBatchWeight = 256;        // a tile counts at least this much: <= budget/256 tiles per batch
 
 // Device control block: written by kernels, read back by the host between phases.
 struct Ctl {
@@ -112,8 +120,10 @@ bcp_status hip_fail(hipError_t e, const char* what);
 struct PlanDevice {
   Region* regions = nullptr;
   TileDesc* tiles = nullptr;
+  TileDesc* heads = nullptr;  // one per batch
   int64_t n_regions = 0;
   int64_t n_tiles = 0;
+  int64_t n_batches = 0;
 };
 
 struct PlannerResult {

@@ -552,8 +552,11 @@ __global__ __launch_bounds__(kBlock) void k_coverage(const bcp_shard_meta* recs,
 // One thread per tile: find the region (binary search in the scanned tile counts) and decode the
 // tile completely -- leading row indices, row / segment range, byte offsets -- so the copy kernel
 // does no index arithmetic beyond its own lanes.
+// weight[i]: what the tile counts towards a batch budget (0 for big tiles, which are batches of
+// their own).
 __global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_start, const Region* regions,
-                                                       int64_t n_regions, uint64_t n_tiles, TileDesc* tiles) {
+                                                       int64_t n_regions, uint64_t n_tiles, TileDesc* tiles,
+                                                       uint64_t* weight) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
   const int64_t r = upper_bound_u64(tile_start, n_regions + 1, i) - 1;
@@ -563,9 +566,10 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_star
   t.src_buf = (uint32_t)R.src_buf;
   t.dst_buf = (uint32_t)R.dst_buf;
   t.kind = (uint32_t)R.kind;
-  t.esize = 0;
-  t.tdim = 0;
+  t.first = (uint32_t)i;
+  t.count = 1;
   t.pad_ = 0;
+  uint64_t bytes;
   int64_t so = R.src_base, dof = R.dst_base;
   const int nd = R.ndim;
   const uint32_t tpg = R.tiles_per_group;
@@ -586,8 +590,8 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_star
     t.b = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 1] - b0);
     t.p0 = R.spitch[nd - 1];
     t.p1 = R.dpitch[nd - 2];
-    t.esize = (uint32_t)R.run_bytes;
-    t.tdim = td;
+    t.kind |= ((uint32_t)R.run_bytes << 8) | (td << 16);
+    bytes = (uint64_t)t.a * t.b * (uint64_t)R.run_bytes;
     so += (int64_t)a0 * R.spitch[nd - 2] + (int64_t)b0 * R.spitch[nd - 1];
     dof += (int64_t)a0 * R.dpitch[nd - 2] + (int64_t)b0 * R.dpitch[nd - 1];
   } else {
@@ -616,10 +620,44 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_star
       so += (int64_t)row0 * sp;
       dof += (int64_t)row0 * dp;
     }
+    bytes = (uint64_t)t.a * t.b;
   }
   t.src_off = so;
   t.dst_off = dof;
   tiles[i] = t;
+  weight[i] = bytes >= kSmallTileBytes ? 0 : max(bytes, (uint64_t)kMinBatchWeight);
+}
+
+// A batch starts at tile i when i is big, follows a big tile, or the running weight of the small
+// tiles crosses a multiple of the batch budget.  wprefix: exclusive scan of weight.
+__global__ __launch_bounds__(kBlock) void k_batch_flags(const uint64_t* weight, const uint64_t* wprefix,
+                                                        uint64_t n_tiles, uint32_t budget, uint32_t* flags) {
+  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_tiles) return;
+  uint32_t f = 1;
+  if (i > 0 && weight[i] != 0 && weight[i - 1] != 0) f = (wprefix[i] / budget) != (wprefix[i - 1] / budget);
+  flags[i] = f;
+}
+
+// batch_id: exclusive scan of flags (so a start tile's batch is batch_id[i]); bstart[b] = first tile.
+__global__ __launch_bounds__(kBlock) void k_batch_starts(const uint32_t* batch_id, uint64_t n_tiles, uint32_t* bstart) {
+  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i > n_tiles) return;
+  if (i == n_tiles) {
+    bstart[batch_id[n_tiles]] = (uint32_t)n_tiles;  // sentinel after the last batch
+    return;
+  }
+  if (batch_id[i + 1] != batch_id[i]) bstart[batch_id[i]] = (uint32_t)i;
+}
+
+__global__ __launch_bounds__(kBlock) void k_batch_heads(const TileDesc* tiles, const uint32_t* bstart,
+                                                        uint32_t n_batches, TileDesc* heads) {
+  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
+  if (b >= n_batches) return;
+  TileDesc t = tiles[bstart[b]];
+  t.first = bstart[b];
+  t.count = bstart[b + 1] - bstart[b];
+  heads[b] = t;
 }
 
 bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
@@ -801,12 +839,34 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     return BCP_ERR_OOM;
   }
 
-  // 5. tile table
+  // 5. tile table, then batches: big tiles alone, runs of small tiles together
   TileDesc* tiles = nullptr;
+  TileDesc* heads = nullptr;
+  uint32_t n_batches = 0;
   BCP_HIP(arena.alloc(&tiles, (size_t)n_tiles));
+  BCP_HIP(arena.alloc(&heads, (size_t)n_tiles));
   if (n_tiles > 0) {
-    hipLaunchKernelGGL(k_fill_tiles, dim3(blocks_for((int64_t)n_tiles)), dim3(kBlock), 0, st, tile_start, regions,
-                       (int64_t)n_regions, n_tiles, tiles);
+    uint64_t* weight = nullptr;
+    uint64_t* wprefix = nullptr;
+    uint32_t* flags = nullptr;
+    uint32_t* bstart = nullptr;
+    BCP_HIP(arena.alloc(&weight, (size_t)n_tiles));
+    BCP_HIP(arena.alloc(&wprefix, (size_t)n_tiles + 1));
+    BCP_HIP(arena.alloc(&flags, (size_t)n_tiles + 1));
+    BCP_HIP(arena.alloc(&bstart, (size_t)n_tiles + 1));
+    const unsigned nblk = blocks_for((int64_t)n_tiles + 1);
+    hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, tile_start, regions, (int64_t)n_regions,
+                       n_tiles, tiles, weight);
+    BCP_HIP(hipGetLastError());
+    if (bcp_status s = device_scan<uint64_t, uint64_t>(weight, wprefix, (int64_t)n_tiles, arena, st)) return s;
+    hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes, flags);
+    BCP_HIP(hipGetLastError());
+    if (bcp_status s = device_scan<uint32_t, uint32_t>(flags, flags, (int64_t)n_tiles, arena, st)) return s;
+    hipLaunchKernelGGL(k_batch_starts, dim3(nblk), dim3(kBlock), 0, st, flags, n_tiles, bstart);
+    BCP_HIP(hipGetLastError());
+    BCP_HIP(hipMemcpyAsync(&n_batches, flags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    BCP_HIP(hipStreamSynchronize(st));
+    hipLaunchKernelGGL(k_batch_heads, dim3(blocks_for(n_batches)), dim3(kBlock), 0, st, tiles, bstart, n_batches, heads);
     BCP_HIP(hipGetLastError());
   }
   BCP_HIP(hipEventRecord(ev1, st));
@@ -819,10 +879,13 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   out->ctl = h;
   out->dev.regions = regions;
   out->dev.tiles = tiles;
+  out->dev.heads = heads;
   out->dev.n_regions = n_regions;
   out->dev.n_tiles = (int64_t)n_tiles;
+  out->dev.n_batches = (int64_t)n_batches;
   if (regions) arena.release(regions);
   arena.release(tiles);
+  arena.release(heads);
   return BCP_OK;
 }
 
