@@ -31,15 +31,17 @@ PlanConfig& config() { return g_config; }
 
 using namespace bcp;
 
-// The pointer table of a reshard call travels host -> device through a small ring of pinned
-// staging slots, so an asynchronous call never reads a slot a later call already rewrote.
+// Buffer pointers normally travel as kernel arguments.  Only a table too big for that
+// (more than kMaxKernargPtrs buffers) goes host -> device through a small ring of pinned staging
+// slots, set up at the first such call, so an asynchronous call never reads a slot a later call
+// already rewrote.
 constexpr int kSlots = 8;
 
 struct bcp_plan_s {
   PlanDevice dev;
   bcp_stats stats{};
   int device = 0;
-  void* table_dev = nullptr;   // [queue counter | src pointers | dst pointers]
+  void* table_dev = nullptr;   // [src pointers | dst pointers]
   char* table_host = nullptr;  // pinned, kSlots slots
   size_t table_bytes = 0;
   int32_t n_src = 0, n_dst = 0;
@@ -267,14 +269,7 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     st.n_batches = res.dev.n_batches;
     plan->n_src = (int32_t)(st.max_src_buf + 1);
     plan->n_dst = (int32_t)(st.max_dst_buf + 1);
-    plan->table_bytes = 8 + sizeof(void*) * (size_t)(plan->n_src + plan->n_dst);
-    hipError_t e = hipMalloc(&plan->table_dev, plan->table_bytes);
-    if (e == hipSuccess) e = hipHostMalloc((void**)&plan->table_host, plan->table_bytes * kSlots, hipHostMallocDefault);
-    for (int i = 0; i < kSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&plan->slot_done[i], hipEventDisableTiming);
-    if (e != hipSuccess) {
-      s = hip_fail(e, "bcp_plan: pointer table allocation");
-      break;
-    }
+    plan->table_bytes = sizeof(void*) * (size_t)(plan->n_src + plan->n_dst);
   } while (0);
   if (s != BCP_OK) {
     const std::string keep = g_error;
@@ -290,8 +285,7 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
 bcp_status bcp_plan_destroy(bcp_plan_t plan) {
   if (!plan) return BCP_OK;
   if (plan->dev.regions) (void)hipFree(plan->dev.regions);
-  if (plan->dev.tiles) (void)hipFree(plan->dev.tiles);
-  if (plan->dev.heads) (void)hipFree(plan->dev.heads);
+  if (plan->dev.heads) (void)hipFree(plan->dev.heads);  // heads, tiles and queue are one allocation
   if (plan->table_dev) (void)hipFree(plan->table_dev);
   if (plan->table_host) (void)hipHostFree(plan->table_host);
   for (int i = 0; i < kSlots; ++i)
@@ -398,18 +392,25 @@ bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_
     return BCP_ERR_INVALID_ARG;
   }
   hipStream_t st = (hipStream_t)stream;
+  if (plan->n_src + plan->n_dst <= kMaxKernargPtrs)
+    return launch_reshard(plan->dev, src_blobs, plan->n_src, dst_buffers, plan->n_dst, nullptr, st);
   std::lock_guard<std::mutex> g(plan->mu);
+  if (!plan->table_dev) {
+    hipError_t e = hipMalloc(&plan->table_dev, plan->table_bytes);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&plan->table_host, plan->table_bytes * kSlots, hipHostMallocDefault);
+    for (int i = 0; i < kSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&plan->slot_done[i], hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e, "bcp_reshard: pointer table allocation");
+  }
   const int slot = plan->next_slot;
   plan->next_slot = (slot + 1) % kSlots;
   if (plan->slot_used[slot]) BCP_HIP(hipEventSynchronize(plan->slot_done[slot]));
   char* h = plan->table_host + plan->table_bytes * (size_t)slot;
-  std::memset(h, 0, 8);  // queue counter starts at zero
-  std::memcpy(h + 8, src_blobs, sizeof(void*) * (size_t)plan->n_src);
-  std::memcpy(h + 8 + sizeof(void*) * (size_t)plan->n_src, dst_buffers, sizeof(void*) * (size_t)plan->n_dst);
+  std::memcpy(h, src_blobs, sizeof(void*) * (size_t)plan->n_src);
+  std::memcpy(h + sizeof(void*) * (size_t)plan->n_src, dst_buffers, sizeof(void*) * (size_t)plan->n_dst);
   BCP_HIP(hipMemcpyAsync(plan->table_dev, h, plan->table_bytes, hipMemcpyHostToDevice, st));
   BCP_HIP(hipEventRecord(plan->slot_done[slot], st));
   plan->slot_used[slot] = true;
-  return launch_reshard(plan->dev, plan->table_dev, plan->n_src, plan->n_dst, st);
+  return launch_reshard(plan->dev, nullptr, plan->n_src, nullptr, plan->n_dst, plan->table_dev, st);
 }
 
 bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream) {

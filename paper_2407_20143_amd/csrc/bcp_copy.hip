@@ -29,6 +29,7 @@ namespace {
 constexpr int kMaxThreads = 1024;
 constexpr int kLdsBytes = 32 * 33 * 16;  // >= 64*65*4: transpose staging incl. one pad column
 constexpr int kLdsPtrs = 1024;           // buffer pointers staged in LDS (more: read from global)
+constexpr int kArgPtrs = kMaxKernargPtrs;  // buffer pointers passed as kernel arguments
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -240,11 +241,20 @@ __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t
   }
 }
 
-// table: [queue counter (8 bytes) | n_src source pointers | n_dst destination pointers]
-__global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restrict__ heads, uint32_t n_batches,
-                                                         const TileDesc* __restrict__ tiles,
-                                                         const uint64_t* __restrict__ ptr_table, uint32_t n_src,
-                                                         uint32_t n_ptrs, unsigned long long* queue, int persistent) {
+// Buffer pointers reach the kernel as kernel arguments (up to kArgPtrs of them: no host-to-device
+// copy, no staging) or, for bigger tables, through a device array.  Either way they are staged in
+// LDS once per workgroup when they fit.
+struct PtrArgs {
+  uint64_t p[kArgPtrs];
+};
+
+// queue[0]: next batch index; queue[1]: workgroups that are done.  The last workgroup to finish
+// puts both back to zero, so the next launch on this plan needs no memset.
+template <typename PTRS>
+__device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads, uint32_t n_batches,
+                                             const TileDesc* __restrict__ tiles, const PTRS& ptr_table,
+                                             uint32_t n_src, uint32_t n_ptrs, unsigned long long* queue,
+                                             int persistent) {
   __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
   __shared__ uint64_t lds_ptrs[kLdsPtrs];
   __shared__ uint32_t slot[2];
@@ -288,23 +298,47 @@ __global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restr
   uint32_t cur = __builtin_amdgcn_readfirstlane(slot[0]);
   uint32_t nxt = __builtin_amdgcn_readfirstlane(slot[1]);
   __syncthreads();  // both slots read before slot[0] is written again
-  if (cur >= n_batches) return;
-  TileDesc H = heads[cur];
-  int ph = 0;
-  for (;;) {
-    TileDesc N = H;
-    if (nxt < n_batches) N = heads[nxt];  // scalar loads, consumed only after this batch's copy
-    unsigned long long popped = 0;
-    if (threadIdx.x == 0) popped = atomicAdd(queue, 1ull);
-    run_batch(H);
-    if (threadIdx.x == 0) slot[ph] = (uint32_t)min(popped, (unsigned long long)n_batches);
-    __syncthreads();
-    if (nxt >= n_batches) return;  // uniform: the queue only grows, every workgroup gets here
-    H = N;
-    cur = nxt;
-    nxt = __builtin_amdgcn_readfirstlane(slot[ph]);
-    ph ^= 1;  // the other slot is written next, so no second barrier is needed
+  if (cur < n_batches) {
+    TileDesc H = heads[cur];
+    int ph = 0;
+    for (;;) {
+      TileDesc N = H;
+      if (nxt < n_batches) N = heads[nxt];  // scalar loads, consumed only after this batch's copy
+      unsigned long long popped = 0;
+      if (threadIdx.x == 0) popped = atomicAdd(queue, 1ull);
+      run_batch(H);
+      if (threadIdx.x == 0) slot[ph] = (uint32_t)min(popped, (unsigned long long)n_batches);
+      __syncthreads();
+      if (nxt >= n_batches) break;  // uniform: the queue only grows, every workgroup gets here
+      H = N;
+      cur = nxt;
+      nxt = __builtin_amdgcn_readfirstlane(slot[ph]);
+      ph ^= 1;  // the other slot is written next, so no second barrier is needed
+    }
   }
+  // this workgroup pops no more; the last one to say so rearms the queue
+  if (threadIdx.x == 0) {
+    __threadfence();
+    if (atomicAdd(queue + 1, 1ull) == (unsigned long long)gridDim.x - 1) {
+      atomicExch(queue, 0ull);
+      atomicExch(queue + 1, 0ull);
+    }
+  }
+}
+
+__global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restrict__ heads, uint32_t n_batches,
+                                                         const TileDesc* __restrict__ tiles, PtrArgs ptrs,
+                                                         uint32_t n_src, uint32_t n_ptrs, unsigned long long* queue,
+                                                         int persistent) {
+  reshard_body(heads, n_batches, tiles, ptrs.p, n_src, n_ptrs, queue, persistent);
+}
+
+__global__ __launch_bounds__(kMaxThreads) void k_reshard_table(const TileDesc* __restrict__ heads, uint32_t n_batches,
+                                                               const TileDesc* __restrict__ tiles,
+                                                               const uint64_t* __restrict__ ptr_table, uint32_t n_src,
+                                                               uint32_t n_ptrs, unsigned long long* queue,
+                                                               int persistent) {
+  reshard_body(heads, n_batches, tiles, ptr_table, n_src, n_ptrs, queue, persistent);
 }
 
 __global__ __launch_bounds__(256) void k_copy_baseline(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
@@ -331,11 +365,11 @@ int device_cu_count() {
   return n;
 }
 
-bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, int32_t n_dst,
-                          hipStream_t stream) {
+// src/dst: host arrays of device pointers when the table fits the kernel arguments
+// (n_src + n_dst <= kMaxKernargPtrs), else `table` is a device array [src pointers | dst pointers].
+bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
+                          int32_t n_dst, const void* table, hipStream_t stream) {
   if (plan.n_batches == 0) return BCP_OK;
-  unsigned long long* queue = (unsigned long long*)table;
-  const uint64_t* ptrs = (const uint64_t*)((const char*)table + 8);
   const PlanConfig cfg = config();
   unsigned grid;
   if (cfg.persistent) {
@@ -348,9 +382,20 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_s
   } else {
     grid = (unsigned)plan.n_batches;
   }
-  hipLaunchKernelGGL(k_reshard, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.heads,
-                     (uint32_t)plan.n_batches, plan.tiles, ptrs, (uint32_t)n_src, (uint32_t)(n_src + n_dst), queue,
-                     cfg.persistent);
+  const uint32_t n_ptrs = (uint32_t)(n_src + n_dst);
+  if (!table) {
+    PtrArgs args;
+    for (int32_t i = 0; i < n_src; ++i) args.p[i] = (uint64_t)(uintptr_t)src[i];
+    for (int32_t i = 0; i < n_dst; ++i) args.p[n_src + i] = (uint64_t)(uintptr_t)dst[i];
+    for (uint32_t i = n_ptrs; i < (uint32_t)kArgPtrs; ++i) args.p[i] = 0;
+    hipLaunchKernelGGL(k_reshard, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.heads,
+                       (uint32_t)plan.n_batches, plan.tiles, args, (uint32_t)n_src, n_ptrs, plan.queue,
+                       cfg.persistent);
+  } else {
+    hipLaunchKernelGGL(k_reshard_table, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.heads,
+                       (uint32_t)plan.n_batches, plan.tiles, (const uint64_t*)table, (uint32_t)n_src, n_ptrs,
+                       plan.queue, cfg.persistent);
+  }
   BCP_HIP(hipGetLastError());
   return BCP_OK;
 }

@@ -120,7 +120,8 @@ bcp_status hip_fail(hipError_t e, const char* what);
 struct PlanDevice {
   Region* regions = nullptr;
   TileDesc* tiles = nullptr;
-  TileDesc* heads = nullptr;  // one per batch
+  TileDesc* heads = nullptr;  // one per batch; heads, tiles and queue share one allocation
+  unsigned long long* queue = nullptr;  // [next batch, finished workgroups], zero between launches
   int64_t n_regions = 0;
   int64_t n_tiles = 0;
   int64_t n_batches = 0;
@@ -137,9 +138,9 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
                        int64_t n_target, uint32_t flags, hipStream_t stream, PlannerResult* out);
 
 // ---- copy (bcp_copy.hip) ---------------------------------------------------------------------
-// table: device block [queue counter (8 bytes) | src pointers | dst pointers]
-bcp_status launch_reshard(const PlanDevice& plan, const void* table, int32_t n_src, int32_t n_dst,
-                          hipStream_t stream);
+constexpr int kMaxKernargPtrs = 256;  // buffer pointers that travel as kernel arguments
+bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
+                          int32_t n_dst, const void* table, hipStream_t stream);
 bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream);
 int device_cu_count();
 

@@ -1,4 +1,4 @@
-// GPU planner: from saved / target shard records to copy regions and tiles.
+// GPU planner: from saved / target shard records to copy regions, tiles and batches.
 //
 // Sec. 3.3 Step 2 of the paper ("identifying matching segments between the saved tensor shards
 // and the sharding specification of new shards") run as data-parallel kernels:
@@ -7,10 +7,16 @@
 //   2. sort the saved boxes by FQN (LSD radix sort, 4-bit digits, stable);
 //   3. per target box, find its FQN's run of saved boxes; scan the candidate-pair counts;
 //   4. one thread per candidate pair: intersect the two boxes; wave ballot + prefix to compact
-//      the non-empty intersections into a dense, deterministic region list;
-//   5. normalise each region (drop unit dims, merge dims contiguous on both sides), tile it,
-//      scan the tile counts and write the tile table; check coverage and saved disjointness.
+//      the non-empty intersections into a dense, deterministic region list; each region is
+//      normalised on the spot (unit dims dropped, dims contiguous on both sides merged) and tiled;
+//   5. scan the tile counts; weigh the tiles, group runs of small tiles into batches, and write one
+//      fully decoded descriptor per batch head (and per small tile);
+//   plus the checks: coverage of every target record, saved shards pairwise disjoint, records of
+//   one FQN agreeing on shape and itemsize.
+// Temporaries live in a process-wide, grow-only workspace, so a plan costs three device
+// allocations of its own (regions, descriptors, queue words) and four host synchronisations.
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "bcp_internal.h"
@@ -19,7 +25,9 @@ namespace bcp {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kScanItems = 4;  // items per thread in the device-wide scan
+constexpr int kScanItems = 4;         // items per thread in the multi-block scan
+constexpr int kSmallScanThreads = 1024;
+constexpr int64_t kSmallScanMax = 1 << 14;  // up to here one workgroup scans alone (one launch)
 
 using ull = unsigned long long;
 
@@ -35,17 +43,16 @@ __device__ inline T wave_inclusive_scan(T v) {
   return v;
 }
 
-// Exclusive scan of one value per thread over a 256-thread block; *total gets the block sum.
-// lds: at least 4 entries.
+// Exclusive scan of one value per thread over the workgroup (a multiple of 64 threads, at most
+// 1024); *total gets the workgroup sum.  lds: at least 16 entries.
 template <typename T>
 __device__ inline T block_exclusive_scan(T v, T* total, T* lds) {
   const T inc = wave_inclusive_scan(v);
-  const unsigned w = threadIdx.x >> 6;
+  const unsigned w = threadIdx.x >> 6, nw = blockDim.x >> 6;
   if (lane_id() == 63) lds[w] = inc;
   __syncthreads();
   T woff = 0, tot = 0;
-#pragma unroll
-  for (unsigned i = 0; i < kBlock / 64; ++i) {
+  for (unsigned i = 0; i < nw; ++i) {
     const T c = lds[i];
     if (i < w) woff += c;
     tot += c;
@@ -58,7 +65,7 @@ __device__ inline T block_exclusive_scan(T v, T* total, T* lds) {
 // ---- device-wide exclusive scan: out[i] = sum(in[0..i)), out[n] = total --------------------
 template <typename Tin, typename T>
 __global__ __launch_bounds__(kBlock) void k_scan_reduce(const Tin* in, int64_t n, T* part) {
-  __shared__ T lds[4];
+  __shared__ T lds[16];
   const int64_t base = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanItems;
   T s = 0;
   for (int i = 0; i < kScanItems; ++i)
@@ -69,10 +76,10 @@ __global__ __launch_bounds__(kBlock) void k_scan_reduce(const Tin* in, int64_t n
 }
 
 template <typename T>
-__global__ __launch_bounds__(kBlock) void k_scan_parts(T* part, int64_t nb) {
-  __shared__ T lds[4];
+__global__ __launch_bounds__(kSmallScanThreads) void k_scan_parts(T* part, int64_t nb) {
+  __shared__ T lds[16];
   T carry = 0;
-  for (int64_t base = 0; base < nb; base += kBlock) {
+  for (int64_t base = 0; base < nb; base += blockDim.x) {
     const int64_t i = base + threadIdx.x;
     const T v = i < nb ? part[i] : (T)0;
     T tot;
@@ -84,7 +91,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_parts(T* part, int64_t nb) {
 
 template <typename Tin, typename T>
 __global__ __launch_bounds__(kBlock) void k_scan_final(const Tin* in, int64_t n, const T* part, T* out) {
-  __shared__ T lds[4];
+  __shared__ T lds[16];
   const int64_t base = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * kScanItems;
   T v[kScanItems];
   T s = 0;
@@ -102,30 +109,68 @@ __global__ __launch_bounds__(kBlock) void k_scan_final(const Tin* in, int64_t n,
   if (base < n && base + kScanItems >= n) out[n] = run;
 }
 
-template <typename T>
-__global__ void k_set_one(T* p, T v) {
-  *p = v;
+// the whole scan in one workgroup (small inputs: one launch instead of three); n >= 0
+template <typename Tin, typename T>
+__global__ __launch_bounds__(kSmallScanThreads) void k_scan_small(const Tin* in, int64_t n, T* out) {
+  __shared__ T lds[16];
+  T carry = 0;
+  for (int64_t base = 0; base < n; base += blockDim.x) {
+    const int64_t i = base + threadIdx.x;
+    const T v = i < n ? (T)in[i] : (T)0;
+    T tot;
+    const T ex = block_exclusive_scan(v, &tot, lds);
+    if (i < n) out[i] = carry + ex;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) out[n] = carry;
 }
 
-struct Arena {
-  std::vector<void*> ptrs;
-  ~Arena() {
-    for (void* p : ptrs) (void)hipFree(p);
+// ---- workspace -------------------------------------------------------------------------------
+// Grow-only cache of device chunks shared by all bcp_plan calls of the process (planning is
+// serialised by the mutex).  A plan's temporaries are bump-allocated from it and simply
+// forgotten at the end of the call.
+struct Workspace {
+  struct Chunk {
+    char* base;
+    size_t size, used;
+    int device;
+  };
+  std::vector<Chunk> chunks;
+  std::mutex mu;
+  int device = -1;
+
+  void reset(int dev) {
+    if (dev != device) {  // another device: drop everything (rare)
+      for (Chunk& c : chunks) (void)hipFree(c.base);
+      chunks.clear();
+      device = dev;
+    }
+    for (Chunk& c : chunks) c.used = 0;
+  }
+  hipError_t raw(void** p, size_t bytes) {
+    bytes = (std::max<size_t>(bytes, 1) + 255) & ~(size_t)255;
+    for (Chunk& c : chunks)
+      if (c.size - c.used >= bytes) {
+        *p = c.base + c.used;
+        c.used += bytes;
+        return hipSuccess;
+      }
+    size_t sz = std::max<size_t>(bytes, (size_t)8 << 20);
+    if (!chunks.empty()) sz = std::max(sz, chunks.back().size * 2);
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, sz);
+    if (e != hipSuccess && sz > bytes) e = hipMalloc(&q, sz = bytes);
+    if (e != hipSuccess) return e;
+    chunks.push_back(Chunk{(char*)q, sz, bytes, device});
+    *p = q;
+    return hipSuccess;
   }
   template <typename T>
   hipError_t alloc(T** p, size_t count) {
-    void* q = nullptr;
-    hipError_t e = hipMalloc(&q, std::max<size_t>(count, 1) * sizeof(T));
-    if (e == hipSuccess) {
-      ptrs.push_back(q);
-      *p = (T*)q;
-    }
-    return e;
-  }
-  void release(void* p) {  // ownership leaves the arena
-    ptrs.erase(std::remove(ptrs.begin(), ptrs.end(), p), ptrs.end());
+    return raw((void**)p, count * sizeof(T));
   }
 };
+Workspace g_ws;
 
 inline unsigned blocks_for(int64_t n, int per_block = kBlock) {
   return (unsigned)std::max<int64_t>(1, (n + per_block - 1) / per_block);
@@ -133,17 +178,17 @@ inline unsigned blocks_for(int64_t n, int per_block = kBlock) {
 
 // in and out may alias when Tin == T.  out has n+1 entries.
 template <typename Tin, typename T>
-bcp_status device_scan(const Tin* in, T* out, int64_t n, Arena& arena, hipStream_t st) {
-  if (n <= 0) {
-    hipLaunchKernelGGL(k_set_one<T>, dim3(1), dim3(1), 0, st, out, (T)0);
+bcp_status device_scan(const Tin* in, T* out, int64_t n, Workspace& ws, hipStream_t st) {
+  if (n <= kSmallScanMax) {
+    hipLaunchKernelGGL((k_scan_small<Tin, T>), dim3(1), dim3(kSmallScanThreads), 0, st, in, std::max<int64_t>(n, 0), out);
     BCP_HIP(hipGetLastError());
     return BCP_OK;
   }
   const unsigned nb = blocks_for(n, kBlock * kScanItems);
   T* part = nullptr;
-  BCP_HIP(arena.alloc(&part, nb));
+  BCP_HIP(ws.alloc(&part, nb));
   hipLaunchKernelGGL((k_scan_reduce<Tin, T>), dim3(nb), dim3(kBlock), 0, st, in, n, part);
-  hipLaunchKernelGGL((k_scan_parts<T>), dim3(1), dim3(kBlock), 0, st, part, (int64_t)nb);
+  hipLaunchKernelGGL((k_scan_parts<T>), dim3(1), dim3(kSmallScanThreads), 0, st, part, (int64_t)nb);
   hipLaunchKernelGGL((k_scan_final<Tin, T>), dim3(nb), dim3(kBlock), 0, st, in, n, part, out);
   BCP_HIP(hipGetLastError());
   return BCP_OK;
@@ -336,9 +381,9 @@ __global__ __launch_bounds__(kBlock) void k_pair_count(const Box* boxes, int64_t
 
 __device__ inline bool boxes_intersect(const Box& a, const Box& b) {
   for (int k = 0; k < a.ndim; ++k) {
-    const int64_t lo = max(a.off[k], b.off[k]);
-    const int64_t hi = min(a.off[k] + a.len[k], b.off[k] + b.len[k]);
-    if (lo >= hi) return false;
+    const int64_t lo = a.off[k] > b.off[k] ? a.off[k] : b.off[k];
+    const int64_t ha = a.off[k] + a.len[k], hb = b.off[k] + b.len[k];
+    if (lo >= (ha < hb ? ha : hb)) return false;
   }
   return true;
 }
@@ -364,13 +409,13 @@ __global__ __launch_bounds__(kBlock) void k_saved_check(const Box* boxes, int64_
   for (int64_t j = i + 1; j < nbs && skeys[j] == skeys[i]; ++j) {
     const Box& b = boxes[sidx[j]];
     if (a.ndim == b.ndim && boxes_intersect(a, b)) {
-      report(ctl, max(a.rec, b.rec), kErrOverlap);
+      report(ctl, a.rec > b.rec ? a.rec : b.rec, kErrOverlap);
       return;
     }
   }
 }
 
-// ---- steps 4+5: intersect, compact, normalise, tile --------------------------------------------
+// ---- step 4: intersect, compact, normalise, tile ------------------------------------------------
 __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_bytes, Region* R, int64_t* volume) {
   const int n = t.ndim;
   if (s.ndim != n) return false;  // reported as a shape mismatch elsewhere
@@ -379,8 +424,9 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   int m = 0;
   int64_t soff = 0, doff = 0, vol = 1;
   for (int k = 0; k < n; ++k) {
-    const int64_t lo = max(s.off[k], t.off[k]);
-    const int64_t hi = min(s.off[k] + s.len[k], t.off[k] + t.len[k]);
+    const int64_t lo = s.off[k] > t.off[k] ? s.off[k] : t.off[k];
+    const int64_t hs = s.off[k] + s.len[k], ht = t.off[k] + t.len[k];
+    const int64_t hi = hs < ht ? hs : ht;
     if (lo >= hi) return false;
     soff += (lo - s.off[k]) * s.stride[k];
     doff += (lo - t.off[k]) * t.stride[k];
@@ -448,9 +494,9 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
     const uint64_t ta = ((uint64_t)L[a] + td - 1) / td, tb = ((uint64_t)L[b] + td - 1) / td;
     uint64_t groups = 1;
     for (int k = 0; k < nd - 2; ++k) groups *= (uint64_t)R->len[k];
-    R->tiles_b = (uint32_t)min(tb, (uint64_t)0xffffffffu);
+    R->tiles_b = (uint32_t)(tb < 0xffffffffull ? tb : 0xffffffffull);
     const uint64_t tpg = ta * tb;
-    R->tiles_per_group = (uint32_t)min(tpg, (uint64_t)0xffffffffu);
+    R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
     R->n_tiles = (tpg >> 32) ? ~0ull : groups * tpg;
     return true;
   }
@@ -475,7 +521,7 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   uint64_t tpg;
   if ((uint64_t)R->run_bytes >= tile_bytes) {
     const uint64_t segs = ((uint64_t)R->run_bytes + tile_bytes - 1) / tile_bytes;
-    R->segs_per_row = (uint32_t)min(segs, (uint64_t)0xffffffffu);
+    R->segs_per_row = (uint32_t)(segs < 0xffffffffull ? segs : 0xffffffffull);
     tpg = (segs >> 32) ? ~0ull : L0 * segs;
   } else {
     uint64_t rpt = tile_bytes / (uint64_t)R->run_bytes;
@@ -483,10 +529,17 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
     R->rows_per_tile = (uint32_t)rpt;
     tpg = (L0 + rpt - 1) / rpt;
   }
-  R->tiles_per_group = (uint32_t)min(tpg, (uint64_t)0xffffffffu);
+  R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
   R->n_tiles = (tpg >> 32) ? ~0ull : groups * tpg;
   return true;
 }
+
+// plan statistics are summed per workgroup in LDS first: one global atomic per counter and
+// workgroup instead of one per region
+struct BlockStats {
+  ull payload, transposed, dims[kDims + 1];
+  long long max_src, max_dst;
+};
 
 // One thread per candidate pair.  WRITE == false: count the non-empty intersections per block.
 // WRITE == true: write them densely at blk_off[block] + rank inside the block (rank from wave
@@ -498,6 +551,12 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
                                                   uint32_t* blk_cnt, const uint32_t* blk_off, uint32_t tile_bytes,
                                                   Region* regions, uint64_t* tile_cnt, ull* cov, Ctl* ctl) {
   __shared__ uint32_t wcnt[kBlock / 64];
+  __shared__ BlockStats bs;
+  if (WRITE && threadIdx.x == 0) {
+    bs.payload = bs.transposed = 0;
+    for (int k = 0; k <= kDims; ++k) bs.dims[k] = 0;
+    bs.max_src = bs.max_dst = -1;
+  }
   const uint64_t p = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   bool hit = false;
   const Box* sb = nullptr;
@@ -522,21 +581,31 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
     }
     return;
   }
-  if (!hit) return;
-  uint32_t pos = blk_off[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane_id()) - 1ull));
-  for (unsigned i = 0; i < w; ++i) pos += wcnt[i];
-  Region R;
-  int64_t vol = 0;
-  build_region(*sb, *tb, tile_bytes, &R, &vol);
-  regions[pos] = R;
-  tile_cnt[pos] = R.n_tiles;
-  atomicAdd(&cov[tb->rec], (ull)vol);
-  atomicAdd(&ctl->payload_bytes, (ull)vol * (ull)tb->itemsize);
-  atomicAdd(&ctl->dims_hist[R.ndim + (R.kind == kRows && R.run_bytes > tb->itemsize ? 1 : 0)], 1ull);
-  if (R.kind == kTranspose) atomicAdd(&ctl->n_transposed, 1ull);
-  atomicMax(&ctl->max_src_buf, (long long)R.src_buf);
-  atomicMax(&ctl->max_dst_buf, (long long)R.dst_buf);
-  if (R.n_tiles == ~0ull) report(ctl, 0, kErrInvalid);
+  if (hit) {
+    uint32_t pos = blk_off[blockIdx.x] + (uint32_t)__popcll(m & ((1ull << lane_id()) - 1ull));
+    for (unsigned i = 0; i < w; ++i) pos += wcnt[i];
+    Region R;
+    int64_t vol = 0;
+    build_region(*sb, *tb, tile_bytes, &R, &vol);
+    regions[pos] = R;
+    tile_cnt[pos] = R.n_tiles;
+    atomicAdd(&cov[tb->rec], (ull)vol);
+    atomicAdd(&bs.payload, (ull)vol * (ull)tb->itemsize);
+    atomicAdd(&bs.dims[R.ndim + (R.kind == kRows && R.run_bytes > tb->itemsize ? 1 : 0)], 1ull);
+    if (R.kind == kTranspose) atomicAdd(&bs.transposed, 1ull);
+    atomicMax(&bs.max_src, (long long)R.src_buf);
+    atomicMax(&bs.max_dst, (long long)R.dst_buf);
+    if (R.n_tiles == ~0ull) report(ctl, 0, kErrInvalid);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && (wcnt[0] | wcnt[1] | wcnt[2] | wcnt[3])) {
+    atomicAdd(&ctl->payload_bytes, bs.payload);
+    if (bs.transposed) atomicAdd(&ctl->n_transposed, bs.transposed);
+    for (int k = 0; k <= kDims; ++k)
+      if (bs.dims[k]) atomicAdd(&ctl->dims_hist[k], bs.dims[k]);
+    atomicMax(&ctl->max_src_buf, bs.max_src);
+    atomicMax(&ctl->max_dst_buf, bs.max_dst);
+  }
 }
 
 __global__ __launch_bounds__(kBlock) void k_coverage(const bcp_shard_meta* recs, int64_t n_saved, int64_t n_target,
@@ -549,24 +618,16 @@ __global__ __launch_bounds__(kBlock) void k_coverage(const bcp_shard_meta* recs,
   else if (cov[i] < want && !allow_uncovered) report(ctl, n_saved + i, kErrUncovered);
 }
 
-// One thread per tile: find the region (binary search in the scanned tile counts) and decode the
-// tile completely -- leading row indices, row / segment range, byte offsets -- so the copy kernel
-// does no index arithmetic beyond its own lanes.
-// weight[i]: what the tile counts towards a batch budget (0 for big tiles, which are batches of
-// their own).
-__global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_start, const Region* regions,
-                                                       int64_t n_regions, uint64_t n_tiles, TileDesc* tiles,
-                                                       uint64_t* weight) {
-  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= n_tiles) return;
-  const int64_t r = upper_bound_u64(tile_start, n_regions + 1, i) - 1;
-  const Region& R = regions[r];
-  const uint32_t local = (uint32_t)(i - tile_start[r]);
+// ---- step 5: tiles and batches -------------------------------------------------------------------
+// Decode tile `local` of region R completely -- leading row indices, row / segment range, byte
+// offsets -- so the copy kernel does no index arithmetic beyond its own lanes.  Returns the
+// tile's payload bytes.
+__device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc* out) {
   TileDesc t;
   t.src_buf = (uint32_t)R.src_buf;
   t.dst_buf = (uint32_t)R.dst_buf;
   t.kind = (uint32_t)R.kind;
-  t.first = (uint32_t)i;
+  t.first = 0;
   t.count = 1;
   t.pad_ = 0;
   uint64_t bytes;
@@ -586,8 +647,9 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_star
     const uint32_t td = R.tdim;
     const uint32_t ta = w / R.tiles_b, tb = w - ta * R.tiles_b;
     const uint64_t a0 = (uint64_t)ta * td, b0 = (uint64_t)tb * td;
-    t.a = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 2] - a0);
-    t.b = (uint32_t)min((uint64_t)td, (uint64_t)R.len[nd - 1] - b0);
+    const uint64_t ra = (uint64_t)R.len[nd - 2] - a0, rb = (uint64_t)R.len[nd - 1] - b0;
+    t.a = (uint32_t)(ra < td ? ra : td);
+    t.b = (uint32_t)(rb < td ? rb : td);
     t.p0 = R.spitch[nd - 1];
     t.p1 = R.dpitch[nd - 2];
     t.kind |= ((uint32_t)R.run_bytes << 8) | (td << 16);
@@ -610,12 +672,14 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_star
       const int64_t off = (int64_t)seg * R.tile_bytes;
       so += (int64_t)row * sp + off;
       dof += (int64_t)row * dp + off;
-      t.a = (uint32_t)min((int64_t)R.tile_bytes, R.run_bytes - off);
+      const int64_t left = R.run_bytes - off;
+      t.a = (uint32_t)(left < (int64_t)R.tile_bytes ? left : (int64_t)R.tile_bytes);
       t.b = 1;
     } else {  // a few whole short rows
       const uint64_t L0 = nd >= 1 ? (uint64_t)R.len[nd - 1] : 1;
       const uint64_t row0 = (uint64_t)w * R.rows_per_tile;
-      t.b = (uint32_t)min((uint64_t)R.rows_per_tile, L0 - row0);
+      const uint64_t left = L0 - row0;
+      t.b = (uint32_t)(left < R.rows_per_tile ? left : R.rows_per_tile);
       t.a = (uint32_t)R.run_bytes;
       so += (int64_t)row0 * sp;
       dof += (int64_t)row0 * dp;
@@ -624,8 +688,21 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_star
   }
   t.src_off = so;
   t.dst_off = dof;
-  tiles[i] = t;
-  weight[i] = bytes >= kSmallTileBytes ? 0 : max(bytes, (uint64_t)kMinBatchWeight);
+  if (out) *out = t;
+  return bytes;
+}
+
+// Pass A, one thread per tile: its region (binary search in the scanned tile counts) and what it
+// counts towards a batch budget: 0 for big tiles, which are batches of their own.
+__global__ __launch_bounds__(kBlock) void k_tile_weights(const uint64_t* tile_start, const Region* regions,
+                                                         int64_t n_regions, uint64_t n_tiles, uint32_t* tile_region,
+                                                         uint64_t* weight) {
+  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_tiles) return;
+  const int64_t r = upper_bound_u64(tile_start, n_regions + 1, i) - 1;
+  tile_region[i] = (uint32_t)r;
+  const uint64_t bytes = decode_tile(regions[r], (uint32_t)(i - tile_start[r]), nullptr);
+  weight[i] = bytes >= kSmallTileBytes ? 0 : (bytes > kMinBatchWeight ? bytes : (uint64_t)kMinBatchWeight);
 }
 
 // A batch starts at tile i when i is big, follows a big tile, or the running weight of the small
@@ -639,25 +716,39 @@ __global__ __launch_bounds__(kBlock) void k_batch_flags(const uint64_t* weight, 
   flags[i] = f;
 }
 
-// batch_id: exclusive scan of flags (so a start tile's batch is batch_id[i]); bstart[b] = first tile.
+// batch_id: exclusive scan of the start flags, so a start tile's batch is batch_id[i]; bstart[b] is
+// batch b's first tile, with a sentinel after the last batch.
 __global__ __launch_bounds__(kBlock) void k_batch_starts(const uint32_t* batch_id, uint64_t n_tiles, uint32_t* bstart) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i > n_tiles) return;
   if (i == n_tiles) {
-    bstart[batch_id[n_tiles]] = (uint32_t)n_tiles;  // sentinel after the last batch
+    bstart[batch_id[n_tiles]] = (uint32_t)n_tiles;
     return;
   }
   if (batch_id[i + 1] != batch_id[i]) bstart[batch_id[i]] = (uint32_t)i;
 }
 
-__global__ __launch_bounds__(kBlock) void k_batch_heads(const TileDesc* tiles, const uint32_t* bstart,
-                                                        uint32_t n_batches, TileDesc* heads) {
-  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
-  if (b >= n_batches) return;
-  TileDesc t = tiles[bstart[b]];
-  t.first = bstart[b];
-  t.count = bstart[b + 1] - bstart[b];
-  heads[b] = t;
+// Pass B, one thread per tile: the decoded descriptor goes to heads[batch] when the tile opens a
+// batch and to tiles[i] when it is small (members of multi-tile batches are fetched from there).
+__global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_start, const Region* regions,
+                                                       const uint32_t* tile_region, const uint64_t* weight,
+                                                       const uint32_t* batch_id, const uint32_t* bstart,
+                                                       uint64_t n_tiles, TileDesc* tiles, TileDesc* heads) {
+  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_tiles) return;
+  const uint32_t r = tile_region[i];
+  const bool opens = batch_id[i + 1] != batch_id[i];
+  const bool small = weight[i] != 0;
+  if (!opens && !small) return;
+  TileDesc t;
+  decode_tile(regions[r], (uint32_t)(i - tile_start[r]), &t);
+  t.first = (uint32_t)i;
+  if (small) tiles[i] = t;
+  if (opens) {
+    const uint32_t b = batch_id[i];
+    t.count = bstart[b + 1] - bstart[b];
+    heads[b] = t;
+  }
 }
 
 bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
@@ -680,11 +771,19 @@ bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
   return BCP_ERR_INVALID_ARG;
 }
 
+// device memory a plan keeps; freed here on any early return
+struct Owned {
+  void* p[3] = {nullptr, nullptr, nullptr};
+  ~Owned() {
+    for (void* q : p)
+      if (q) (void)hipFree(q);
+  }
+};
+
 }  // namespace
 
 bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shard_meta* target,
                        int64_t n_target, uint32_t flags, hipStream_t st, PlannerResult* out) {
-  Arena arena;
   const int64_t n_total = n_saved + n_target;
   const uint32_t tile_bytes = (uint32_t)config().tile_bytes;
   out->dev = PlanDevice{};
@@ -700,6 +799,12 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     set_error("too many records");
     return BCP_ERR_INVALID_ARG;
   }
+  int dev = 0;
+  BCP_HIP(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> ws_lock(g_ws.mu);
+  Workspace& ws = g_ws;
+  ws.reset(dev);
+  Owned owned;
 
   hipEvent_t ev0, ev1;
   BCP_HIP(hipEventCreate(&ev0));
@@ -715,18 +820,18 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   bcp_shard_meta* recs = nullptr;
   Ctl* ctl = nullptr;
   uint32_t* box_start = nullptr;
-  BCP_HIP(arena.alloc(&recs, (size_t)n_total));
-  BCP_HIP(arena.alloc(&ctl, 1));
-  BCP_HIP(arena.alloc(&box_start, (size_t)n_total + 1));
+  BCP_HIP(ws.alloc(&recs, (size_t)n_total));
+  BCP_HIP(ws.alloc(&ctl, 1));
+  BCP_HIP(ws.alloc(&box_start, (size_t)n_total + 1));
   if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, hipMemcpyHostToDevice, st));
   BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, hipMemcpyHostToDevice, st));
   BCP_HIP(hipMemcpyAsync(ctl, &init, sizeof(Ctl), hipMemcpyHostToDevice, st));
   BCP_HIP(hipEventRecord(ev0, st));
 
-  // 1. validate + count boxes, scan
+  // 1. validate + count boxes, scan                                                    (sync 1)
   hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total)), dim3(kBlock), 0, st, recs, n_saved, n_total, box_start, ctl);
   BCP_HIP(hipGetLastError());
-  if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, arena, st)) return s;
+  if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, ws, st)) return s;
   Ctl h{};
   uint32_t nb_host[2] = {0, 0};
   BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
@@ -743,17 +848,17 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   }
 
   Box* boxes = nullptr;
-  BCP_HIP(arena.alloc(&boxes, (size_t)nbx));
+  BCP_HIP(ws.alloc(&boxes, (size_t)nbx));
   hipLaunchKernelGGL(k_emit_boxes, dim3(blocks_for(n_total)), dim3(kBlock), 0, st, recs, n_saved, n_total, box_start, boxes);
   BCP_HIP(hipGetLastError());
 
   // 2. sort saved boxes by fqn
   uint64_t *keys_a = nullptr, *keys_b = nullptr;
   uint32_t *idx_a = nullptr, *idx_b = nullptr;
-  BCP_HIP(arena.alloc(&keys_a, (size_t)nbs));
-  BCP_HIP(arena.alloc(&keys_b, (size_t)nbs));
-  BCP_HIP(arena.alloc(&idx_a, (size_t)nbs));
-  BCP_HIP(arena.alloc(&idx_b, (size_t)nbs));
+  BCP_HIP(ws.alloc(&keys_a, (size_t)nbs));
+  BCP_HIP(ws.alloc(&keys_b, (size_t)nbs));
+  BCP_HIP(ws.alloc(&idx_a, (size_t)nbs));
+  BCP_HIP(ws.alloc(&idx_b, (size_t)nbs));
   if (nbs > 0) {
     const unsigned nblk = blocks_for(nbs);
     hipLaunchKernelGGL(k_sort_init, dim3(nblk), dim3(kBlock), 0, st, boxes, nbs, keys_a, idx_a);
@@ -762,11 +867,11 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     while (bits < 64 && (h.max_saved_fqn >> bits) != 0) ++bits;
     if (nbs > 1 && bits > 0) {
       uint32_t* hist = nullptr;
-      BCP_HIP(arena.alloc(&hist, (size_t)16 * nblk + 1));
+      BCP_HIP(ws.alloc(&hist, (size_t)16 * nblk + 1));
       for (int shift = 0; shift < bits; shift += 4) {
         hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(kBlock), 0, st, keys_a, nbs, shift, hist, nblk);
         BCP_HIP(hipGetLastError());
-        if (bcp_status s = device_scan<uint32_t, uint32_t>(hist, hist, (int64_t)16 * nblk, arena, st)) return s;
+        if (bcp_status s = device_scan<uint32_t, uint32_t>(hist, hist, (int64_t)16 * nblk, ws, st)) return s;
         hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(kBlock), 0, st, keys_a, idx_a, nbs, shift, hist, nblk, keys_b, idx_b);
         BCP_HIP(hipGetLastError());
         std::swap(keys_a, keys_b);
@@ -775,14 +880,17 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     }
   }
 
-  // 3. candidate pairs
+  // 3. candidate pairs                                                                     (sync 2)
   uint32_t* grp_lo = nullptr;
   uint64_t* pair_start = nullptr;
-  BCP_HIP(arena.alloc(&grp_lo, (size_t)nbt));
-  BCP_HIP(arena.alloc(&pair_start, (size_t)nbt + 1));
+  ull* cov = nullptr;
+  BCP_HIP(ws.alloc(&grp_lo, (size_t)nbt));
+  BCP_HIP(ws.alloc(&pair_start, (size_t)nbt + 1));
+  BCP_HIP(ws.alloc(&cov, (size_t)n_target));
+  BCP_HIP(hipMemsetAsync(cov, 0, sizeof(ull) * (size_t)n_target, st));
   hipLaunchKernelGGL(k_pair_count, dim3(blocks_for(nbt)), dim3(kBlock), 0, st, boxes, nbs, nbt, keys_a, idx_a, recs, n_saved, grp_lo, pair_start, ctl);
   BCP_HIP(hipGetLastError());
-  if (bcp_status s = device_scan<uint64_t, uint64_t>(pair_start, pair_start, nbt, arena, st)) return s;
+  if (bcp_status s = device_scan<uint64_t, uint64_t>(pair_start, pair_start, nbt, ws, st)) return s;
   if (nbs > 0) {
     hipLaunchKernelGGL(k_saved_check, dim3(blocks_for(nbs)), dim3(kBlock), 0, st, boxes, nbs, keys_a, idx_a, recs,
                        (flags & BCP_SKIP_OVERLAP_CHECK) ? 0 : 1, ctl);
@@ -793,99 +901,112 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   BCP_HIP(hipMemcpyAsync(&n_pairs, pair_start + nbt, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   BCP_HIP(hipStreamSynchronize(st));
   if (bcp_status s = device_error(h, n_saved)) return s;
-  if (n_pairs >= (1ull << 40)) {
+  if (n_pairs >= (1ull << 31) * kBlock) {
     set_error("too many candidate pairs");
     return BCP_ERR_OOM;
   }
 
-  // 4. count, then write the non-empty intersections
-  ull* cov = nullptr;
-  BCP_HIP(arena.alloc(&cov, (size_t)n_target));
-  BCP_HIP(hipMemsetAsync(cov, 0, sizeof(ull) * (size_t)n_target, st));
+  // 4. count, then write the non-empty intersections.  Regions are a plan-owned allocation: sized
+  // by the pair count when that is cheap, else by the exact region count            (sync 3, rare)
   uint32_t n_regions = 0;
   Region* regions = nullptr;
   uint64_t* tile_start = nullptr;
+  uint32_t* blk = nullptr;
+  unsigned nblk_pairs = 0;
   if (n_pairs > 0) {
-    const unsigned nblk = blocks_for((int64_t)n_pairs);
-    uint32_t* blk = nullptr;
-    BCP_HIP(arena.alloc(&blk, (size_t)nblk + 1));
-    hipLaunchKernelGGL((k_pairs<false>), dim3(nblk), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
+    nblk_pairs = blocks_for((int64_t)n_pairs);
+    BCP_HIP(ws.alloc(&blk, (size_t)nblk_pairs + 1));
+    hipLaunchKernelGGL((k_pairs<false>), dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
                        n_pairs, blk, blk, tile_bytes, (Region*)nullptr, (uint64_t*)nullptr, cov, ctl);
     BCP_HIP(hipGetLastError());
-    if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk, arena, st)) return s;
-    BCP_HIP(hipMemcpyAsync(&n_regions, blk + nblk, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-    BCP_HIP(hipStreamSynchronize(st));
-    BCP_HIP(arena.alloc(&regions, (size_t)n_regions));
-    BCP_HIP(arena.alloc(&tile_start, (size_t)n_regions + 1));
-    if (n_regions > 0) {
-      hipLaunchKernelGGL((k_pairs<true>), dim3(nblk), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
-                         n_pairs, blk, blk, tile_bytes, regions, tile_start, cov, ctl);
-      BCP_HIP(hipGetLastError());
+    if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk_pairs, ws, st)) return s;
+    size_t cap = (size_t)n_pairs;
+    if (cap * sizeof(Region) > ((size_t)64 << 20)) {
+      BCP_HIP(hipMemcpyAsync(&n_regions, blk + nblk_pairs, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+      BCP_HIP(hipStreamSynchronize(st));
+      cap = n_regions;
     }
-  } else {
-    BCP_HIP(arena.alloc(&tile_start, 1));
-  }
-  hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
-                     (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);
-  BCP_HIP(hipGetLastError());
-  if (bcp_status s = device_scan<uint64_t, uint64_t>(tile_start, tile_start, n_regions, arena, st)) return s;
-  uint64_t n_tiles = 0;
-  BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-  BCP_HIP(hipMemcpyAsync(&n_tiles, tile_start + n_regions, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-  BCP_HIP(hipStreamSynchronize(st));
-  if (bcp_status s = device_error(h, n_saved)) return s;
-  if (n_tiles >= 0xffffffffull) {
-    set_error("too many tiles; raise tile_bytes with bcp_configure");
-    return BCP_ERR_OOM;
-  }
-
-  // 5. tile table, then batches: big tiles alone, runs of small tiles together
-  TileDesc* tiles = nullptr;
-  TileDesc* heads = nullptr;
-  uint32_t n_batches = 0;
-  BCP_HIP(arena.alloc(&tiles, (size_t)n_tiles));
-  BCP_HIP(arena.alloc(&heads, (size_t)n_tiles));
-  if (n_tiles > 0) {
-    uint64_t* weight = nullptr;
-    uint64_t* wprefix = nullptr;
-    uint32_t* flags = nullptr;
-    uint32_t* bstart = nullptr;
-    BCP_HIP(arena.alloc(&weight, (size_t)n_tiles));
-    BCP_HIP(arena.alloc(&wprefix, (size_t)n_tiles + 1));
-    BCP_HIP(arena.alloc(&flags, (size_t)n_tiles + 1));
-    BCP_HIP(arena.alloc(&bstart, (size_t)n_tiles + 1));
-    const unsigned nblk = blocks_for((int64_t)n_tiles + 1);
-    hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, tile_start, regions, (int64_t)n_regions,
-                       n_tiles, tiles, weight);
+    BCP_HIP(hipMalloc(&owned.p[0], std::max<size_t>(cap, 1) * sizeof(Region)));
+    regions = (Region*)owned.p[0];
+    BCP_HIP(ws.alloc(&tile_start, cap + 1));
+    // slots beyond the region count stay zero so that the scan below may run over `cap` entries
+    BCP_HIP(hipMemsetAsync(tile_start, 0, sizeof(uint64_t) * (cap + 1), st));
+    hipLaunchKernelGGL((k_pairs<true>), dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
+                       n_pairs, blk, blk, tile_bytes, regions, tile_start, cov, ctl);
     BCP_HIP(hipGetLastError());
-    if (bcp_status s = device_scan<uint64_t, uint64_t>(weight, wprefix, (int64_t)n_tiles, arena, st)) return s;
-    hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes, flags);
+    hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
+                       (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);
     BCP_HIP(hipGetLastError());
-    if (bcp_status s = device_scan<uint32_t, uint32_t>(flags, flags, (int64_t)n_tiles, arena, st)) return s;
-    hipLaunchKernelGGL(k_batch_starts, dim3(nblk), dim3(kBlock), 0, st, flags, n_tiles, bstart);
-    BCP_HIP(hipGetLastError());
-    BCP_HIP(hipMemcpyAsync(&n_batches, flags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    if (bcp_status s = device_scan<uint64_t, uint64_t>(tile_start, tile_start, (int64_t)cap, ws, st)) return s;
+    // tile total and region count                                                         (sync 4)
+    uint64_t n_tiles = 0;
+    BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+    BCP_HIP(hipMemcpyAsync(&n_tiles, tile_start + cap, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    BCP_HIP(hipMemcpyAsync(&n_regions, blk + nblk_pairs, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     BCP_HIP(hipStreamSynchronize(st));
-    hipLaunchKernelGGL(k_batch_heads, dim3(blocks_for(n_batches)), dim3(kBlock), 0, st, tiles, bstart, n_batches, heads);
+    if (bcp_status s = device_error(h, n_saved)) return s;
+    if (n_tiles >= 0xffffffffull) {
+      set_error("too many tiles; raise tile_bytes with bcp_configure");
+      return BCP_ERR_OOM;
+    }
+
+    // 5. batches and descriptors: [heads | tiles] in one plan-owned allocation
+    TileDesc* heads = nullptr;
+    TileDesc* tiles = nullptr;
+    uint32_t n_batches = 0;
+    if (n_tiles > 0) {
+      BCP_HIP(hipMalloc(&owned.p[1], sizeof(TileDesc) * 2 * (size_t)n_tiles + 64));
+      heads = (TileDesc*)owned.p[1];
+      tiles = heads + n_tiles;
+      out->dev.queue = (unsigned long long*)(tiles + n_tiles);
+      BCP_HIP(hipMemsetAsync(out->dev.queue, 0, 64, st));
+      uint64_t* weight = nullptr;
+      uint64_t* wprefix = nullptr;
+      uint32_t* tile_region = nullptr;
+      uint32_t* bflags = nullptr;
+      uint32_t* bstart = nullptr;
+      BCP_HIP(ws.alloc(&weight, (size_t)n_tiles));
+      BCP_HIP(ws.alloc(&wprefix, (size_t)n_tiles + 1));
+      BCP_HIP(ws.alloc(&tile_region, (size_t)n_tiles));
+      BCP_HIP(ws.alloc(&bflags, (size_t)n_tiles + 1));
+      BCP_HIP(ws.alloc(&bstart, (size_t)n_tiles + 1));
+      const unsigned nblk = blocks_for((int64_t)n_tiles + 1);
+      hipLaunchKernelGGL(k_tile_weights, dim3(nblk), dim3(kBlock), 0, st, tile_start, regions, (int64_t)n_regions,
+                         n_tiles, tile_region, weight);
+      BCP_HIP(hipGetLastError());
+      if (bcp_status s = device_scan<uint64_t, uint64_t>(weight, wprefix, (int64_t)n_tiles, ws, st)) return s;
+      hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes, bflags);
+      BCP_HIP(hipGetLastError());
+      if (bcp_status s = device_scan<uint32_t, uint32_t>(bflags, bflags, (int64_t)n_tiles, ws, st)) return s;
+      hipLaunchKernelGGL(k_batch_starts, dim3(nblk), dim3(kBlock), 0, st, bflags, n_tiles, bstart);
+      hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, tile_start, regions, tile_region, weight,
+                         bflags, bstart, n_tiles, tiles, heads);
+      BCP_HIP(hipGetLastError());
+      BCP_HIP(hipMemcpyAsync(&n_batches, bflags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    }
+    BCP_HIP(hipEventRecord(ev1, st));
+    BCP_HIP(hipStreamSynchronize(st));                                                 // (final sync)
+    BCP_HIP(hipEventElapsedTime(&out->device_ms, ev0, ev1));
+    h.n_tiles = n_tiles;
+    out->dev.tiles = tiles;
+    out->dev.heads = heads;
+    out->dev.n_tiles = (int64_t)n_tiles;
+    out->dev.n_batches = (int64_t)n_batches;
+  } else {
+    hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
+                       (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);
     BCP_HIP(hipGetLastError());
+    BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+    BCP_HIP(hipStreamSynchronize(st));
+    if (bcp_status s = device_error(h, n_saved)) return s;
   }
-  BCP_HIP(hipEventRecord(ev1, st));
-  BCP_HIP(hipStreamSynchronize(st));
-  BCP_HIP(hipEventElapsedTime(&out->device_ms, ev0, ev1));
 
   h.n_pairs = n_pairs;
   h.n_regions = n_regions;
-  h.n_tiles = n_tiles;
   out->ctl = h;
   out->dev.regions = regions;
-  out->dev.tiles = tiles;
-  out->dev.heads = heads;
   out->dev.n_regions = n_regions;
-  out->dev.n_tiles = (int64_t)n_tiles;
-  out->dev.n_batches = (int64_t)n_batches;
-  if (regions) arena.release(regions);
-  arena.release(tiles);
-  arena.release(heads);
+  owned.p[0] = owned.p[1] = nullptr;  // the plan owns them now
   return BCP_OK;
 }
 

@@ -119,6 +119,14 @@ def test_cfg5_scaled():
     check_case(synth.cfg5(layers=2, hidden=256, experts=16, ffn=88, n_small=3000))
 
 
+@pytest.mark.parametrize("n_bufs", [200, 700])
+def test_many_buffers(n_bufs):
+    """More buffers than fit the kernel arguments (pointer table in device memory), and more than
+    the kernel stages in LDS."""
+    specs, saved, target = synth.small_tensor_case(1500, 77, n_bufs=n_bufs, max_shards=6, hi=2000)
+    check_case(Case(f"many{n_bufs}", 77, specs, saved, target))
+
+
 def test_round_trip_on_gpu():
     case = synth.random_case(400, n_tensors=8, max_elems=20000, saved_mode="flat", target_mode="grid")
     src = synth.materialize(case.saved, case.tensors, case.seed, poison=POISON)
