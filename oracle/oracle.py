@@ -60,49 +60,53 @@ def _load():
         _lib.orc_reshard.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
-            ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
+            ctypes.c_char_p, ctypes.c_int]
         assert _lib.orc_max_dims() == MAX_DIMS
     return _lib
 
 
+def _pad(t):
+    return tuple(t) + (0,) * (MAX_DIMS - len(t))
+
+
 def _marshal(layout):
     """Layout (paper_2407_20143_amd.synth) -> (parts array, shards array).  A group's shared part
-    list is emitted once."""
-    n_parts = 0
+    list is emitted once.  Filled column-wise: a million shards take about a second."""
+    part_list = []
+    begins = []
     seen = {}
     for sh in layout.shards:
         key = id(sh.parts) if sh.group >= 0 else None
-        if key is None or key not in seen:
-            if key is not None:
-                seen[key] = n_parts
-            n_parts += len(sh.parts)
-    parts = np.zeros(max(n_parts, 1), dtype=PART_DTYPE)
-    shards = np.zeros(max(len(layout.shards), 1), dtype=SHARD_DTYPE)
-    seen = {}
-    cur = 0
-    for i, sh in enumerate(layout.shards):
-        key = id(sh.parts) if sh.group >= 0 else None
         if key is not None and key in seen:
-            begin = seen[key]
-        else:
-            begin = cur
-            if key is not None:
-                seen[key] = begin
-            for p in sh.parts:
-                r = parts[cur]
-                n = len(p.global_shape)
-                r["fqn"], r["ndim"] = p.fqn, n
-                r["global_shape"][:n] = p.global_shape
-                r["offsets"][:n] = p.offsets
-                r["lengths"][:n] = p.lengths
-                cur += 1
-        s = shards[i]
-        s["part_begin"], s["part_count"] = begin, len(sh.parts)
-        s["flat_begin"], s["flat_end"] = sh.flat_begin, sh.flat_end
-        s["byte_offset"], s["itemsize"], s["buf"] = sh.byte_offset, sh.itemsize, sh.buf
-        if sh.strides is not None:
-            s["has_strides"] = 1
-            s["strides"][:len(sh.strides)] = sh.strides
+            begins.append(seen[key])
+            continue
+        if key is not None:
+            seen[key] = len(part_list)
+        begins.append(len(part_list))
+        part_list.extend(sh.parts)
+    parts = np.zeros(max(len(part_list), 1), dtype=PART_DTYPE)
+    k = len(part_list)
+    if k:
+        parts["fqn"][:k] = [p.fqn for p in part_list]
+        parts["ndim"][:k] = [len(p.global_shape) for p in part_list]
+        parts["global_shape"][:k] = [_pad(p.global_shape) for p in part_list]
+        parts["offsets"][:k] = [_pad(p.offsets) for p in part_list]
+        parts["lengths"][:k] = [_pad(p.lengths) for p in part_list]
+    n = len(layout.shards)
+    shards = np.zeros(max(n, 1), dtype=SHARD_DTYPE)
+    if n:
+        shards["part_begin"][:n] = begins
+        shards["part_count"][:n] = [len(sh.parts) for sh in layout.shards]
+        shards["flat_begin"][:n] = [sh.flat_begin for sh in layout.shards]
+        shards["flat_end"][:n] = [sh.flat_end for sh in layout.shards]
+        shards["byte_offset"][:n] = [sh.byte_offset for sh in layout.shards]
+        shards["itemsize"][:n] = [sh.itemsize for sh in layout.shards]
+        shards["buf"][:n] = [sh.buf for sh in layout.shards]
+        for i, sh in enumerate(layout.shards):
+            if sh.strides is not None:
+                shards["has_strides"][i] = 1
+                shards["strides"][i, :len(sh.strides)] = sh.strides
     return parts, shards
 
 
@@ -121,15 +125,20 @@ def _as_np(t) -> np.ndarray:
 
 
 def reshard(saved, target, src_blobs, dst_init: Optional[List] = None, poison: int = 0xA5,
-            allow_uncovered: bool = False, threads: Optional[int] = None, want_written: bool = False):
+            allow_uncovered: bool = False, threads: Optional[int] = None, want_written: bool = False,
+            only_fqns: Optional[Sequence[int]] = None, dst_inplace: Optional[List[np.ndarray]] = None):
     """Run the oracle.  saved/target: synth.Layout.  src_blobs: CPU uint8 buffers (torch or numpy).
     Returns the destination buffers as numpy uint8 arrays (bytes no target shard covers keep
-    `poison`), and with want_written also per-byte write counters."""
+    `poison`), and with want_written also per-byte write counters.  only_fqns: produce just these
+    tensors (everything else in the destination keeps its initial bytes).  dst_inplace: write into
+    these numpy buffers instead of fresh ones (large sparse checks)."""
     lib = _load()
     sparts, sshards = _marshal(saved)
     tparts, tshards = _marshal(target)
     src = [np.ascontiguousarray(_as_np(b)) for b in src_blobs]
-    if dst_init is None:
+    if dst_inplace is not None:
+        dst = dst_inplace
+    elif dst_init is None:
         dst = [np.full(n, poison, dtype=np.uint8) for n in target.buf_bytes]
     else:
         dst = [np.array(_as_np(b), copy=True) for b in dst_init]
@@ -141,9 +150,12 @@ def reshard(saved, target, src_blobs, dst_init: Optional[List] = None, poison: i
     err = ctypes.create_string_buffer(512)
     if threads is None:
         threads = min(os.cpu_count() or 1, 16)
+    only = np.array(list(only_fqns), dtype=np.int64) if only_fqns is not None else None
     rc = lib.orc_reshard(sparts.ctypes.data, sshards.ctypes.data, len(saved.shards), sp, src_sizes.ctypes.data,
                          tparts.ctypes.data, tshards.ctypes.data, len(target.shards), dp, dst_sizes.ctypes.data,
-                         wp, int(allow_uncovered), int(threads), err, len(err))
+                         wp, int(allow_uncovered), int(threads),
+                         only.ctypes.data if only is not None else None, len(only) if only is not None else 0,
+                         err, len(err))
     if rc != 0:
         raise OracleError(rc, err.value.decode())
     return (dst, written) if want_written else dst

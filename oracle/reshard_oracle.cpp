@@ -17,6 +17,7 @@
 // Parity status: pinned (tests/test_oracle_pins.py: library-slicing closed form, the paper's
 // (3,2) worked example, reassembly / round-trip / exactly-once invariants, brute force).
 // The region list of a plan has no counterpart here: many region lists are correct.
+#include <algorithm>
 #include <atomic>
 #include <cstdint>
 #include <cstdio>
@@ -203,9 +204,11 @@ void do_fqn(Job& job, int64_t fqn, const std::vector<Ref>& trefs) {
       const orc_shard& sh = job.saved.shards[r.shard];
       const orc_part& p = job.saved.parts[r.part];
       const int64_t pvol = volume(p.lengths, n);
-      for (int64_t local = 0; local < pvol; ++local) {
+      // only the elements of this part that lie inside the shard's slice of the concatenation
+      const int64_t first = std::max<int64_t>(sh.flat_begin - r.concat_pos, 0);
+      const int64_t last = std::min<int64_t>(sh.flat_end - r.concat_pos, pvol);
+      for (int64_t local = first; local < last; ++local) {
         const int64_t ci = r.concat_pos + local;  // index in the concatenation
-        if (ci < sh.flat_begin || ci >= sh.flat_end) continue;
         unravel(local, p.lengths, n, y);
         for (int d = 0; d < n; ++d) x[d] = p.offsets[d] + y[d];
         const int64_t gi = ravel(x, t0.global_shape, n);
@@ -222,9 +225,10 @@ void do_fqn(Job& job, int64_t fqn, const std::vector<Ref>& trefs) {
     const orc_shard& sh = job.target.shards[r.shard];
     const orc_part& p = job.target.parts[r.part];
     const int64_t pvol = volume(p.lengths, n);
-    for (int64_t local = 0; local < pvol; ++local) {
+    const int64_t first = std::max<int64_t>(sh.flat_begin - r.concat_pos, 0);
+    const int64_t last = std::min<int64_t>(sh.flat_end - r.concat_pos, pvol);
+    for (int64_t local = first; local < last; ++local) {
       const int64_t ci = r.concat_pos + local;
-      if (ci < sh.flat_begin || ci >= sh.flat_end) continue;
       unravel(local, p.lengths, n, y);
       for (int d = 0; d < n; ++d) x[d] = p.offsets[d] + y[d];
       const int64_t gi = ravel(x, t0.global_shape, n);
@@ -250,6 +254,7 @@ void do_fqn(Job& job, int64_t fqn, const std::vector<Ref>& trefs) {
 
 extern "C" {
 
+// only_fqns (optional, n_only entries): produce only these tensors; the rest of dst is untouched.
 // Reshard on the host.  src[i] / dst[i] are host byte buffers of src_bytes[i] / dst_bytes[i]
 // bytes.  dst_written (optional): per-byte counters the caller zeroed, incremented for every
 // byte written.  Returns ORC_OK or an error code and copies a message into err (if non-null).
@@ -259,7 +264,8 @@ int orc_reshard(const orc_part* sparts, const orc_shard* saved, int64_t n_saved,
                 const uint8_t* const* src, const int64_t* src_bytes,
                 const orc_part* tparts, const orc_shard* target, int64_t n_target,
                 uint8_t* const* dst, const int64_t* dst_bytes, uint8_t* const* dst_written,
-                int allow_uncovered, int n_threads, char* err, int err_len) {
+                int allow_uncovered, int n_threads, const int64_t* only_fqns, int64_t n_only,
+                char* err, int err_len) {
   Job job;
   job.saved = Side{sparts, saved, n_saved, {}};
   job.target = Side{tparts, target, n_target, {}};
@@ -271,7 +277,11 @@ int orc_reshard(const orc_part* sparts, const orc_shard* saved, int64_t n_saved,
   job.allow_uncovered = allow_uncovered != 0;
   if (index_side(job.saved, job.err) && index_side(job.target, job.err)) {
     std::vector<const std::pair<const int64_t, std::vector<Ref>>*> work;
-    for (auto& kv : job.target.by_fqn) work.push_back(&kv);
+    for (auto& kv : job.target.by_fqn) {
+      bool take = n_only <= 0;  // optional filter: only these tensors are produced
+      for (int64_t i = 0; i < n_only && !take; ++i) take = only_fqns[i] == kv.first;
+      if (take) work.push_back(&kv);
+    }
     std::atomic<size_t> next{0};
     auto worker = [&]() {
       for (;;) {

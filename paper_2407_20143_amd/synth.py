@@ -17,7 +17,7 @@ from __future__ import annotations
 import math
 from collections import defaultdict
 from dataclasses import dataclass, field
-from typing import Dict, List, Optional, Sequence, Tuple
+from typing import Dict, List, NamedTuple, Optional, Sequence, Tuple
 
 import numpy as np
 import torch
@@ -38,8 +38,7 @@ class TensorSpec:
     dist: Tuple  # ("uniform", lo, hi) | ("normal", mean, std) | ("normal_sq", std) | ("bits",)
 
 
-@dataclass(frozen=True)
-class Part:
+class Part(NamedTuple):
     """One box of one tensor: offsets/lengths along the axes of the global shape."""
     fqn: int
     global_shape: Tuple[int, ...]
@@ -51,7 +50,7 @@ class Part:
         return math.prod(self.lengths)
 
 
-@dataclass
+@dataclass(slots=True)
 class Shard:
     """Stored shard = elements [flat_begin, flat_end) of concat(flatten(part) for part in parts).
 
@@ -169,15 +168,19 @@ def coverage_mask(layout: Layout, tensors: Dict[int, TensorSpec], device="cpu") 
 
 
 def materialize(layout: Layout, tensors: Dict[int, TensorSpec], seed: int, device="cpu",
-                poison: Optional[int] = None) -> List[torch.Tensor]:
+                poison: Optional[int] = None, only_bufs=None) -> List[Optional[torch.Tensor]]:
     """Byte buffers of `layout` holding the seeded values (library slicing only).
 
     Applied to a saved layout this gives the source blobs; applied to a target layout it
     gives what a correct reshard must leave in the destination buffers (bytes no shard
-    covers keep `poison`, or are unspecified when poison is None).
+    covers keep `poison`, or are unspecified when poison is None).  only_bufs: build just these
+    buffers (the others come back as None) -- full-size checks go through the layout piecewise.
     """
     bufs = []
-    for n in layout.buf_bytes:
+    for i, n in enumerate(layout.buf_bytes):
+        if only_bufs is not None and i not in only_bufs:
+            bufs.append(None)
+            continue
         if poison is None:
             bufs.append(torch.zeros(n, dtype=torch.uint8, device=device))
         else:
@@ -185,6 +188,8 @@ def materialize(layout: Layout, tensors: Dict[int, TensorSpec], seed: int, devic
     by_fqn = defaultdict(list)
     groups = defaultdict(list)
     for sh in layout.shards:
+        if only_bufs is not None and sh.buf not in only_bufs:
+            continue
         if sh.group >= 0:
             groups[sh.group].append(sh)
         else:
@@ -368,32 +373,48 @@ def moe_layout(ts, ep: int, tp: int, itemsize: int, fqn_base: int = 0) -> Layout
     return lay
 
 
-def _random_shape(rng: np.random.Generator, lo: int, hi: int) -> Tuple[int, ...]:
-    n = int(rng.integers(lo, hi + 1))
-    rank = int(rng.integers(1, 4))
-    if rank == 1:
-        return (n,)
-    d0 = int(rng.integers(1, max(2, int(round(n ** 0.5)) + 1)))
-    if rank == 2:
-        return (d0, max(1, n // d0))
-    rest = max(1, n // d0)
-    d1 = int(rng.integers(1, max(2, int(round(rest ** 0.5)) + 1)))
-    return (d0, d1, max(1, rest // d1))
+def _random_shapes(rng: np.random.Generator, count: int, lo: int, hi: int) -> List[Tuple[int, ...]]:
+    """`count` shapes of rank 1..3 with about lo..hi elements (all draws vectorised)."""
+    n = rng.integers(lo, hi + 1, size=count)
+    rank = rng.integers(1, 4, size=count)
+    u0, u1 = rng.random(count), rng.random(count)
+    shapes = []
+    for i in range(count):
+        ni = int(n[i])
+        if rank[i] == 1:
+            shapes.append((ni,))
+            continue
+        d0 = 1 + int(u0[i] * max(1, int(round(ni ** 0.5))))
+        rest = max(1, ni // d0)
+        if rank[i] == 2:
+            shapes.append((d0, rest))
+            continue
+        d1 = 1 + int(u1[i] * max(1, int(round(rest ** 0.5))))
+        shapes.append((d0, d1, max(1, rest // d1)))
+    return shapes
 
 
-def _random_1d_sharding(rng: np.random.Generator, shape, max_shards: int):
-    """Cut one random dimension at sorted random points (empty shards can occur)."""
-    dim = int(rng.integers(0, len(shape)))
-    s = int(rng.integers(1, max_shards + 1))
-    cuts = sorted(int(c) for c in rng.integers(0, shape[dim] + 1, size=s - 1))
-    edges = [0] + cuts + [shape[dim]]
-    boxes = []
-    for a, b in zip(edges[:-1], edges[1:]):
-        off = [0] * len(shape)
-        ln = list(shape)
-        off[dim], ln[dim] = a, b - a
-        boxes.append((tuple(off), tuple(ln)))
-    return boxes
+def _random_1d_shardings(rng: np.random.Generator, shapes, max_shards: int):
+    """Per shape: one random dimension cut at sorted random points (empty shards can occur)."""
+    count = len(shapes)
+    udim = rng.random(count)
+    ns = rng.integers(1, max_shards + 1, size=count)
+    ucut = rng.random((count, max(max_shards - 1, 0)))
+    out = []
+    for i, shape in enumerate(shapes):
+        dim = int(udim[i] * len(shape))
+        ln_d = shape[dim]
+        k = int(ns[i]) - 1
+        cuts = sorted(int(c * (ln_d + 1)) for c in ucut[i, :k])
+        edges = [0] + cuts + [ln_d]
+        boxes = []
+        for a, b in zip(edges[:-1], edges[1:]):
+            off = [0] * len(shape)
+            ln = list(shape)
+            off[dim], ln[dim] = a, b - a
+            boxes.append((tuple(off), tuple(ln)))
+        out.append(boxes)
+    return out
 
 
 def small_tensor_case(n_tensors: int, seed: int, n_bufs: int = 64, max_shards: int = 16,
@@ -407,14 +428,18 @@ def small_tensor_case(n_tensors: int, seed: int, n_bufs: int = 64, max_shards: i
     specs: Dict[int, TensorSpec] = {}
     saved, target = Layout(), Layout()
     pks = _Packer(n_bufs, granule), _Packer(n_bufs, granule)
-    for i in range(n_tensors):
-        fqn = fqn_base + i
-        shape = _random_shape(rng, lo, hi)
-        specs[fqn] = TensorSpec(fqn, f"small.{i}", shape, dtype, ("normal", 0.0, 1.0))
-        for lay, pk, base in ((saved, pks[0], buf_base[0]), (target, pks[1], buf_base[1])):
-            for off, ln in _random_1d_sharding(rng, shape, max_shards):
-                part = Part(fqn, shape, off, ln)
-                b = int(rng.integers(0, n_bufs))
+    shapes = _random_shapes(rng, n_tensors, lo, hi)
+    for i, shape in enumerate(shapes):
+        specs[fqn_base + i] = TensorSpec(fqn_base + i, f"small.{i}", shape, dtype, ("normal", 0.0, 1.0))
+    for lay, pk, base in ((saved, pks[0], buf_base[0]), (target, pks[1], buf_base[1])):
+        shardings = _random_1d_shardings(rng, shapes, max_shards)
+        bufs = rng.integers(0, n_bufs, size=sum(len(b) for b in shardings))
+        j = 0
+        for i, boxes in enumerate(shardings):
+            for off, ln in boxes:
+                part = Part(fqn_base + i, shapes[i], off, ln)
+                b = int(bufs[j])
+                j += 1
                 lay.shards.append(regular(part, e, base + b, pk.take(b, part.volume * e)))
     saved.buf_bytes = pks[0].sizes()
     target.buf_bytes = pks[1].sizes()
