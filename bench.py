@@ -42,6 +42,11 @@ def build_case(name: str):
         return synth.cfg5(n_small=0), "MoE expert weights bf16, EP8TP2 -> EP4TP4"
     if name == "cfg5_small":
         return synth.cfg5(include_experts=False), "100k small fp32 tensors under random 1-D shardings"
+    if name.startswith("copy"):  # copy, copy_s4 (source shifted 4 bytes), copy_d4, copy_d2 ...
+        shift = int(name.split("_")[1][1:]) if "_" in name else 0
+        side = name.split("_")[1][0] if "_" in name else "s"
+        return (synth.copy_case(8 << 30, shift if side == "s" else 0, shift if side == "d" else 0),
+                "plain copy of one 8 GiB byte tensor through the reshard kernel (bandwidth ceiling)")
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -69,6 +74,9 @@ def cpu_baseline(workload: str):
     elif workload == "cfg5_small":
         case = synth.cfg5(include_experts=False, n_small=20000)
         what = "20000 of the 100000 small tensors"
+    elif workload.startswith("copy"):
+        case = synth.copy_case(1 << 30)
+        what = "1 GiB of the 8 GiB byte tensor"
     else:
         case = synth.cfg1()
         what = "the whole cfg1 workload"
@@ -117,6 +125,7 @@ def main():
         src = [b.cuda() for b in src]
     dst = [torch.empty(n, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
     torch.cuda.synchronize()
+    torch.cuda.empty_cache()  # hand the generator's temporaries back: the library allocates with hipMalloc
     t_gen = time.perf_counter() - t0
     saved_meta, target_meta = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
     payload = case.target.payload_bytes()

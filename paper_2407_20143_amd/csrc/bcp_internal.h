@@ -47,6 +47,9 @@ struct Region {
   uint32_t tiles_per_group;  // tiles per index of the leading row dimensions
   uint32_t tdim;             // kTranspose: tile edge in elements
   uint32_t tiles_b;          // kTranspose: tiles along the last dimension
+  uint32_t lead_mod;         // kRows, long rows: cut segments where the destination offset is a
+                             // multiple of this (0: offsets are aligned anyway, cut at multiples of
+                             // tile_bytes from the row start)
   uint64_t n_tiles;
 };
 

@@ -28,6 +28,7 @@ constexpr int kBlock = 256;
 constexpr int kScanItems = 4;         // items per thread in the multi-block scan
 constexpr int kSmallScanThreads = 1024;
 constexpr int64_t kSmallScanMax = 1 << 14;  // up to here one workgroup scans alone (one launch)
+constexpr uint64_t kSegmentAlign = 256;     // destination alignment of the cuts inside long rows
 
 using ull = unsigned long long;
 
@@ -457,6 +458,7 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   R->segs_per_row = 1;
   R->tdim = 0;
   R->tiles_b = 0;
+  R->lead_mod = 0;
   for (int k = 0; k < kDims; ++k) {
     R->len[k] = 1;
     R->spitch[k] = 0;
@@ -520,7 +522,15 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   for (int k = 0; k < nd - 1; ++k) groups *= (uint64_t)L[k];
   uint64_t tpg;
   if ((uint64_t)R->run_bytes >= tile_bytes) {
-    const uint64_t segs = ((uint64_t)R->run_bytes + tile_bytes - 1) / tile_bytes;
+    // Two workgroups writing parts of one cache line cost bandwidth, so segments of a long row are
+    // cut where the destination offset is a multiple of kSegmentAlign (buffers themselves are
+    // assumed at least that aligned).  Rows whose destination starts are aligned anyway need no
+    // lead-in; otherwise the first segment of a row is shorter and one more segment (possibly
+    // empty) is reserved per row.
+    uint64_t misal = (uint64_t)R->dst_base;
+    for (int k = 0; k < nd; ++k) misal |= (uint64_t)R->dpitch[k];
+    R->lead_mod = (misal % kSegmentAlign) ? kSegmentAlign : 0;
+    const uint64_t segs = ((uint64_t)R->run_bytes + (R->lead_mod ? kSegmentAlign - 1 : 0) + tile_bytes - 1) / tile_bytes;
     R->segs_per_row = (uint32_t)(segs < 0xffffffffull ? segs : 0xffffffffull);
     tpg = (segs >> 32) ? ~0ull : L0 * segs;
   } else {
@@ -669,11 +679,16 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
     t.p1 = dp;
     if ((uint64_t)R.run_bytes >= R.tile_bytes) {  // a segment of one long row
       const uint32_t row = w / R.segs_per_row, seg = w - row * R.segs_per_row;
-      const int64_t off = (int64_t)seg * R.tile_bytes;
-      so += (int64_t)row * sp + off;
-      dof += (int64_t)row * dp + off;
-      const int64_t left = R.run_bytes - off;
-      t.a = (uint32_t)(left < (int64_t)R.tile_bytes ? left : (int64_t)R.tile_bytes);
+      so += (int64_t)row * sp;
+      dof += (int64_t)row * dp;
+      const int64_t lead = R.lead_mod ? dof % (int64_t)R.lead_mod : 0;
+      int64_t begin = (int64_t)seg * R.tile_bytes - lead, end = begin + (int64_t)R.tile_bytes;
+      if (begin < 0) begin = 0;
+      if (end > R.run_bytes) end = R.run_bytes;
+      if (end < begin) end = begin;  // the spare segment of a row that did not need it
+      so += begin;
+      dof += begin;
+      t.a = (uint32_t)(end - begin);
       t.b = 1;
     } else {  // a few whole short rows
       const uint64_t L0 = nd >= 1 ? (uint64_t)R.len[nd - 1] : 1;

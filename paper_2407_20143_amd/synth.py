@@ -467,6 +467,17 @@ def cfg1(n: int = 1024, m: int = 1024, strided_target: bool = False) -> Case:
     return Case("cfg1" + ("_strided" if strided_target else ""), BASE_SEED + 1, {0: spec}, saved, target)
 
 
+def copy_case(nbytes: int = 8 << 30, src_shift: int = 0, dst_shift: int = 0) -> Case:
+    """One byte tensor saved whole and loaded whole: the reshard degenerates to a plain copy
+    (the practical bandwidth ceiling of the copy kernel).  Shifts move the shard inside its
+    buffer to give source and destination different alignments."""
+    spec = TensorSpec(0, "bytes", (nbytes,), torch.uint8, ("bits",))
+    part = Part(0, (nbytes,), (0,), (nbytes,))
+    return Case(f"copy_{src_shift}_{dst_shift}", BASE_SEED, {0: spec},
+                Layout([regular(part, 1, 0, src_shift)], [nbytes + src_shift]),
+                Layout([regular(part, 1, 0, dst_shift)], [nbytes + dst_shift]))
+
+
 def llama_case(name: str, seed: int, layers: int, hidden: int, ffn: int, vocab: int, states,
                tp_s: int, pp_s: int, tp_t: int, pp_t: int, only_target_ranks=None) -> Case:
     model = llama_tensors(layers, hidden, ffn, vocab)
