@@ -23,6 +23,31 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 
+# HBM bytes per k_reshard launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the plain
+# copy kernel of known size in the same run), per workload, with the hash of the kernel sources
+# they were taken on.  Reported as null as soon as the sources differ.
+MEASURED_TRAFFIC = {
+    "cfg3": {"bytes_per_launch": 188951094515,
+             "csrc_sha256": "d3cb3bf68f4843abe1461ab46dc58c3ca2c36a5a5f35525a218024a8e17de164"},
+}
+
+
+def csrc_sha256() -> str:
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2407_20143_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str):
+    m = MEASURED_TRAFFIC.get(workload)
+    if m is None or m["csrc_sha256"] != csrc_sha256():
+        return None
+    return m["bytes_per_launch"]
+
 
 def build_case(name: str):
     from paper_2407_20143_amd import synth
@@ -42,6 +67,14 @@ def build_case(name: str):
         return synth.cfg5(n_small=0), "MoE expert weights bf16, EP8TP2 -> EP4TP4"
     if name == "cfg5_small":
         return synth.cfg5(include_experts=False), "100k small fp32 tensors under random 1-D shardings"
+    if name == "vdit_32to64":
+        return synth.table3_vdit(32, 64), "vDiT-shaped (h1664, 48 blocks) FSDP ZeRO-2 bf16 + 3 fp32 states, 32 -> 64 ranks"
+    if name == "vdit_128to64":
+        return synth.table3_vdit(128, 64), "vDiT-shaped (h1664, 48 blocks) FSDP ZeRO-2 bf16 + 3 fp32 states, 128 -> 64 ranks"
+    if name == "tgpt_75to150":
+        return synth.table3_tgpt_group(75, 150), "tGPT-70B-shaped, one TP4/PP8 group, fp32 Adam states, DP 75 -> 150"
+    if name == "tgpt_150to75":
+        return synth.table3_tgpt_group(150, 75), "tGPT-70B-shaped, one TP4/PP8 group, fp32 Adam states, DP 150 -> 75"
     if name.startswith("copy"):  # copy, copy_s4 (source shifted 4 bytes), copy_d4, copy_d2 ...
         shift = int(name.split("_")[1][1:]) if "_" in name else 0
         side = name.split("_")[1][0] if "_" in name else "s"
@@ -77,6 +110,14 @@ def cpu_baseline(workload: str):
     elif workload.startswith("copy"):
         case = synth.copy_case(1 << 30)
         what = "1 GiB of the 8 GiB byte tensor"
+    elif workload.startswith("vdit"):
+        a, b = (int(v) for v in workload.split("_")[1].split("to"))
+        case = synth.table3_vdit(a, b, layers=3)
+        what = "3 of the 48 blocks (all four states) of the vDiT-shaped workload"
+    elif workload.startswith("tgpt"):
+        a, b = (int(v) for v in workload.split("_")[1].split("to"))
+        case = synth.table3_tgpt_group(a, b, layers=1, first_stage=False)
+        what = "one of the 10 layers of the tGPT-shaped group (three fp32 states)"
     else:
         case = synth.cfg1()
         what = "the whole cfg1 workload"
@@ -89,6 +130,11 @@ def cpu_baseline(workload: str):
     payload = case.target.payload_bytes()
     return {"value": round(2 * payload / dt / 1e9, 4), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": what, "seconds": round(dt, 2)}
+
+
+def note(msg: str):
+    """Progress line on stderr (stdout carries only the JSON result)."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
 def main():
@@ -118,6 +164,7 @@ def main():
                       threads=args.threads)
 
     case, desc = build_case(args.workload)
+    note(f"workload {args.workload}: generating inputs on the GPU")
     t0 = time.perf_counter()
     small = args.workload == "cfg5_small"
     src = synth.materialize(case.saved, case.tensors, case.seed, device="cpu" if small else "cuda")
@@ -136,6 +183,7 @@ def main():
         binding.reshard(p, src, dst, stream=stream, check_sizes=False)
         return p
 
+    note(f"inputs ready in {t_gen:.1f} s; first plan + checked reshard")
     # one checked pass first: buffer sizes against the plan's extents
     p = binding.plan(saved_meta, target_meta, stream=stream)
     binding.reshard(p, src, dst, stream=stream, check_sizes=True)
@@ -145,6 +193,7 @@ def main():
     for _ in range(args.warmup):
         step().destroy()
     torch.cuda.synchronize()
+    note(f"warm-up done; timing {args.steps} steps")
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     plan_ms = []
@@ -169,6 +218,7 @@ def main():
     value = 2 * payload / (ms_per_step * 1e-3) / 1e9
     achieved = 2 * payload / (kern_avg * 1e-3) / 1e9
 
+    note(f"timed: {ms_per_step:.3f} ms per step; ceiling copies")
     extra = {}
     if args.reshard_only:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -224,13 +274,14 @@ def main():
         "plan": {k: stats[k] for k in ("n_saved_boxes", "n_target_boxes", "n_pairs", "n_regions", "n_tiles",
                                        "n_batches", "n_transposed")},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args.workload),
                      "kernel": "k_reshard", "bytes_per_launch": 2 * payload},
         "ceiling": ceil,
         "input_generation_s": round(t_gen, 1),
     }
     out.update(extra)
     if not args.no_cpu_baseline:
+        note("CPU oracle baseline on a sample of the workload")
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out), flush=True)
 

@@ -342,6 +342,109 @@ def zero_layout(model: Sequence[_ModelTensor], states, tp: int, dp: int, replica
     return lay
 
 
+def flat_units_layout(model: Sequence[_ModelTensor], states, units: Sequence[Sequence[int]], dp: int,
+                      tp: int = 1, tp_rank: int = 0) -> Layout:
+    """FSDP / Megatron-distributed-optimizer style flat sharding: per state and per unit (a list of
+    tensor indices, e.g. one transformer block) the TP-local shards are flattened and concatenated
+    and cut evenly into `dp` slices.  One buffer per DP rank holding its slice of every unit and
+    state, back to back at 256-byte aligned offsets."""
+    pk = _Packer(dp)
+    lay = Layout()
+    gid = 0
+    for si, (_, dtype, _) in enumerate(states):
+        e = dtype.itemsize
+        for unit in units:
+            parts = []
+            for ti in unit:
+                mt = model[ti]
+                off, ln = _tp_box(mt.shape, mt.tp_dim, tp, tp_rank)
+                parts.append(Part(si * len(model) + ti, tuple(mt.shape), off, ln))
+            parts = tuple(parts)
+            n = sum(p.volume for p in parts)
+            chunk = -(-n // dp)
+            for d in range(dp):
+                a, b = min(n, d * chunk), min(n, (d + 1) * chunk)
+                lay.shards.append(Shard(parts, a, b, e, d, pk.take(d, (b - a) * e), None, gid))
+            gid += 1
+    lay.buf_bytes = pk.sizes()
+    return lay
+
+
+def dit_tensors(layers: int, hidden: int, text_dim: int = 4096) -> Tuple[List[_ModelTensor], List[List[int]]]:
+    """A video-DiT-shaped parameter list (spatial + temporal self-attention, cross-attention to
+    text, adaLN modulation, 4x MLP) and its FSDP units: one per block plus one for the rest."""
+    h = hidden
+    ts: List[_ModelTensor] = []
+    units: List[List[int]] = []
+
+    def add(unit, name, shape):
+        unit.append(len(ts))
+        ts.append(_ModelTensor(name, tuple(shape), None, 0))
+
+    root: List[int] = []
+    add(root, "x_embedder.proj.weight", (h, 16 * 2 * 2 * 2))
+    add(root, "x_embedder.proj.bias", (h,))
+    add(root, "t_embedder.mlp.0.weight", (h, 256))
+    add(root, "t_embedder.mlp.0.bias", (h,))
+    add(root, "t_embedder.mlp.2.weight", (h, h))
+    add(root, "t_embedder.mlp.2.bias", (h,))
+    add(root, "y_embedder.proj.weight", (h, text_dim))
+    add(root, "y_embedder.proj.bias", (h,))
+    for i in range(layers):
+        u: List[int] = []
+        p = f"blocks.{i}."
+        add(u, p + "adaLN_modulation.weight", (6 * h, h))
+        add(u, p + "adaLN_modulation.bias", (6 * h,))
+        for attn in ("attn", "attn_temp"):
+            add(u, p + attn + ".qkv.weight", (3 * h, h))
+            add(u, p + attn + ".qkv.bias", (3 * h,))
+            add(u, p + attn + ".proj.weight", (h, h))
+            add(u, p + attn + ".proj.bias", (h,))
+        add(u, p + "cross_attn.q.weight", (h, h))
+        add(u, p + "cross_attn.q.bias", (h,))
+        add(u, p + "cross_attn.kv.weight", (2 * h, h))
+        add(u, p + "cross_attn.kv.bias", (2 * h,))
+        add(u, p + "cross_attn.proj.weight", (h, h))
+        add(u, p + "cross_attn.proj.bias", (h,))
+        add(u, p + "mlp.fc1.weight", (4 * h, h))
+        add(u, p + "mlp.fc1.bias", (4 * h,))
+        add(u, p + "mlp.fc2.weight", (h, 4 * h))
+        add(u, p + "mlp.fc2.bias", (h,))
+        units.append(u)
+    add(root, "final_layer.adaLN_modulation.weight", (2 * h, h))
+    add(root, "final_layer.adaLN_modulation.bias", (2 * h,))
+    add(root, "final_layer.linear.weight", (16 * 2 * 2 * 2, h))
+    add(root, "final_layer.linear.bias", (16 * 2 * 2 * 2,))
+    units.append(root)
+    return ts, units
+
+
+def gpt_stage_tensors(layers: int, hidden: int, vocab: int, first_stage: bool) -> Tuple[List[_ModelTensor], List[List[int]]]:
+    """One pipeline stage of a GPT-3 style decoder (fused qkv, 4x MLP, biases, LayerNorm with bias)
+    as Megatron lays it out; a single flat unit (the distributed optimizer's buffer)."""
+    h = hidden
+    ts: List[_ModelTensor] = []
+    if first_stage:
+        ts.append(_ModelTensor("embedding.word_embeddings.weight", (vocab, h), 0, 0))
+    for i in range(layers):
+        p = f"layers.{i}."
+        ts += [
+            _ModelTensor(p + "input_layernorm.weight", (h,), None, i),
+            _ModelTensor(p + "input_layernorm.bias", (h,), None, i),
+            _ModelTensor(p + "attention.qkv.weight", (3 * h, h), 0, i),
+            _ModelTensor(p + "attention.qkv.bias", (3 * h,), 0, i),
+            _ModelTensor(p + "attention.dense.weight", (h, h), 1, i),
+            _ModelTensor(p + "attention.dense.bias", (h,), None, i),
+            _ModelTensor(p + "post_attention_layernorm.weight", (h,), None, i),
+            _ModelTensor(p + "post_attention_layernorm.bias", (h,), None, i),
+            _ModelTensor(p + "mlp.fc1.weight", (4 * h, h), 0, i),
+            _ModelTensor(p + "mlp.fc1.bias", (4 * h,), 0, i),
+            _ModelTensor(p + "mlp.fc2.weight", (h, 4 * h), 1, i),
+            _ModelTensor(p + "mlp.fc2.bias", (h,), None, i),
+        ]
+    return ts, [list(range(len(ts)))]
+
+
 def moe_tensors(layers: int, hidden: int, experts: int, ffn: int):
     """Stacked expert weights: gate, up [E, ffn, h]; down [E, h, ffn].  EP splits dim 0, TP splits
     dim 1 of gate/up and dim 2 of down."""
@@ -514,6 +617,32 @@ def cfg4(layers: int = 32, hidden: int = 4096, ffn: int = 11008, vocab: int = 32
     return Case("cfg4", BASE_SEED + 4, _specs(model, states),
                 zero_layout(model, states, 1, dp_s, replicate_norms=False),
                 zero_layout(model, states, tp_t, dp_t, replicate_norms=True))
+
+
+ADAM_FP32_STATES = [STATE_FP32_MASTER, STATE_FP32_EXP_AVG, STATE_FP32_EXP_AVG_SQ]
+
+
+def table3_vdit(dp_s: int = 32, dp_t: int = 64, layers: int = 48, hidden: int = 1664, text_dim: int = 4096) -> Case:
+    """Shaped like the paper's vDiT rows of Table 3 (hidden 1664, 48 layers, FSDP ZeRO-2, 32 -> 64 and
+    128 -> 64 GPUs): bf16 flat parameters and fp32 Adam states, one FSDP unit per block, every unit
+    cut evenly over the DP ranks.  The model itself is internal to the paper; this is a DiT-style
+    stand-in of the same width and depth (about 3.5 B parameters)."""
+    model, units = dit_tensors(layers, hidden, text_dim)
+    states = [STATE_BF16_WEIGHT] + ADAM_FP32_STATES
+    return Case(f"vdit_dp{dp_s}to{dp_t}", BASE_SEED + 6, _specs(model, states),
+                flat_units_layout(model, states, units, dp_s), flat_units_layout(model, states, units, dp_t))
+
+
+def table3_tgpt_group(dp_s: int = 75, dp_t: int = 150, layers: int = 10, hidden: int = 8192, vocab: int = 51200,
+                      tp: int = 4, first_stage: bool = True) -> Case:
+    """Shaped like the paper's tGPT 70B rows of Table 3 (hidden 8192, 80 layers, TP4 PP8, DP 75 <-> 150):
+    ONE (tp rank 0, pp stage) group -- 10 of the 80 layers, plus the vocab-parallel embedding on the
+    first stage -- whose fp32 Adam states sit in Megatron's distributed-optimizer buffer cut over the
+    DP ranks.  All target DP ranks of the group are built on one GPU (26 GB one way)."""
+    model, units = gpt_stage_tensors(layers, hidden, vocab, first_stage)
+    return Case(f"tgpt_dp{dp_s}to{dp_t}", BASE_SEED + 7, _specs(model, ADAM_FP32_STATES),
+                flat_units_layout(model, ADAM_FP32_STATES, units, dp_s, tp=tp, tp_rank=0),
+                flat_units_layout(model, ADAM_FP32_STATES, units, dp_t, tp=tp, tp_rank=0))
 
 
 def cfg5(layers: int = 16, hidden: int = 4096, experts: int = 64, ffn: int = 1408,

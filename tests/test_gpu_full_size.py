@@ -127,6 +127,62 @@ def test_cfg4_full_zero_flat_shards():
     check_oracle_sample(case, src, dst, sm, tm, [f for f in cut if case.tensors[f].shape[0] <= 4096] or cut[:1])
 
 
+def _flat_target_groups(case):
+    groups = {}
+    for sh in case.target.shards:
+        groups.setdefault(sh.group, set()).add(sh.buf)
+    return groups
+
+
+@pytest.mark.parametrize("dp", [(32, 64), (128, 64)])
+def test_table3_vdit_full(dp):
+    """vDiT-shaped FSDP ZeRO-2 reshard at full width and depth (48.6 GB one way)."""
+    case = synth.table3_vdit(*dp)
+    src, dst, sm, tm, st = reshard_on_gpu(case)
+    # every target buffer holds a slice of every unit, so the closed form is built unit by unit
+    for gid in sorted(_flat_target_groups(case))[::7]:
+        shards = [sh for sh in case.target.shards if sh.group == gid]
+        sub = synth.Layout(shards, case.target.buf_bytes)
+        want = synth.materialize(sub, case.tensors, case.seed, device="cuda", poison=POISON)
+        for sh in shards:
+            n = sh.numel * sh.itemsize
+            assert torch.equal(dst[sh.buf][sh.byte_offset:sh.byte_offset + n], want[sh.buf][sh.byte_offset:sh.byte_offset + n])
+        del want
+    sample = fqns_by_name(case, {"blocks.0.adaLN_modulation.weight", "blocks.17.attn_temp.qkv.weight.master",
+                                 "blocks.47.mlp.fc2.weight.exp_avg_sq", "blocks.30.mlp.fc1.bias.exp_avg",
+                                 "y_embedder.proj.weight.master"})
+    assert len(sample) == 5
+    check_oracle_sample(case, src, dst, sm, tm, sample)
+
+
+@pytest.mark.parametrize("dp", [(75, 150), (150, 75)])
+def test_table3_tgpt_group_full(dp):
+    """tGPT-70B-shaped: one TP/PP group's fp32 Adam states, DP 75 <-> 150 (25.4 GB one way)."""
+    case = synth.table3_tgpt_group(*dp)
+    src, dst, sm, tm, st = reshard_on_gpu(case)
+    for gid in _flat_target_groups(case):
+        shards = [sh for sh in case.target.shards if sh.group == gid]
+        sub = synth.Layout(shards, case.target.buf_bytes)
+        want = synth.materialize(sub, case.tensors, case.seed, device="cuda", poison=POISON)
+        for sh in shards:
+            n = sh.numel * sh.itemsize
+            assert torch.equal(dst[sh.buf][sh.byte_offset:sh.byte_offset + n], want[sh.buf][sh.byte_offset:sh.byte_offset + n])
+        del want
+    sample = fqns_by_name(case, {"layers.0.attention.qkv.weight.master", "layers.9.mlp.fc2.weight.exp_avg",
+                                 "layers.4.input_layernorm.bias.exp_avg_sq", "layers.6.mlp.fc1.bias.master"})
+    assert len(sample) == 4
+    check_oracle_sample(case, src, dst, sm, tm, sample)
+
+
+def test_one_region_beyond_4_gib():
+    """A single 5 GiB region: byte offsets and tile counts past 2^32."""
+    case = synth.copy_case(5 << 30, 0, 4)
+    src, dst, sm, tm, st = reshard_on_gpu(case)
+    assert st["n_regions"] == 1 and st["payload_bytes"] == 5 << 30
+    assert torch.equal(dst[0][4:], src[0])
+    assert bool((dst[0][:4] == POISON).all())
+
+
 def test_cfg5_experts_full():
     case = synth.cfg5(n_small=0)
     src, dst, sm, tm, st = reshard_on_gpu(case)

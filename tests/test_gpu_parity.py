@@ -119,6 +119,15 @@ def test_cfg5_scaled():
     check_case(synth.cfg5(layers=2, hidden=256, experts=16, ffn=88, n_small=3000))
 
 
+def test_table3_shapes_scaled():
+    """The paper's Table 3 reshards at reduced width: FSDP ZeRO-2 32 -> 64 and 128 -> 64 ranks
+    (per-block flat units), Megatron distributed optimizer DP 75 <-> 150 inside one TP/PP group."""
+    check_case(synth.table3_vdit(32, 64, layers=3, hidden=104, text_dim=200))
+    check_case(synth.table3_vdit(128, 64, layers=3, hidden=104, text_dim=200))
+    check_case(synth.table3_tgpt_group(75, 150, layers=2, hidden=256, vocab=2048))
+    check_case(synth.table3_tgpt_group(150, 75, layers=2, hidden=256, vocab=2048, first_stage=False))
+
+
 @pytest.mark.parametrize("n_bufs", [200, 700])
 def test_many_buffers(n_bufs):
     """More buffers than fit the kernel arguments (pointer table in device memory), and more than

@@ -141,7 +141,11 @@ def test_closed_form_model_shapes():
              synth.cfg3(layers=4, hidden=32, ffn=88, vocab=64),
              synth.cfg3(layers=4, hidden=32, ffn=88, vocab=64, rank_share=True),
              synth.cfg4(layers=2, hidden=24, ffn=40, vocab=52, dp_s=16, dp_t=12),
-             synth.cfg5(layers=1, hidden=16, experts=8, ffn=12, n_small=50)]
+             synth.cfg5(layers=1, hidden=16, experts=8, ffn=12, n_small=50),
+             synth.table3_vdit(8, 16, layers=2, hidden=24, text_dim=40),
+             synth.table3_vdit(16, 8, layers=2, hidden=24, text_dim=40),
+             synth.table3_tgpt_group(5, 10, layers=2, hidden=32, vocab=128),
+             synth.table3_tgpt_group(10, 5, layers=1, hidden=32, vocab=128, first_stage=False)]
     for case in cases:
         _, got = run(case)
         assert_bufs_equal(got, expect(case))
