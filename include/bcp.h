@@ -67,6 +67,8 @@ typedef enum bcp_status {
 #define BCP_PLAN_DEFAULT 0u
 #define BCP_ALLOW_UNCOVERED 1u      /* target elements without a saved source keep their bytes */
 #define BCP_SKIP_OVERLAP_CHECK 2u   /* trust the caller that saved shards are pairwise disjoint */
+#define BCP_ORDER_BY_SOURCE 4u      /* order the work by (source blob, source byte) so that it can run
+                                       while the blobs arrive: see bcp_reshard_arrived */
 
 typedef struct bcp_stats {
   int64_t n_saved_boxes;   /* regular boxes after decomposing the saved records */
@@ -135,6 +137,23 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved,
  * tables and queue counter. */
 bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src,
                        void* const* dst_buffers, int32_t n_dst, void* stream);
+
+/* Chunked arrival (the step before this path in the paper's load pipeline, Sec. 4.2: read ->
+ * deserialize -> H2D): run the part of a BCP_ORDER_BY_SOURCE plan whose LAST source byte lies in
+ * bytes [byte_begin, byte_end) of src_blobs[src_buf].  Valid once bytes [0, byte_end) of that blob
+ * are in place in stream order; calling it for consecutive chunks that cover every blob executes
+ * every region exactly once.  Other arguments and rules as bcp_reshard. */
+bcp_status bcp_reshard_arrived(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src,
+                               void* const* dst_buffers, int32_t n_dst,
+                               int32_t src_buf, int64_t byte_begin, int64_t byte_end, void* stream);
+
+/* The whole overlapped loop: blob by blob, chunk by chunk, copy host_blobs[i] (HOST memory, pinned
+ * for real overlap, blob_bytes[i] bytes) into src_blobs[i] (device) on copy_stream and run
+ * bcp_reshard_arrived for the chunk on `stream` as soon as it has landed.  Enqueues everything and
+ * returns; both streams keep their default priority.  The plan must be BCP_ORDER_BY_SOURCE. */
+bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs, const int64_t* blob_bytes,
+                                 void* const* src_blobs, int32_t n_src, void* const* dst_buffers, int32_t n_dst,
+                                 int64_t chunk_bytes, void* copy_stream, void* stream);
 
 bcp_status bcp_plan_stats(bcp_plan_t plan, bcp_stats* out);
 

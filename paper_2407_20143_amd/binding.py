@@ -39,9 +39,11 @@ REGION_INFO = np.dtype([
 BCP_OK = 0
 BCP_ALLOW_UNCOVERED = 1
 BCP_SKIP_OVERLAP_CHECK = 2
+BCP_ORDER_BY_SOURCE = 4
 
 EXPORTS = [
-    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_plan", "bcp_reshard", "bcp_plan_stats",
+    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_plan", "bcp_reshard", "bcp_reshard_arrived",
+    "bcp_reshard_from_host", "bcp_plan_stats",
     "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy", "bcp_configure", "bcp_copy_baseline", "bcp_last_error",
     "bcp_status_name", "bcp_abi_version", "bcp_sizeof_shard_meta",
 ]
@@ -70,6 +72,8 @@ def lib():
         L.bcp_decompose.argtypes = [vp, vp, ctypes.POINTER(i64)]
         L.bcp_plan.argtypes = [vp, i64, vp, i64, u32, vp, ctypes.POINTER(vp)]
         L.bcp_reshard.argtypes = [vp, vp, i32, vp, i32, vp]
+        L.bcp_reshard_arrived.argtypes = [vp, vp, i32, vp, i32, i32, i64, i64, vp]
+        L.bcp_reshard_from_host.argtypes = [vp, vp, vp, vp, i32, vp, i32, i64, vp, vp]
         L.bcp_plan_stats.argtypes = [vp, vp]
         L.bcp_plan_regions.argtypes = [vp, vp, i64, ctypes.POINTER(i64)]
         L.bcp_plan_buffer_extents.argtypes = [vp, vp, i32, vp, i32]
@@ -258,6 +262,28 @@ def reshard(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, stream=None, ch
                         raise ValueError(f"{what}[{i}] holds {have} bytes, the plan touches {int(need)}")
     _check(lib().bcp_reshard(p._h, _ptrs(src_blobs), len(src_blobs), _ptrs(dst_buffers), len(dst_buffers),
                              _stream_ptr(stream)))
+
+
+def reshard_arrived(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, src_buf: int, byte_begin: int,
+                    byte_end: int, stream=None) -> None:
+    """bcp_reshard_arrived: the work whose last source byte lies in [byte_begin, byte_end) of blob src_buf."""
+    _check(lib().bcp_reshard_arrived(p._h, _ptrs(src_blobs), len(src_blobs), _ptrs(dst_buffers), len(dst_buffers),
+                                     src_buf, byte_begin, byte_end, _stream_ptr(stream)))
+
+
+def reshard_from_host(p: Plan, host_blobs: Sequence, src_blobs: Sequence, dst_buffers: Sequence, chunk_bytes: int,
+                      copy_stream, stream=None) -> None:
+    """bcp_reshard_from_host: chunked host-to-device arrival overlapped with the reshard."""
+    sizes = (ctypes.c_int64 * max(len(host_blobs), 1))(*[b.numel() * b.element_size() for b in host_blobs])
+    for i, need in enumerate(p.buffer_extents()[0]):
+        if i >= len(host_blobs) or sizes[i] < need:
+            raise ValueError(f"host blob {i} is shorter than the {int(need)} bytes the plan reads from it")
+    for h, d in zip(host_blobs, src_blobs):
+        if d.numel() * d.element_size() < h.numel() * h.element_size():
+            raise ValueError("device blob smaller than its host blob")
+    _check(lib().bcp_reshard_from_host(p._h, _ptrs(host_blobs), sizes, _ptrs(src_blobs), len(src_blobs),
+                                       _ptrs(dst_buffers), len(dst_buffers), chunk_bytes,
+                                       _stream_ptr(copy_stream), _stream_ptr(stream)))
 
 
 def configure(tile_bytes: int = 0, persistent: int = -1, wg_per_cu: int = 0, threads: int = 0) -> None:

@@ -49,6 +49,8 @@ struct bcp_plan_s {
   bool slot_used[kSlots]{};
   int next_slot = 0;
   std::mutex mu;
+  std::vector<hipEvent_t> chunk_events;  // bcp_reshard_from_host: one per chunk in flight, reused
+  std::mutex chunk_mu;
 };
 
 extern "C" {
@@ -229,7 +231,7 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     set_error("bcp_plan: null metadata array or negative count");
     return BCP_ERR_INVALID_ARG;
   }
-  if (flags & ~(BCP_ALLOW_UNCOVERED | BCP_SKIP_OVERLAP_CHECK)) {
+  if (flags & ~(BCP_ALLOW_UNCOVERED | BCP_SKIP_OVERLAP_CHECK | BCP_ORDER_BY_SOURCE)) {
     set_error("bcp_plan: unknown flag");
     return BCP_ERR_INVALID_ARG;
   }
@@ -290,6 +292,7 @@ bcp_status bcp_plan_destroy(bcp_plan_t plan) {
   if (plan->table_host) (void)hipHostFree(plan->table_host);
   for (int i = 0; i < kSlots; ++i)
     if (plan->slot_done[i]) (void)hipEventDestroy(plan->slot_done[i]);
+  for (hipEvent_t e : plan->chunk_events) (void)hipEventDestroy(e);
   delete plan;
   return BCP_OK;
 }
@@ -364,42 +367,42 @@ bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t
 }
 
 // ---- reshard ---------------------------------------------------------------------------------
-bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
-                       int32_t n_dst, void* stream) {
+static bcp_status reshard_impl(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
+                               int32_t n_dst, void* stream, const uint64_t* key_range, const char* who) {
   if (!plan) {
-    set_error("bcp_reshard: plan is null");
+    set_error(std::string(who) + ": plan is null");
     return BCP_ERR_INVALID_ARG;
   }
   if (plan->dev.n_tiles == 0) return BCP_OK;
   if (!src_blobs || !dst_buffers || n_src < plan->n_src || n_dst < plan->n_dst) {
-    set_error("bcp_reshard: need at least " + std::to_string(plan->n_src) + " source and " +
+    set_error(std::string(who) + ": need at least " + std::to_string(plan->n_src) + " source and " +
               std::to_string(plan->n_dst) + " destination buffers");
     return BCP_ERR_INVALID_ARG;
   }
   for (int32_t i = 0; i < plan->n_src; ++i)
     if (!src_blobs[i]) {
-      set_error("bcp_reshard: src_blobs[" + std::to_string(i) + "] is null");
+      set_error(std::string(who) + ": src_blobs[" + std::to_string(i) + "] is null");
       return BCP_ERR_INVALID_ARG;
     }
   for (int32_t i = 0; i < plan->n_dst; ++i)
     if (!dst_buffers[i]) {
-      set_error("bcp_reshard: dst_buffers[" + std::to_string(i) + "] is null");
+      set_error(std::string(who) + ": dst_buffers[" + std::to_string(i) + "] is null");
       return BCP_ERR_INVALID_ARG;
     }
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) {
-    set_error("bcp_reshard: the plan belongs to another device");
+    set_error(std::string(who) + ": the plan belongs to another device");
     return BCP_ERR_INVALID_ARG;
   }
   hipStream_t st = (hipStream_t)stream;
   if (plan->n_src + plan->n_dst <= kMaxKernargPtrs)
-    return launch_reshard(plan->dev, src_blobs, plan->n_src, dst_buffers, plan->n_dst, nullptr, st);
+    return launch_reshard(plan->dev, src_blobs, plan->n_src, dst_buffers, plan->n_dst, nullptr, st, key_range);
   std::lock_guard<std::mutex> g(plan->mu);
   if (!plan->table_dev) {
     hipError_t e = hipMalloc(&plan->table_dev, plan->table_bytes);
     if (e == hipSuccess) e = hipHostMalloc((void**)&plan->table_host, plan->table_bytes * kSlots, hipHostMallocDefault);
     for (int i = 0; i < kSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&plan->slot_done[i], hipEventDisableTiming);
-    if (e != hipSuccess) return hip_fail(e, "bcp_reshard: pointer table allocation");
+    if (e != hipSuccess) return hip_fail(e, "pointer table allocation");
   }
   const int slot = plan->next_slot;
   plan->next_slot = (slot + 1) % kSlots;
@@ -410,7 +413,78 @@ bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_
   BCP_HIP(hipMemcpyAsync(plan->table_dev, h, plan->table_bytes, hipMemcpyHostToDevice, st));
   BCP_HIP(hipEventRecord(plan->slot_done[slot], st));
   plan->slot_used[slot] = true;
-  return launch_reshard(plan->dev, nullptr, plan->n_src, nullptr, plan->n_dst, plan->table_dev, st);
+  return launch_reshard(plan->dev, nullptr, plan->n_src, nullptr, plan->n_dst, plan->table_dev, st, key_range);
+}
+
+bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
+                       int32_t n_dst, void* stream) {
+  return reshard_impl(plan, src_blobs, n_src, dst_buffers, n_dst, stream, nullptr, "bcp_reshard");
+}
+
+bcp_status bcp_reshard_arrived(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
+                               int32_t n_dst, int32_t src_buf, int64_t byte_begin, int64_t byte_end, void* stream) {
+  if (src_buf < 0 || byte_begin < 0 || byte_end < byte_begin || (byte_end >> kKeyShift)) {
+    set_error("bcp_reshard_arrived: bad source range");
+    return BCP_ERR_INVALID_ARG;
+  }
+  if (plan && plan->dev.n_tiles && !plan->dev.batch_key) {
+    set_error("bcp_reshard_arrived: the plan was not built with BCP_ORDER_BY_SOURCE");
+    return BCP_ERR_INVALID_ARG;
+  }
+  const uint64_t range[2] = {((uint64_t)src_buf << kKeyShift) | (uint64_t)byte_begin,
+                             ((uint64_t)src_buf << kKeyShift) | (uint64_t)byte_end};
+  return reshard_impl(plan, src_blobs, n_src, dst_buffers, n_dst, stream, range, "bcp_reshard_arrived");
+}
+
+bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs, const int64_t* blob_bytes,
+                                 void* const* src_blobs, int32_t n_src, void* const* dst_buffers, int32_t n_dst,
+                                 int64_t chunk_bytes, void* copy_stream, void* stream) {
+  if (!plan || !host_blobs || !blob_bytes || chunk_bytes <= 0) {
+    set_error("bcp_reshard_from_host: bad argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  if (copy_stream == stream) {
+    set_error("bcp_reshard_from_host: the copy stream and the reshard stream must differ");
+    return BCP_ERR_INVALID_ARG;
+  }
+  if (plan->dev.n_tiles == 0) return BCP_OK;
+  hipStream_t cs = (hipStream_t)copy_stream;
+  hipStream_t st = (hipStream_t)stream;
+  // the copy stream starts after whatever the reshard stream has queued (buffers may still be in use)
+  hipEvent_t ev;
+  std::vector<hipEvent_t>& pool = plan->chunk_events;
+  size_t used = 0;
+  auto next_event = [&](hipEvent_t* out) -> hipError_t {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      hipError_t rc = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+      if (rc != hipSuccess) return rc;
+      pool.push_back(e);
+    }
+    *out = pool[used++];
+    return hipSuccess;
+  };
+  std::lock_guard<std::mutex> g(plan->chunk_mu);
+  BCP_HIP(next_event(&ev));
+  BCP_HIP(hipEventRecord(ev, st));
+  BCP_HIP(hipStreamWaitEvent(cs, ev, 0));
+  for (int32_t b = 0; b < plan->n_src && b < n_src; ++b) {
+    if (blob_bytes[b] < 0 || (blob_bytes[b] > 0 && (!host_blobs[b] || !src_blobs || !src_blobs[b]))) {
+      set_error("bcp_reshard_from_host: blob " + std::to_string(b) + " has no host or device buffer");
+      return BCP_ERR_INVALID_ARG;
+    }
+    for (int64_t off = 0; off < blob_bytes[b]; off += chunk_bytes) {
+      const int64_t n = std::min(chunk_bytes, blob_bytes[b] - off);
+      BCP_HIP(hipMemcpyAsync((char*)src_blobs[b] + off, (const char*)host_blobs[b] + off, (size_t)n,
+                             hipMemcpyHostToDevice, cs));
+      BCP_HIP(next_event(&ev));
+      BCP_HIP(hipEventRecord(ev, cs));
+      BCP_HIP(hipStreamWaitEvent(st, ev, 0));
+      // everything whose last source byte lies in this chunk can go now
+      if (bcp_status s = bcp_reshard_arrived(plan, src_blobs, n_src, dst_buffers, n_dst, b, off, off + n, stream)) return s;
+    }
+  }
+  return BCP_OK;
 }
 
 bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream) {

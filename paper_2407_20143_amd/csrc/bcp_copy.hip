@@ -258,6 +258,9 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
   __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
   __shared__ uint64_t lds_ptrs[kLdsPtrs];
   __shared__ uint32_t slot[2];
+  // ranged launch (a chunk of a source blob has arrived): the lookup kernel left the first batch in
+  // the queue word and one past the last batch in queue[3]
+  if (persistent == 2) n_batches = (uint32_t)queue[3];
   const bool ptrs_in_lds = n_ptrs <= (uint32_t)kLdsPtrs;
   if (ptrs_in_lds)
     for (uint32_t i = threadIdx.x; i < n_ptrs; i += blockDim.x) lds_ptrs[i] = ptr_table[i];
@@ -341,6 +344,27 @@ __global__ __launch_bounds__(kMaxThreads) void k_reshard_table(const TileDesc* _
   reshard_body(heads, n_batches, tiles, ptr_table, n_src, n_ptrs, queue, persistent);
 }
 
+// Batches of a source-ordered plan whose key lies in [key_lo, key_hi): the queue starts at the
+// first of them, queue[3] is one past the last.
+__global__ void k_range_lookup(const uint64_t* __restrict__ batch_key, uint32_t n_batches, uint64_t key_lo,
+                               uint64_t key_hi, unsigned long long* queue) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  uint32_t bound[2];
+  const uint64_t want[2] = {key_lo, key_hi};
+  for (int k = 0; k < 2; ++k) {
+    uint32_t lo = 0, hi = n_batches;
+    while (lo < hi) {
+      const uint32_t mid = lo + ((hi - lo) >> 1);
+      if (batch_key[mid] < want[k]) lo = mid + 1; else hi = mid;
+    }
+    bound[k] = lo;
+  }
+  queue[0] = bound[0];
+  queue[1] = 0;
+  queue[2] = bound[0];
+  queue[3] = bound[1];
+}
+
 __global__ __launch_bounds__(256) void k_copy_baseline(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
                                                        uint64_t n_vec, uint32_t vec_per_block) {
   const uint64_t base = (uint64_t)blockIdx.x * vec_per_block;
@@ -368,9 +392,19 @@ int device_cu_count() {
 // src/dst: host arrays of device pointers when the table fits the kernel arguments
 // (n_src + n_dst <= kMaxKernargPtrs), else `table` is a device array [src pointers | dst pointers].
 bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
-                          int32_t n_dst, const void* table, hipStream_t stream) {
+                          int32_t n_dst, const void* table, hipStream_t stream, const uint64_t* key_range) {
   if (plan.n_batches == 0) return BCP_OK;
-  const PlanConfig cfg = config();
+  PlanConfig cfg = config();
+  if (key_range) {
+    if (!plan.batch_key) {
+      set_error("the plan was not built with BCP_ORDER_BY_SOURCE");
+      return BCP_ERR_INVALID_ARG;
+    }
+    hipLaunchKernelGGL(k_range_lookup, dim3(1), dim3(64), 0, stream, plan.batch_key, (uint32_t)plan.n_batches,
+                       key_range[0], key_range[1], plan.queue);
+    BCP_HIP(hipGetLastError());
+    cfg.persistent = 2;  // the range is only known on the device: always the queue-driven grid
+  }
   unsigned grid;
   if (cfg.persistent) {
     const int cus = device_cu_count();

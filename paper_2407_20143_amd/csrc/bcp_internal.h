@@ -75,6 +75,7 @@ struct TileDesc {
 };
 static_assert(sizeof(TileDesc) == 64, "one tile descriptor per 64-byte line");
 
+constexpr int kKeyShift = 44;                    // source-order key: buffer index above, byte offset below
 constexpr uint32_t kSmallTileBytes = 16 * 1024;  // tiles below this may share a batch
 constexpr uint32_t kMinBatchWeight = 256;        // a tile counts at least this much: <= budget/256 tiles per batch
 
@@ -89,6 +90,7 @@ struct Ctl {
   unsigned long long n_transposed;
   long long max_src_buf, max_dst_buf;
   unsigned long long dims_hist[kDims + 1];
+  unsigned long long max_src_end;  // one past the highest source byte offset any region reads
 };
 
 // device error codes carried in err_key's low byte (mapped to bcp_status on the host)
@@ -124,7 +126,8 @@ struct PlanDevice {
   Region* regions = nullptr;
   TileDesc* tiles = nullptr;
   TileDesc* heads = nullptr;  // one per batch; heads, tiles and queue share one allocation
-  unsigned long long* queue = nullptr;  // [next batch, finished workgroups], zero between launches
+  unsigned long long* queue = nullptr;  // [next batch, finished workgroups, range begin, range end]
+  uint64_t* batch_key = nullptr;        // source-ordered plans: (src_buf << kKeyShift | last source byte) per batch
   int64_t n_regions = 0;
   int64_t n_tiles = 0;
   int64_t n_batches = 0;
@@ -143,7 +146,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
 // ---- copy (bcp_copy.hip) ---------------------------------------------------------------------
 constexpr int kMaxKernargPtrs = 256;  // buffer pointers that travel as kernel arguments
 bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
-                          int32_t n_dst, const void* table, hipStream_t stream);
+                          int32_t n_dst, const void* table, hipStream_t stream,
+                          const uint64_t* key_range = nullptr);
 bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream);
 int device_cu_count();
 

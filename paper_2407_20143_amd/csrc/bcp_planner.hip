@@ -547,7 +547,7 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
 // plan statistics are summed per workgroup in LDS first: one global atomic per counter and
 // workgroup instead of one per region
 struct BlockStats {
-  ull payload, transposed, dims[kDims + 1];
+  ull payload, transposed, dims[kDims + 1], src_end;
   long long max_src, max_dst;
 };
 
@@ -566,6 +566,7 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
     bs.payload = bs.transposed = 0;
     for (int k = 0; k <= kDims; ++k) bs.dims[k] = 0;
     bs.max_src = bs.max_dst = -1;
+    bs.src_end = 0;
   }
   const uint64_t p = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   bool hit = false;
@@ -603,6 +604,9 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
     atomicAdd(&bs.payload, (ull)vol * (ull)tb->itemsize);
     atomicAdd(&bs.dims[R.ndim + (R.kind == kRows && R.run_bytes > tb->itemsize ? 1 : 0)], 1ull);
     if (R.kind == kTranspose) atomicAdd(&bs.transposed, 1ull);
+    ull send = (ull)(R.src_base + R.run_bytes);
+    for (int k = 0; k < R.ndim; ++k) send += (ull)((R.len[k] - 1) * R.spitch[k]);
+    atomicMax(&bs.src_end, send);
     atomicMax(&bs.max_src, (long long)R.src_buf);
     atomicMax(&bs.max_dst, (long long)R.dst_buf);
     if (R.n_tiles == ~0ull) report(ctl, 0, kErrInvalid);
@@ -613,6 +617,7 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
     if (bs.transposed) atomicAdd(&ctl->n_transposed, bs.transposed);
     for (int k = 0; k <= kDims; ++k)
       if (bs.dims[k]) atomicAdd(&ctl->dims_hist[k], bs.dims[k]);
+    atomicMax(&ctl->max_src_end, bs.src_end);
     atomicMax(&ctl->max_src_buf, bs.max_src);
     atomicMax(&ctl->max_dst_buf, bs.max_dst);
   }
@@ -709,25 +714,56 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
 
 // Pass A, one thread per tile: its region (binary search in the scanned tile counts) and what it
 // counts towards a batch budget: 0 for big tiles, which are batches of their own.
+// key (optional): source-order sort key, (source buffer, last source byte the tile reads).
 __global__ __launch_bounds__(kBlock) void k_tile_weights(const uint64_t* tile_start, const Region* regions,
                                                          int64_t n_regions, uint64_t n_tiles, uint32_t* tile_region,
-                                                         uint64_t* weight) {
+                                                         uint32_t* tile_local, uint64_t* weight, uint64_t* key,
+                                                         uint32_t* order) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
   const int64_t r = upper_bound_u64(tile_start, n_regions + 1, i) - 1;
   tile_region[i] = (uint32_t)r;
-  const uint64_t bytes = decode_tile(regions[r], (uint32_t)(i - tile_start[r]), nullptr);
+  tile_local[i] = (uint32_t)(i - tile_start[r]);
+  TileDesc t;
+  const uint64_t bytes = decode_tile(regions[r], (uint32_t)(i - tile_start[r]), &t);
   weight[i] = bytes >= kSmallTileBytes ? 0 : (bytes > kMinBatchWeight ? bytes : (uint64_t)kMinBatchWeight);
+  if (key) {
+    uint64_t last = (uint64_t)t.src_off;
+    if ((t.kind & 0xffu) == kTranspose) {
+      const uint64_t e = (t.kind >> 8) & 0xffu;
+      last += (uint64_t)(t.a ? t.a - 1 : 0) * e + (uint64_t)(t.b ? t.b - 1 : 0) * (uint64_t)t.p0 + (e ? e - 1 : 0);
+    } else if (bytes) {
+      last += (uint64_t)(t.b - 1) * (uint64_t)t.p0 + t.a - 1;
+    }
+    key[i] = ((uint64_t)t.src_buf << kKeyShift) | last;
+    order[i] = (uint32_t)i;
+  }
+}
+
+// source-ordered plans: bring the per-tile arrays into sorted order
+__global__ __launch_bounds__(kBlock) void k_gather_tiles(const uint32_t* order, uint64_t n_tiles,
+                                                         const uint32_t* region_in, const uint32_t* local_in,
+                                                         const uint64_t* weight_in, uint32_t* region_out,
+                                                         uint32_t* local_out, uint64_t* weight_out) {
+  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_tiles) return;
+  const uint32_t o = order[i];
+  region_out[i] = region_in[o];
+  local_out[i] = local_in[o];
+  weight_out[i] = weight_in[o];
 }
 
 // A batch starts at tile i when i is big, follows a big tile, or the running weight of the small
 // tiles crosses a multiple of the batch budget.  wprefix: exclusive scan of weight.
+// key (optional, sorted): a batch never spans two source buffers.
 __global__ __launch_bounds__(kBlock) void k_batch_flags(const uint64_t* weight, const uint64_t* wprefix,
-                                                        uint64_t n_tiles, uint32_t budget, uint32_t* flags) {
+                                                        uint64_t n_tiles, uint32_t budget, const uint64_t* key,
+                                                        uint32_t* flags) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
   uint32_t f = 1;
   if (i > 0 && weight[i] != 0 && weight[i - 1] != 0) f = (wprefix[i] / budget) != (wprefix[i - 1] / budget);
+  if (key && i > 0 && (key[i] >> kKeyShift) != (key[i - 1] >> kKeyShift)) f = 1;
   flags[i] = f;
 }
 
@@ -745,18 +781,24 @@ __global__ __launch_bounds__(kBlock) void k_batch_starts(const uint32_t* batch_i
 
 // Pass B, one thread per tile: the decoded descriptor goes to heads[batch] when the tile opens a
 // batch and to tiles[i] when it is small (members of multi-tile batches are fetched from there).
-__global__ __launch_bounds__(kBlock) void k_fill_tiles(const uint64_t* tile_start, const Region* regions,
-                                                       const uint32_t* tile_region, const uint64_t* weight,
+// key / batch_key (optional, source-ordered plans): batch_key[b] = key of the batch's last tile,
+// the largest in the batch.
+__global__ __launch_bounds__(kBlock) void k_fill_tiles(const Region* regions, const uint32_t* tile_region,
+                                                       const uint32_t* tile_local, const uint64_t* weight,
                                                        const uint32_t* batch_id, const uint32_t* bstart,
-                                                       uint64_t n_tiles, TileDesc* tiles, TileDesc* heads) {
+                                                       uint64_t n_tiles, TileDesc* tiles, TileDesc* heads,
+                                                       const uint64_t* key, uint64_t* batch_key) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
-  const uint32_t r = tile_region[i];
   const bool opens = batch_id[i + 1] != batch_id[i];
   const bool small = weight[i] != 0;
+  if (key && (i + 1 == n_tiles || batch_id[i + 2] != batch_id[i + 1])) {
+    // tile i closes its batch (the next tile opens one, or there is none)
+    batch_key[batch_id[i + 1] - 1] = key[i];
+  }
   if (!opens && !small) return;
   TileDesc t;
-  decode_tile(regions[r], (uint32_t)(i - tile_start[r]), &t);
+  decode_tile(regions[tile_region[i]], tile_local[i], &t);
   t.first = (uint32_t)i;
   if (small) tiles[i] = t;
   if (opens) {
@@ -970,32 +1012,81 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     TileDesc* tiles = nullptr;
     uint32_t n_batches = 0;
     if (n_tiles > 0) {
-      BCP_HIP(hipMalloc(&owned.p[1], sizeof(TileDesc) * 2 * (size_t)n_tiles + 64));
+      const bool by_source = (flags & BCP_ORDER_BY_SOURCE) != 0;
+      // one allocation: heads | tiles | queue words | (source-ordered plans) one key per batch
+      const size_t desc_bytes = sizeof(TileDesc) * 2 * (size_t)n_tiles;
+      BCP_HIP(hipMalloc(&owned.p[1], desc_bytes + 64 + (by_source ? sizeof(uint64_t) * (size_t)n_tiles : 0)));
       heads = (TileDesc*)owned.p[1];
       tiles = heads + n_tiles;
       out->dev.queue = (unsigned long long*)(tiles + n_tiles);
+      out->dev.batch_key = by_source ? (uint64_t*)((char*)owned.p[1] + desc_bytes + 64) : nullptr;
       BCP_HIP(hipMemsetAsync(out->dev.queue, 0, 64, st));
       uint64_t* weight = nullptr;
       uint64_t* wprefix = nullptr;
       uint32_t* tile_region = nullptr;
+      uint32_t* tile_local = nullptr;
       uint32_t* bflags = nullptr;
       uint32_t* bstart = nullptr;
+      uint64_t* key = nullptr;
+      uint32_t* order = nullptr;
       BCP_HIP(ws.alloc(&weight, (size_t)n_tiles));
       BCP_HIP(ws.alloc(&wprefix, (size_t)n_tiles + 1));
       BCP_HIP(ws.alloc(&tile_region, (size_t)n_tiles));
-      BCP_HIP(ws.alloc(&bflags, (size_t)n_tiles + 1));
+      BCP_HIP(ws.alloc(&tile_local, (size_t)n_tiles));
+      BCP_HIP(ws.alloc(&bflags, (size_t)n_tiles + 2));
       BCP_HIP(ws.alloc(&bstart, (size_t)n_tiles + 1));
+      if (by_source) {
+        BCP_HIP(ws.alloc(&key, (size_t)n_tiles));
+        BCP_HIP(ws.alloc(&order, (size_t)n_tiles));
+      }
       const unsigned nblk = blocks_for((int64_t)n_tiles + 1);
       hipLaunchKernelGGL(k_tile_weights, dim3(nblk), dim3(kBlock), 0, st, tile_start, regions, (int64_t)n_regions,
-                         n_tiles, tile_region, weight);
+                         n_tiles, tile_region, tile_local, weight, key, order);
       BCP_HIP(hipGetLastError());
+      if (by_source) {
+        // sort the tiles by (source buffer, last source byte): the plan can then run as blobs arrive
+        if (h.max_src_end >> kKeyShift) {
+          set_error("BCP_ORDER_BY_SOURCE: source offsets beyond 2^44 bytes");
+          return BCP_ERR_INVALID_ARG;
+        }
+        uint64_t *key_b = nullptr, *w2 = nullptr;
+        uint32_t *order_b = nullptr, *hist = nullptr, *r2 = nullptr, *l2 = nullptr;
+        const unsigned nb = blocks_for((int64_t)n_tiles);
+        BCP_HIP(ws.alloc(&key_b, (size_t)n_tiles));
+        BCP_HIP(ws.alloc(&order_b, (size_t)n_tiles));
+        BCP_HIP(ws.alloc(&hist, (size_t)16 * nb + 1));
+        BCP_HIP(ws.alloc(&r2, (size_t)n_tiles));
+        BCP_HIP(ws.alloc(&l2, (size_t)n_tiles));
+        BCP_HIP(ws.alloc(&w2, (size_t)n_tiles));
+        const uint64_t max_key = ((uint64_t)(h.max_src_buf < 0 ? 0 : h.max_src_buf) << kKeyShift) | (h.max_src_end ? h.max_src_end - 1 : 0);
+        int bits = 0;
+        while (bits < 64 && (max_key >> bits) != 0) ++bits;
+        // low bits: byte offsets; then jump straight to the buffer-index bits
+        int off_bits = 0;
+        while (off_bits < kKeyShift && (h.max_src_end >> off_bits) != 0) ++off_bits;
+        for (int shift = 0; shift < bits; shift += 4) {
+          if (shift >= off_bits && shift + 4 <= kKeyShift) continue;  // all-zero digits
+          hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(kBlock), 0, st, key, (int64_t)n_tiles, shift, hist, nb);
+          BCP_HIP(hipGetLastError());
+          if (bcp_status s = device_scan<uint32_t, uint32_t>(hist, hist, (int64_t)16 * nb, ws, st)) return s;
+          hipLaunchKernelGGL(k_radix_scatter, dim3(nb), dim3(kBlock), 0, st, key, order, (int64_t)n_tiles, shift, hist, nb, key_b, order_b);
+          BCP_HIP(hipGetLastError());
+          std::swap(key, key_b);
+          std::swap(order, order_b);
+        }
+        hipLaunchKernelGGL(k_gather_tiles, dim3(nb), dim3(kBlock), 0, st, order, n_tiles, tile_region, tile_local, weight, r2, l2, w2);
+        BCP_HIP(hipGetLastError());
+        tile_region = r2;
+        tile_local = l2;
+        weight = w2;
+      }
       if (bcp_status s = device_scan<uint64_t, uint64_t>(weight, wprefix, (int64_t)n_tiles, ws, st)) return s;
-      hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes, bflags);
+      hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes, key, bflags);
       BCP_HIP(hipGetLastError());
       if (bcp_status s = device_scan<uint32_t, uint32_t>(bflags, bflags, (int64_t)n_tiles, ws, st)) return s;
       hipLaunchKernelGGL(k_batch_starts, dim3(nblk), dim3(kBlock), 0, st, bflags, n_tiles, bstart);
-      hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, tile_start, regions, tile_region, weight,
-                         bflags, bstart, n_tiles, tiles, heads);
+      hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, regions, tile_region, tile_local, weight,
+                         bflags, bstart, n_tiles, tiles, heads, key, out->dev.batch_key);
       BCP_HIP(hipGetLastError());
       BCP_HIP(hipMemcpyAsync(&n_batches, bflags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     }

@@ -136,6 +136,71 @@ def test_many_buffers(n_bufs):
     check_case(Case(f"many{n_bufs}", 77, specs, saved, target))
 
 
+# ---- chunked arrival: source-ordered plans -----------------------------------------------------------
+def _arrival_cases():
+    return [synth.cfg2(layers=2, hidden=512, ffn=1376, vocab=3000),
+            synth.cfg4(layers=2, hidden=136, ffn=344, vocab=1000, dp_s=16, dp_t=12, n_states=1),
+            synth.random_case(600, n_tensors=10, max_elems=60000, saved_mode="grid", target_mode="flat", p_strided=0.3,
+                              granules=(4, 16)),
+            synth.cfg5(layers=1, hidden=128, experts=8, ffn=44, n_small=800)]
+
+
+@pytest.mark.parametrize("idx", range(4))
+def test_source_ordered_plan_runs_as_chunks_arrive(idx):
+    """Every chunk call may only touch source bytes below the chunk's end: the device blobs hold
+    garbage until 'their' chunk lands, and the final result must still be the oracle's."""
+    case = _arrival_cases()[idx]
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    p = binding.plan(sm, tm, flags=binding.BCP_ORDER_BY_SOURCE)
+    # (a) an ordered plan is still a complete plan
+    dsrc = [b.cuda() for b in src]
+    ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    binding.reshard(p, dsrc, ddst)
+    torch.cuda.synchronize()
+    assert_same([t.cpu().numpy() for t in ddst], want, case.name + " ordered plan, one launch")
+    # (b) chunk by chunk, blobs in a shuffled order, odd chunk sizes
+    rng = np.random.default_rng(idx)
+    dsrc = [torch.full((b.numel(),), 0x3C, dtype=torch.uint8, device="cuda") for b in src]
+    ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    for b in rng.permutation(len(src)):
+        n, off = src[b].numel(), 0
+        while off < n:
+            step = int(rng.integers(1, max(2, n // 3)))
+            end = min(n, off + step)
+            dsrc[b][off:end] = src[b][off:end].cuda()
+            binding.reshard_arrived(p, dsrc, ddst, int(b), off, end)
+            off = end
+    torch.cuda.synchronize()
+    assert_same([t.cpu().numpy() for t in ddst], want, case.name + " chunked arrival")
+    p.destroy()
+
+
+def test_reshard_from_pinned_host_blobs():
+    case = synth.cfg3(layers=2, hidden=256, ffn=688, vocab=2000)
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    p = binding.plan(binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target),
+                     flags=binding.BCP_ORDER_BY_SOURCE)
+    host = [b.pin_memory() for b in src]
+    copy_stream = torch.cuda.Stream()
+    for chunk in (1 << 12, 100_000, 1 << 30):
+        dsrc = [torch.full((b.numel(),), 0x3C, dtype=torch.uint8, device="cuda") for b in src]
+        ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+        torch.cuda.synchronize()
+        binding.reshard_from_host(p, host, dsrc, ddst, chunk, copy_stream)
+        torch.cuda.synchronize()
+        assert_same([t.cpu().numpy() for t in ddst], want, f"from host, chunk {chunk}")
+        assert all(torch.equal(d.cpu(), s) for d, s in zip(dsrc, src))
+    # a plan without the ordering flag refuses ranged execution
+    q = binding.plan(binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target))
+    with pytest.raises(binding.BcpError):
+        binding.reshard_arrived(q, dsrc, ddst, 0, 0, 16)
+    q.destroy()
+    p.destroy()
+
+
 def test_round_trip_on_gpu():
     case = synth.random_case(400, n_tensors=8, max_elems=20000, saved_mode="flat", target_mode="grid")
     src = synth.materialize(case.saved, case.tensors, case.seed, poison=POISON)
