@@ -132,6 +132,51 @@ def cpu_baseline(workload: str):
             "sample": what, "seconds": round(dt, 2)}
 
 
+def from_host_leg(binding, saved_meta, target_meta, src, dst, chunk_bytes, payload):
+    """Saved blobs start in pinned host memory.  (1) copy them all, then reshard; (2) copy chunk by
+    chunk on a copy stream while a source-ordered plan reshards what has arrived."""
+    import torch
+    note("pinning host copies of the saved blobs")
+    host = [b.cpu().pin_memory() for b in src]
+    stage = [torch.empty_like(b) for b in src]
+    copy_stream = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    p_seq = binding.plan(saved_meta, target_meta, stream=main)
+    p_ord = binding.plan(saved_meta, target_meta, flags=binding.BCP_ORDER_BY_SOURCE, stream=main)
+    total_src = sum(b.numel() for b in src)
+
+    def h2d_only():
+        for h, d in zip(host, stage):
+            d.copy_(h, non_blocking=True)
+
+    def sequential():
+        h2d_only()
+        binding.reshard(p_seq, stage, dst, stream=main, check_sizes=False)
+
+    def pipelined():
+        binding.reshard_from_host(p_ord, host, stage, dst, chunk_bytes, copy_stream, stream=main)
+
+    out = {"chunk_MiB": chunk_bytes >> 20, "host_bytes": total_src,
+           "ordered_plan_ms": round(p_ord.stats()["plan_wall_ms"], 3), "plain_plan_ms": round(p_seq.stats()["plan_wall_ms"], 3)}
+    for name, fn in (("h2d_only", h2d_only), ("copy_then_reshard", sequential), ("pipelined", pipelined)):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3)
+        out[name + "_ms"] = round(min(ts), 3)
+    out["h2d_GBps"] = round(total_src / out["h2d_only_ms"] / 1e6, 2)
+    out["pipelined_payload_GBps"] = round(payload / out["pipelined_ms"] / 1e6, 2)
+    out["tail_after_last_byte_ms"] = {"copy_then_reshard": round(out["copy_then_reshard_ms"] - out["h2d_only_ms"], 3),
+                                      "pipelined": round(out["pipelined_ms"] - out["h2d_only_ms"], 3)}
+    p_seq.destroy()
+    p_ord.destroy()
+    return out
+
+
 def note(msg: str):
     """Progress line on stderr (stdout carries only the JSON result)."""
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
@@ -148,6 +193,9 @@ def main():
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--from-host", type=int, default=0, metavar="CHUNK_MIB",
+                    help="also time the chunked host-to-HBM arrival overlapped with the reshard (pinned host copies "
+                         "of the saved blobs, chunks of this many MiB) against copy-then-reshard")
     ap.add_argument("--reshard-only", action="store_true",
                     help="extra timing loop of bcp_reshard alone on a prebuilt plan (reported beside the step numbers)")
     args = ap.parse_args()
@@ -228,6 +276,9 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         extra["reshard_only_ms"] = round(e0.elapsed_time(e1) / args.steps, 4)
+
+    if args.from_host:
+        extra["from_host"] = from_host_leg(binding, saved_meta, target_meta, src, dst, args.from_host << 20, payload)
 
     # practical ceiling: a plain streaming copy of the same launch shape, and the runtime's own D2D copy
     n_copy = min(max(b.numel() for b in src), max(b.numel() for b in dst)) // 16 * 16
