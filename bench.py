@@ -75,6 +75,8 @@ def build_case(name: str):
         return synth.table3_tgpt_group(75, 150), "tGPT-70B-shaped, one TP4/PP8 group, fp32 Adam states, DP 75 -> 150"
     if name == "tgpt_150to75":
         return synth.table3_tgpt_group(150, 75), "tGPT-70B-shaped, one TP4/PP8 group, fp32 Adam states, DP 150 -> 75"
+    if name == "fused_qkv":
+        return synth.fused_qkv_case(), "fused GQA QKV blobs (32 layers, h4096, 32q/8kv heads) TP4 -> separate q,k,v TP2"
     if name.startswith("copy"):  # copy, copy_s4 (source shifted 4 bytes), copy_d4, copy_d2 ...
         shift = int(name.split("_")[1][1:]) if "_" in name else 0
         side = name.split("_")[1][0] if "_" in name else "s"

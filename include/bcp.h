@@ -118,6 +118,20 @@ bcp_status bcp_meta_from_flat_slice(const bcp_shard_meta* params_in_order, int64
  * Sec. 3.2 "Decomposing irregular tensors": an irregular shard becomes a series of regular ones. */
 bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, int64_t* inout_n);
 
+/* Save-side deduplication (Sec. 4.1 "Balancing saving workload"): under data parallelism the
+ * same shard lives on several ranks; each must be saved by exactly one of them, and the savers are
+ * chosen Worst-Fit so that the bytes to save are spread evenly.  recs[i] (host) is held by rank
+ * rank_of[i] in [0, n_ranks).  Records with equal fqn_id, ndim, itemsize, offsets, lengths and flat
+ * range are replicas of one shard.  The distinct shards are taken in order of first appearance; each
+ * goes to the holder with the fewest bytes assigned so far (ties: the lowest rank).  keep[i]
+ * (host, n entries) becomes 1 for the chosen record and 0 for its other replicas; load (host,
+ * n_ranks entries, may be null) receives the bytes assigned per rank.  The kept records are pairwise
+ * disjoint if the distinct shards were, i.e. they are a valid saved side for bcp_plan; planning
+ * kept live records against a packed blob layout is the save-side "pack", the inverse of a load.
+ * Host only, no GPU involved. */
+bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_of, int64_t n, int32_t n_ranks,
+                               uint8_t* keep, int64_t* load);
+
 /* Build a copy plan on the current HIP device (Sec. 3.3 Step 2 on the GPU).
  * saved/target: host arrays, borrowed for the duration of the call.  stream: hipStream_t
  * (0 == default stream) the planner kernels run on; the call returns after they finished, so

@@ -42,7 +42,7 @@ BCP_SKIP_OVERLAP_CHECK = 2
 BCP_ORDER_BY_SOURCE = 4
 
 EXPORTS = [
-    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_plan", "bcp_reshard", "bcp_reshard_arrived",
+    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_dedup_worst_fit", "bcp_plan", "bcp_reshard", "bcp_reshard_arrived",
     "bcp_reshard_from_host", "bcp_plan_stats",
     "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy", "bcp_configure", "bcp_copy_baseline", "bcp_last_error",
     "bcp_status_name", "bcp_abi_version", "bcp_sizeof_shard_meta",
@@ -70,6 +70,7 @@ def lib():
         vp, i64, i32, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32
         L.bcp_meta_from_flat_slice.argtypes = [vp, i64, i64, i64, i32, i64, vp, ctypes.POINTER(i64)]
         L.bcp_decompose.argtypes = [vp, vp, ctypes.POINTER(i64)]
+        L.bcp_dedup_worst_fit.argtypes = [vp, vp, i64, i32, vp, vp]
         L.bcp_plan.argtypes = [vp, i64, vp, i64, u32, vp, ctypes.POINTER(vp)]
         L.bcp_reshard.argtypes = [vp, vp, i32, vp, i32, vp]
         L.bcp_reshard_arrived.argtypes = [vp, vp, i32, vp, i32, i32, i64, i64, vp]
@@ -160,6 +161,18 @@ def _records_bulk(shards) -> np.ndarray:
     for i in strided:
         arr["strides"][i, :len(shards[i].strides)] = shards[i].strides
     return arr
+
+
+def dedup_worst_fit(meta: np.ndarray, rank_of, n_ranks: int):
+    """bcp_dedup_worst_fit -> (keep mask, bytes assigned per rank)."""
+    meta = np.ascontiguousarray(meta, dtype=SHARD_META)
+    ranks = np.ascontiguousarray(rank_of, dtype=np.int32)
+    assert len(ranks) == len(meta)
+    keep = np.zeros(max(len(meta), 1), dtype=np.uint8)
+    load = np.zeros(n_ranks, dtype=np.int64)
+    _check(lib().bcp_dedup_worst_fit(meta.ctypes.data if len(meta) else None, ranks.ctypes.data if len(meta) else None,
+                                     len(meta), n_ranks, keep.ctypes.data, load.ctypes.data))
+    return keep[:len(meta)].astype(bool), load
 
 
 def layout_to_meta(layout) -> np.ndarray:

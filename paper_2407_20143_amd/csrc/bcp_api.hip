@@ -4,6 +4,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "bcp_internal.h"
@@ -215,6 +216,74 @@ bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, i
     b.byte_offset = rec->byte_offset + (int64_t)rec->itemsize * (lb[j].flat_start - rec->flat_begin);
     out_boxes[j] = b;
   }
+  return BCP_OK;
+}
+
+// ---- save-side deduplication (Worst-Fit) ----------------------------------------------------------
+namespace {
+struct ShardIdentity {
+  const bcp_shard_meta* r;
+  bool operator==(const ShardIdentity& o) const {
+    const bcp_shard_meta &a = *r, &b = *o.r;
+    if (a.fqn_id != b.fqn_id || a.ndim != b.ndim || a.itemsize != b.itemsize || a.flat_begin != b.flat_begin ||
+        a.flat_end != b.flat_end)
+      return false;
+    for (int k = 0; k < a.ndim; ++k)
+      if (a.offsets[k] != b.offsets[k] || a.lengths[k] != b.lengths[k]) return false;
+    return true;
+  }
+};
+struct ShardIdentityHash {
+  size_t operator()(const ShardIdentity& s) const {
+    const bcp_shard_meta& a = *s.r;
+    uint64_t h = 0x9e3779b97f4a7c15ull ^ (uint64_t)a.fqn_id;
+    auto mix = [&](uint64_t v) { h = (h ^ v) * 0x100000001b3ull; h ^= h >> 29; };
+    mix((uint64_t)a.flat_begin);
+    mix((uint64_t)a.flat_end);
+    for (int k = 0; k < a.ndim; ++k) {
+      mix((uint64_t)a.offsets[k]);
+      mix((uint64_t)a.lengths[k]);
+    }
+    return (size_t)h;
+  }
+};
+}  // namespace
+
+bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_of, int64_t n, int32_t n_ranks,
+                               uint8_t* keep, int64_t* load) {
+  if (n < 0 || n_ranks <= 0 || (n > 0 && (!recs || !rank_of || !keep))) {
+    set_error("bcp_dedup_worst_fit: bad argument");
+    return BCP_ERR_INVALID_ARG;
+  }
+  std::unordered_map<ShardIdentity, int64_t, ShardIdentityHash> group_of;  // identity -> group index
+  std::vector<std::vector<int64_t>> groups;                                // in order of first appearance
+  for (int64_t i = 0; i < n; ++i) {
+    if (recs[i].ndim < 0 || recs[i].ndim > BCP_MAX_DIMS || rank_of[i] < 0 || rank_of[i] >= n_ranks ||
+        recs[i].flat_end < recs[i].flat_begin || recs[i].itemsize <= 0) {
+      set_error("bcp_dedup_worst_fit: bad record " + std::to_string(i));
+      return BCP_ERR_INVALID_ARG;
+    }
+    auto it = group_of.find(ShardIdentity{&recs[i]});
+    if (it == group_of.end()) {
+      group_of.emplace(ShardIdentity{&recs[i]}, (int64_t)groups.size());
+      groups.emplace_back(1, i);
+    } else {
+      groups[(size_t)it->second].push_back(i);
+    }
+  }
+  std::vector<int64_t> assigned((size_t)n_ranks, 0);
+  for (int64_t i = 0; i < n; ++i) keep[i] = 0;
+  for (const std::vector<int64_t>& g : groups) {
+    int64_t best = g[0];
+    for (int64_t i : g) {
+      const int64_t li = assigned[(size_t)rank_of[i]], lb = assigned[(size_t)rank_of[best]];
+      if (li < lb || (li == lb && rank_of[i] < rank_of[best])) best = i;
+    }
+    keep[best] = 1;
+    assigned[(size_t)rank_of[best]] += (recs[best].flat_end - recs[best].flat_begin) * (int64_t)recs[best].itemsize;
+  }
+  if (load)
+    for (int32_t r = 0; r < n_ranks; ++r) load[r] = assigned[(size_t)r];
   return BCP_OK;
 }
 

@@ -312,6 +312,40 @@ def megatron_layout(model: Sequence[_ModelTensor], states, layers: int, tp: int,
     return lay
 
 
+def replicated_live_layout(model: Sequence[_ModelTensor], states, layers: int, tp: int, pp: int, dp: int):
+    """Training-time ("live") layout with data parallelism: every DP rank of a (pp, tp) group holds
+    the same shards, replicated tensors are on every TP rank as well.  One buffer per rank
+    (rank = (pp_rank * tp + tp_rank) * dp + dp_rank).  Returns (layout, holder rank per shard)."""
+    n_ranks = pp * tp * dp
+    pk = _Packer(n_ranks)
+    lay = Layout()
+    rank_of: List[int] = []
+    for si, (_, dtype, _) in enumerate(states):
+        e = dtype.itemsize
+        for ti, mt in enumerate(model):
+            stage = _stage_of(mt, layers, pp)
+            for r in range(tp):
+                off, ln = _tp_box(mt.shape, mt.tp_dim, tp, r)
+                part = Part(si * len(model) + ti, tuple(mt.shape), off, ln)
+                for d in range(dp):
+                    rank = (stage * tp + r) * dp + d
+                    lay.shards.append(regular(part, e, rank, pk.take(rank, part.volume * e)))
+                    rank_of.append(rank)
+    lay.buf_bytes = pk.sizes()
+    return lay, rank_of
+
+
+def packed_layout(shards: Sequence[Shard], buf_of: Sequence[int], n_bufs: int, align: int = BLOB_ALIGN) -> Layout:
+    """The given shards, each stored packed in buffer buf_of[i], back to back (a save-blob layout)."""
+    pk = _Packer(n_bufs, align)
+    lay = Layout()
+    for sh, b in zip(shards, buf_of):
+        lay.shards.append(Shard(sh.parts, sh.flat_begin, sh.flat_end, sh.itemsize, b,
+                                pk.take(b, sh.numel * sh.itemsize), None, sh.group))
+    lay.buf_bytes = pk.sizes()
+    return lay
+
+
 def zero_layout(model: Sequence[_ModelTensor], states, tp: int, dp: int, replicate_norms: bool,
                 only=None) -> Layout:
     """ZeRO-style flat sharding: per state and TP rank the TP-local shards are flattened and
@@ -643,6 +677,43 @@ def table3_tgpt_group(dp_s: int = 75, dp_t: int = 150, layers: int = 10, hidden:
     return Case(f"tgpt_dp{dp_s}to{dp_t}", BASE_SEED + 7, _specs(model, ADAM_FP32_STATES),
                 flat_units_layout(model, ADAM_FP32_STATES, units, dp_s, tp=tp, tp_rank=0),
                 flat_units_layout(model, ADAM_FP32_STATES, units, dp_t, tp=tp, tp_rank=0))
+
+
+def fused_qkv_case(layers: int = 32, hidden: int = 4096, n_heads: int = 32, n_kv: int = 8, tp_s: int = 4,
+                   tp_t: int = 2, dtype: torch.dtype = torch.bfloat16) -> Case:
+    """The layout change Appendix A names as a pain point of resharding scripts: grouped-query
+    attention stored as ONE fused, group-interleaved QKV weight per TP rank (per KV group: its query
+    heads, then its key head, then its value head) is loaded as separate q, k, v tensors under a
+    different TP degree.  No special support is needed: the fused blob is described by one record
+    per (group, q|k|v) block, each a box of the q, k or v tensor with its byte offset in the blob."""
+    d = hidden // n_heads
+    qpg = n_heads // n_kv
+    assert n_kv % tp_s == 0 and n_heads % tp_t == 0 and n_kv % tp_t == 0
+    e = dtype.itemsize
+    specs: Dict[int, TensorSpec] = {}
+    saved, target = Layout(), Layout()
+    pks, pkt = _Packer(tp_s), _Packer(tp_t)
+    for l in range(layers):
+        fq, fk, fv = 3 * l, 3 * l + 1, 3 * l + 2
+        shapes = {fq: (n_heads * d, hidden), fk: (n_kv * d, hidden), fv: (n_kv * d, hidden)}
+        for f, nm in ((fq, "q"), (fk, "k"), (fv, "v")):
+            specs[f] = TensorSpec(f, f"layers.{l}.attn.{nm}.weight", shapes[f], dtype, ("normal", 0.0, 0.02))
+        gps = n_kv // tp_s
+        for r in range(tp_s):
+            base = pks.take(r, gps * (qpg + 2) * d * hidden * e)  # one fused block per layer and rank
+            off = base
+            for g in range(r * gps, (r + 1) * gps):
+                for f, row0, rows in ((fq, g * qpg * d, qpg * d), (fk, g * d, d), (fv, g * d, d)):
+                    part = Part(f, shapes[f], (row0, 0), (rows, hidden))
+                    saved.shards.append(regular(part, e, r, off))
+                    off += rows * hidden * e
+        for r in range(tp_t):
+            for f in (fq, fk, fv):
+                rows = shapes[f][0] // tp_t
+                part = Part(f, shapes[f], (r * rows, 0), (rows, hidden))
+                target.shards.append(regular(part, e, r, pkt.take(r, part.volume * e)))
+    saved.buf_bytes, target.buf_bytes = pks.sizes(), pkt.sizes()
+    return Case(f"fused_qkv_tp{tp_s}to{tp_t}", BASE_SEED + 8, specs, saved, target)
 
 
 def cfg5(layers: int = 16, hidden: int = 4096, experts: int = 64, ffn: int = 1408,

@@ -183,6 +183,14 @@ def test_one_region_beyond_4_gib():
     assert bool((dst[0][:4] == POISON).all())
 
 
+def test_fused_gqa_qkv_full():
+    """32 layers, h 4096, 32 query / 8 KV heads: fused TP4 blobs -> separate q, k, v at TP2 (1.6 GB)."""
+    case = synth.fused_qkv_case()
+    src, dst, sm, tm, st = reshard_on_gpu(case)
+    check_closed_form(case, dst, [[0], [1]])
+    check_oracle_sample(case, src, dst, sm, tm, [0, 1, 2, 3 * 17, 3 * 31 + 2])
+
+
 def test_cfg5_experts_full():
     case = synth.cfg5(n_small=0)
     src, dst, sm, tm, st = reshard_on_gpu(case)

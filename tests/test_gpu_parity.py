@@ -128,6 +128,14 @@ def test_table3_shapes_scaled():
     check_case(synth.table3_tgpt_group(150, 75, layers=2, hidden=256, vocab=2048, first_stage=False))
 
 
+def test_fused_gqa_qkv_to_separate_tensors():
+    """Fused, group-interleaved QKV blobs (Megatron style) loaded as separate q / k / v under another TP."""
+    st = check_case(synth.fused_qkv_case(layers=3, hidden=256, n_heads=16, n_kv=4, tp_s=4, tp_t=2))
+    assert st["n_regions"] == 3 * 3 * 4  # per layer: 4 groups x (q, k, v), each inside one target shard
+    check_case(synth.fused_qkv_case(layers=2, hidden=192, n_heads=12, n_kv=6, tp_s=2, tp_t=3, dtype=torch.float32))
+    check_case(synth.fused_qkv_case(layers=2, hidden=128, n_heads=8, n_kv=8, tp_s=8, tp_t=1))
+
+
 @pytest.mark.parametrize("n_bufs", [200, 700])
 def test_many_buffers(n_bufs):
     """More buffers than fit the kernel arguments (pointer table in device memory), and more than

@@ -142,6 +142,8 @@ def test_closed_form_model_shapes():
              synth.cfg3(layers=4, hidden=32, ffn=88, vocab=64, rank_share=True),
              synth.cfg4(layers=2, hidden=24, ffn=40, vocab=52, dp_s=16, dp_t=12),
              synth.cfg5(layers=1, hidden=16, experts=8, ffn=12, n_small=50),
+             synth.fused_qkv_case(layers=2, hidden=32, n_heads=8, n_kv=4, tp_s=4, tp_t=2),
+             synth.fused_qkv_case(layers=1, hidden=48, n_heads=12, n_kv=6, tp_s=2, tp_t=3, dtype=torch.float32),
              synth.table3_vdit(8, 16, layers=2, hidden=24, text_dim=40),
              synth.table3_vdit(16, 8, layers=2, hidden=24, text_dim=40),
              synth.table3_tgpt_group(5, 10, layers=2, hidden=32, vocab=128),
