@@ -828,7 +828,7 @@ def _random_flat_layout(rng, specs, tp: int, dp: int, granule: int, pack_bufs: i
     return lay
 
 
-RANDOM_DTYPES = (torch.uint8, torch.bfloat16, torch.float32, torch.float64)
+RANDOM_DTYPES = (torch.uint8, torch.bfloat16, torch.float32, torch.float64, torch.complex128)  # 1..16 bytes
 
 
 def random_case(seed: int, n_tensors: int = 5, max_elems: int = 3000, saved_mode: str = "grid",

@@ -75,6 +75,44 @@ def test_random_flat_single_dtype_odd_offsets(seed, dtype):
                                  granules=(1, 2), dtype=dtype))
 
 
+def test_rank_8_tensors():
+    """The dimension limit: rank-8 tensors under grid, flat (decomposition into up to 15 boxes) and
+    strided layouts."""
+    for seed, modes, ps in ((700, ("grid", "grid"), 0.0), (701, ("flat", "grid"), 0.0), (705, ("grid", "flat"), 0.0),
+                            (703, ("grid", "grid"), 0.7), (705, ("flat", "flat"), 0.0)):
+        case = synth.random_case(seed, n_tensors=4, max_elems=40000, saved_mode=modes[0], target_mode=modes[1],
+                                 max_rank=8, p_strided=ps, granules=(16,) if ps else (1, 4, 16))
+        assert max(len(s.shape) for s in case.tensors.values()) >= 6
+        check_case(case)
+
+
+@pytest.mark.parametrize("dtype", [torch.complex128, torch.float64, torch.uint8])
+def test_strided_every_itemsize(dtype):
+    """LDS-staged transposes with 16-, 8- and 1-byte elements (32x32 and 64x64 tiles)."""
+    for seed in range(3):
+        n = 96 + 37 * seed
+        spec = TensorSpec(0, "w", (n, 2 * n + 5), dtype, ("bits",))
+        e = dtype.itemsize
+        saved = Layout([regular(Part(0, spec.shape, (0, 0), spec.shape), e, 0, 0)], [spec.shape[0] * spec.shape[1] * e])
+        half = spec.shape[1] // 2
+        t = [regular(Part(0, spec.shape, (0, 0), (n, half)), e, 0, 0, (1, n)),
+             regular(Part(0, spec.shape, (0, half), (n, spec.shape[1] - half)), e, 1, 0, (1, n))]
+        target = Layout(t, [n * half * e, n * (spec.shape[1] - half) * e])
+        st = check_case(Case("transpose", seed, {0: spec}, saved, target))
+        assert st["n_transposed"] == 2
+
+
+def test_plans_are_reproducible():
+    case = synth.cfg5(layers=1, hidden=128, experts=8, ffn=44, n_small=2000)
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    a, b = binding.plan(sm, tm), binding.plan(sm, tm)
+    ra, rb = a.regions(), b.regions()
+    assert len(ra) > 2000 and ra.tobytes() == rb.tobytes()
+    assert a.stats()["n_batches"] == b.stats()["n_batches"]
+    a.destroy()
+    b.destroy()
+
+
 def test_cfg1_small_and_strided():
     st = check_case(synth.cfg1(256, 192))
     assert st["n_pairs"] == 8 and st["n_regions"] == 8
