@@ -75,6 +75,12 @@ def build_case(name: str):
         return synth.table3_tgpt_group(75, 150), "tGPT-70B-shaped, one TP4/PP8 group, fp32 Adam states, DP 75 -> 150"
     if name == "tgpt_150to75":
         return synth.table3_tgpt_group(150, 75), "tGPT-70B-shaped, one TP4/PP8 group, fp32 Adam states, DP 150 -> 75"
+    if name == "cfg1_strided":
+        return synth.cfg1(strided_target=True), "cfg1 with column-major target buffers (LDS-staged transpose, cache resident)"
+    if name == "transpose":
+        return synth.transpose_case(), "fp32 [16384,16384], 4 row blocks -> 4 column blocks stored column-major (LDS-staged transpose)"
+    if name == "transpose_bf16":
+        return synth.transpose_case(dtype=__import__("torch").bfloat16), "bf16 [16384,16384] row blocks -> column-major column blocks"
     if name == "fused_qkv":
         return synth.fused_qkv_case(), "fused GQA QKV blobs (32 layers, h4096, 32q/8kv heads) TP4 -> separate q,k,v TP2"
     if name.startswith("copy"):  # copy, copy_s4 (source shifted 4 bytes), copy_d4, copy_d2 ...

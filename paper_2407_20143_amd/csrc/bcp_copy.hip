@@ -27,7 +27,9 @@ namespace bcp {
 namespace {
 
 constexpr int kMaxThreads = 1024;
-constexpr int kLdsBytes = 32 * 33 * 16;  // >= 64*65*4: transpose staging incl. one pad column
+constexpr int kLdsBytes = 128 * 129 * 8;  // transpose staging incl. one pad column; the planner picks the tile
+                                          // edge per element size (256 for 1-2 bytes, 128 for 4-8, 64 for 16).
+                                          // With one workgroup per CU, 129 of the CU's 160 KiB of LDS are free.
 constexpr int kLdsPtrs = 1024;           // buffer pointers staged in LDS (more: read from global)
 constexpr int kArgPtrs = kMaxKernargPtrs;  // buffer pointers passed as kernel arguments
 
@@ -178,6 +180,73 @@ __device__ __forceinline__ void transpose_tile(gsrc_t __restrict__ s, gdst_t __r
   __syncthreads();  // the staging area is free again
 }
 
+template <int E>
+__device__ __forceinline__ typename Granule<E>::type get_elem(const u32x4& v, uint32_t i) {
+  if constexpr (E == 16) return v;
+  else if constexpr (E == 8) return u32x2{v[2 * i], v[2 * i + 1]};
+  else if constexpr (E == 4) return v[i];
+  else if constexpr (E == 2) return (uint16_t)(v[i >> 1] >> (16 * (i & 1)));
+  else return (uint8_t)(v[i >> 2] >> (8 * (i & 3)));
+}
+template <int E>
+__device__ __forceinline__ void set_elem(u32x4& v, uint32_t i, typename Granule<E>::type x) {
+  if constexpr (E == 16) v = x;
+  else if constexpr (E == 8) { v[2 * i] = x[0]; v[2 * i + 1] = x[1]; }
+  else if constexpr (E == 4) v[i] = x;
+  else if constexpr (E == 2) v[i >> 1] |= (uint32_t)x << (16 * (i & 1));
+  else v[i >> 2] |= (uint32_t)x << (8 * (i & 3));
+}
+
+// Same transpose with 16-byte global accesses on both sides: a lane loads 16/E elements that are
+// consecutive along a and scatters them into LDS rows a; after the barrier a lane gathers 16/E
+// elements consecutive along b from one LDS row and stores them with one 16-byte store.  Needs
+// na and nb to be multiples of 16/E and 16-byte aligned bases and pitches.
+template <int E>
+__device__ __forceinline__ void transpose_tile_vec(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na,
+                                                   uint32_t nb, int64_t spb, int64_t dpa, uint32_t td, char* lds) {
+  constexpr uint32_t VE = 16 / E;
+  const uint32_t pitch = td + 1, nt = blockDim.x, tid = threadIdx.x;
+  const uint32_t vpr = na / VE, total = vpr * nb;
+  for (uint32_t base = 0; base < total; base += 4 * nt) {
+    u32x4 v[4];
+    uint32_t bb[4], aa[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t idx = base + u * nt + tid;
+      bb[u] = idx / vpr;
+      aa[u] = (idx - bb[u] * vpr) * VE;
+      if (idx < total) v[u] = ld<16>(s + (size_t)aa[u] * E + (int64_t)bb[u] * spb);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (base + u * nt + tid < total) {
+#pragma unroll
+        for (uint32_t i = 0; i < VE; ++i)
+          lds_st<E>(lds + (size_t)((aa[u] + i) * pitch + bb[u]) * E, get_elem<E>(v[u], i));
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t wpr = nb / VE, totw = wpr * na;
+  for (uint32_t w = tid; w < totw; w += nt) {
+    const uint32_t a = w / wpr, b0 = (w - a * wpr) * VE;
+    u32x4 out = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (uint32_t i = 0; i < VE; ++i) set_elem<E>(out, i, lds_ld<E>(lds + (size_t)(a * pitch + b0 + i) * E));
+    st<16>(d + (size_t)b0 * E + (int64_t)a * dpa, out);
+  }
+  __syncthreads();  // the staging area is free again
+}
+
+template <int E>
+__device__ __forceinline__ void transpose_any(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na, uint32_t nb,
+                                              int64_t spb, int64_t dpa, uint32_t td, char* lds) {
+  constexpr uint32_t VE = 16 / E;
+  const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
+  if ((al & 15u) == 0 && na % VE == 0 && nb % VE == 0) transpose_tile_vec<E>(s, d, na, nb, spb, dpa, td, lds);
+  else transpose_tile<E>(s, d, na, nb, spb, dpa, td, lds);
+}
+
 // rows of `run` bytes where 16-byte alignment does not hold everywhere: unaligned 16-byte vectors
 // over all rows at once, then the (run mod 16) tail bytes of every row.
 __device__ __forceinline__ void copy_rows_unaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
@@ -205,11 +274,11 @@ __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t
     const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
     if (WG && (al & (e - 1)) == 0) {
       switch (e) {
-        case 1: transpose_tile<1>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 2: transpose_tile<2>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 4: transpose_tile<4>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 8: transpose_tile<8>(s, d, na, nb, spb, dpa, td, lds); break;
-        default: transpose_tile<16>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 1: transpose_any<1>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 2: transpose_any<2>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 4: transpose_any<4>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 8: transpose_any<8>(s, d, na, nb, spb, dpa, td, lds); break;
+        default: transpose_any<16>(s, d, na, nb, spb, dpa, td, lds); break;
       }
     } else {  // single wave, or elements not aligned to their own size: plain byte moves
       const uint32_t total = na * nb * e;

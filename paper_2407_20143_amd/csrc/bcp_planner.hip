@@ -491,7 +491,8 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
       ++nd;
     }
     R->ndim = nd;
-    const uint32_t td = e <= 4 ? 64u : 32u;
+    // tile edge: the longest runs on both sides that the LDS staging area (128 x 129 x 8 bytes) holds
+    const uint32_t td = e <= 2 ? 256u : (e <= 8 ? 128u : 64u);
     R->tdim = td;
     const uint64_t ta = ((uint64_t)L[a] + td - 1) / td, tb = ((uint64_t)L[b] + td - 1) / td;
     uint64_t groups = 1;
@@ -727,6 +728,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_weights(const uint64_t* tile_st
   TileDesc t;
   const uint64_t bytes = decode_tile(regions[r], (uint32_t)(i - tile_start[r]), &t);
   weight[i] = bytes >= kSmallTileBytes ? 0 : (bytes > kMinBatchWeight ? bytes : (uint64_t)kMinBatchWeight);
+  // a transpose tile of any useful size wants the whole workgroup and its LDS staging
+  if ((t.kind & 0xffu) == kTranspose && bytes >= 1024) weight[i] = 0;
   if (key) {
     uint64_t last = (uint64_t)t.src_off;
     if ((t.kind & 0xffu) == kTranspose) {

@@ -604,6 +604,24 @@ def cfg1(n: int = 1024, m: int = 1024, strided_target: bool = False) -> Case:
     return Case("cfg1" + ("_strided" if strided_target else ""), BASE_SEED + 1, {0: spec}, saved, target)
 
 
+def transpose_case(n: int = 16384, m: int = 16384, dtype: torch.dtype = torch.float32, shards: int = 4) -> Case:
+    """A [n, m] tensor saved row-major in `shards` row blocks and loaded as `shards` column blocks whose
+    buffers hold them column-major (a transposed view: BasicMeta strides (1, n)): every region takes
+    the LDS-staged path."""
+    e = dtype.itemsize
+    spec = TensorSpec(0, "w", (n, m), dtype, ("bits",))
+    saved, target = Layout(), Layout()
+    for r in range(shards):
+        part = Part(0, (n, m), (r * (n // shards), 0), (n // shards, m))
+        saved.shards.append(regular(part, e, r, 0))
+        saved.buf_bytes.append(part.volume * e)
+    for c in range(shards):
+        part = Part(0, (n, m), (0, c * (m // shards)), (n, m // shards))
+        target.shards.append(regular(part, e, c, 0, (1, n)))
+        target.buf_bytes.append(part.volume * e)
+    return Case(f"transpose_{n}x{m}", BASE_SEED + 9, {0: spec}, saved, target)
+
+
 def copy_case(nbytes: int = 8 << 30, src_shift: int = 0, dst_shift: int = 0) -> Case:
     """One byte tensor saved whole and loaded whole: the reshard degenerates to a plain copy
     (the practical bandwidth ceiling of the copy kernel).  Shifts move the shard inside its

@@ -183,6 +183,22 @@ def test_one_region_beyond_4_gib():
     assert bool((dst[0][:4] == POISON).all())
 
 
+def test_transposed_target_1_gib():
+    """All-LDS-path workload at 1 GiB: row blocks -> column blocks stored column-major."""
+    case = synth.transpose_case()
+    src, dst, sm, tm, st = reshard_on_gpu(case)
+    assert st["n_transposed"] == st["n_regions"] == 16
+    G = torch.cat([b.view(torch.int32).view(4096, 16384) for b in src])     # the whole tensor, row-major (as bits)
+    for c in range(4):
+        want = G[:, 4096 * c:4096 * (c + 1)].t().contiguous()              # column-major storage of the block
+        assert torch.equal(dst[c].view(torch.int32).view(4096, 16384), want)
+    case = synth.transpose_case(2048, 1536, torch.bfloat16, shards=2)
+    src, dst, sm, tm, st = reshard_on_gpu(case)
+    want = oracle.reshard(case.saved, case.target, [b.cpu() for b in src], poison=POISON)
+    for b, w in enumerate(want):
+        assert np.array_equal(dst[b].cpu().numpy(), w)
+
+
 def test_fused_gqa_qkv_full():
     """32 layers, h 4096, 32 query / 8 KV heads: fused TP4 blobs -> separate q, k, v at TP2 (1.6 GB)."""
     case = synth.fused_qkv_case()
