@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # copy kernel of known size in the same run), per workload, with the hash of the kernel sources
 # they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188951094515,
-             "csrc_sha256": "d3cb3bf68f4843abe1461ab46dc58c3ca2c36a5a5f35525a218024a8e17de164"},
+    "cfg3": {"bytes_per_launch": 188968957997,
+             "csrc_sha256": "e1ada873461a11ce24716f9b9a16736f598bdc08ff0d3bd0c268423c166c5d3c"},
 }
 
 
@@ -201,6 +201,9 @@ def main():
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--raw-inputs", action="store_true",
+                    help="fill the saved blobs with one random fill each instead of per-tensor values (byte traffic "
+                         "is the same; keeps the dispatch count low under rocprofv3 --pmc)")
     ap.add_argument("--from-host", type=int, default=0, metavar="CHUNK_MIB",
                     help="also time the chunked host-to-HBM arrival overlapped with the reshard (pinned host copies "
                          "of the saved blobs, chunks of this many MiB) against copy-then-reshard")
@@ -223,9 +226,12 @@ def main():
     note(f"workload {args.workload}: generating inputs on the GPU")
     t0 = time.perf_counter()
     small = args.workload == "cfg5_small"
-    src = synth.materialize(case.saved, case.tensors, case.seed, device="cpu" if small else "cuda")
-    if small:
-        src = [b.cuda() for b in src]
+    if args.raw_inputs:
+        src = [torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda") for n in case.saved.buf_bytes]
+    else:
+        src = synth.materialize(case.saved, case.tensors, case.seed, device="cpu" if small else "cuda")
+        if small:
+            src = [b.cuda() for b in src]
     dst = [torch.empty(n, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
     torch.cuda.synchronize()
     torch.cuda.empty_cache()  # hand the generator's temporaries back: the library allocates with hipMalloc
