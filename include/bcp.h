@@ -69,6 +69,8 @@ typedef enum bcp_status {
 #define BCP_SKIP_OVERLAP_CHECK 2u   /* trust the caller that saved shards are pairwise disjoint */
 #define BCP_ORDER_BY_SOURCE 4u      /* order the work by (source blob, source byte) so that it can run
                                        while the blobs arrive: see bcp_reshard_arrived */
+#define BCP_META_ON_DEVICE 8u       /* saved / target point to DEVICE memory (metadata produced or kept on the
+                                       GPU): no host-to-device upload of the records */
 
 typedef struct bcp_stats {
   int64_t n_saved_boxes;   /* regular boxes after decomposing the saved records */
@@ -133,7 +135,8 @@ bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_o
                                uint8_t* keep, int64_t* load);
 
 /* Build a copy plan on the current HIP device (Sec. 3.3 Step 2 on the GPU).
- * saved/target: host arrays, borrowed for the duration of the call.  stream: hipStream_t
+ * saved/target: host arrays (device arrays with BCP_META_ON_DEVICE), borrowed for the duration of
+ * the call.  stream: hipStream_t
  * (0 == default stream) the planner kernels run on; the call returns after they finished, so
  * the plan is usable on any stream.  On success *out_plan owns device memory until
  * bcp_plan_destroy.  Saved FQNs no target asks for are ignored.  A plan is immutable and may be

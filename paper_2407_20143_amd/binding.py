@@ -40,6 +40,7 @@ BCP_OK = 0
 BCP_ALLOW_UNCOVERED = 1
 BCP_SKIP_OVERLAP_CHECK = 2
 BCP_ORDER_BY_SOURCE = 4
+BCP_META_ON_DEVICE = 8
 
 EXPORTS = [
     "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_dedup_worst_fit", "bcp_plan", "bcp_reshard", "bcp_reshard_arrived",
@@ -241,6 +242,22 @@ def _stream_ptr(stream) -> int:
     if isinstance(stream, int):
         return stream
     return int(stream.cuda_stream)
+
+
+def meta_to_device(meta: np.ndarray):
+    """Upload a bcp_shard_meta array once (for plans built with BCP_META_ON_DEVICE)."""
+    import torch
+    raw = np.ascontiguousarray(meta, dtype=SHARD_META).view(np.uint8)
+    return torch.from_numpy(raw.copy()).cuda(), len(meta)
+
+
+def plan_from_device_meta(saved_dev, n_saved: int, target_dev, n_target: int, flags: int = 0, stream=None) -> Plan:
+    """bcp_plan with BCP_META_ON_DEVICE: the records are byte tensors in device memory."""
+    h = ctypes.c_void_p()
+    _check(lib().bcp_plan(saved_dev.data_ptr() if n_saved else None, n_saved,
+                          target_dev.data_ptr() if n_target else None, n_target,
+                          flags | BCP_META_ON_DEVICE, _stream_ptr(stream), ctypes.byref(h)))
+    return Plan(h)
 
 
 def plan(saved_meta: np.ndarray, target_meta: np.ndarray, flags: int = 0, stream=None) -> Plan:

@@ -300,7 +300,7 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     set_error("bcp_plan: null metadata array or negative count");
     return BCP_ERR_INVALID_ARG;
   }
-  if (flags & ~(BCP_ALLOW_UNCOVERED | BCP_SKIP_OVERLAP_CHECK | BCP_ORDER_BY_SOURCE)) {
+  if (flags & ~(BCP_ALLOW_UNCOVERED | BCP_SKIP_OVERLAP_CHECK | BCP_ORDER_BY_SOURCE | BCP_META_ON_DEVICE)) {
     set_error("bcp_plan: unknown flag");
     return BCP_ERR_INVALID_ARG;
   }

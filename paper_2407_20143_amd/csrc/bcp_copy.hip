@@ -27,9 +27,12 @@ namespace bcp {
 namespace {
 
 constexpr int kMaxThreads = 1024;
-constexpr int kLdsBytes = 128 * 129 * 8;  // transpose staging incl. one pad column; the planner picks the tile
-                                          // edge per element size (256 for 1-2 bytes, 128 for 4-8, 64 for 16).
-                                          // With one workgroup per CU, 129 of the CU's 160 KiB of LDS are free.
+// The staging area in LDS is sized at launch: what the plan's largest transposed tile needs, and
+// at least the room the small-tile batches take (one descriptor and one counter per thread).
+constexpr uint32_t small_batch_lds_bytes(uint32_t threads) {
+  return threads * (uint32_t)sizeof(TileDesc) + (threads + 1 + kMaxThreads / 64) * 4u;
+}
+constexpr uint32_t kMaxDynamicLds = 144 * 1024;  // of the CU's 160 KiB; pointers and queue slots are static
 constexpr int kLdsPtrs = 1024;           // buffer pointers staged in LDS (more: read from global)
 constexpr int kArgPtrs = kMaxKernargPtrs;  // buffer pointers passed as kernel arguments
 
@@ -137,12 +140,12 @@ __device__ __forceinline__ void copy_rows(gsrc_t __restrict__ s, gdst_t __restri
 }
 
 // one contiguous run whose two sides disagree modulo 16: byte head up to the destination's next
-// 16-byte boundary, aligned 16-byte stores fed by unaligned 16-byte loads, byte tail.  nt >= 16.
+// 16-byte boundary, aligned 16-byte stores fed by unaligned 16-byte loads, byte tail.
 __device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t run,
                                                     uint32_t tid, uint32_t nt) {
   uint32_t head = (uint32_t)(-(uintptr_t)d) & 15u;
   if (head > run) head = run;
-  if (tid < head) d[tid] = s[tid];
+  for (uint32_t i = tid; i < head; i += nt) d[i] = s[i];
   const uint32_t body = (run - head) >> 4;
   gsrc_t s2 = s + head;
   gdst_t d2 = d + head;
@@ -159,24 +162,37 @@ __device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_
   }
   for (; i < body; i += nt) st<16>(d2 + (size_t)i * 16, ld<-16>(s2 + (size_t)i * 16));
   const uint32_t done = head + (body << 4);
-  const uint32_t tail = run - done;
-  if (tid < tail) d[done + tid] = s[done + tid];
+  for (uint32_t i = done + tid; i < run; i += nt) d[i] = s[i];
 }
 
+// ---- transposed tiles ----------------------------------------------------------------------------
+// source: element (a, b) at s + a*E + b*spb (contiguous along a)
+// destination: element (a, b) at d + b*E + a*dpa (contiguous along b)
+// A tile is na x nb elements, at most tda x tdb (the full tile's edges, powers of two).
+// Staging: row a holds the tile's elements (a, 0 .. nb), tdb + 1 elements apart: the odd pitch
+// spreads both a column and a row over the LDS banks.
+
+// element by element, for tiles whose addresses or extents rule out 16-byte accesses
 template <int E>
 __device__ __forceinline__ void transpose_tile(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na,
-                                               uint32_t nb, int64_t spb, int64_t dpa, uint32_t td, char* lds) {
-  // source: element (a, b) at s + a*E + b*spb (contiguous along a)
-  // destination: element (a, b) at d + b*E + a*dpa (contiguous along b)
-  const uint32_t pitch = td + 1;  // LDS row pitch in elements
-  const uint32_t x = threadIdx.x % td, y0 = threadIdx.x / td, step = blockDim.x / td;
-  if (x < na)
-    for (uint32_t b = y0; b < nb; b += step)
-      lds_st<E>(lds + (size_t)(b * pitch + x) * E, ld<E>(s + (size_t)x * E + (int64_t)b * spb));
+                                               uint32_t nb, int64_t spb, int64_t dpa, uint32_t tda, uint32_t tdb,
+                                               char* lds) {
+  const uint32_t pitch = tdb + 1;
+  uint32_t tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));  // opaque, see transpose_full_tile
+  {
+    const uint32_t x = tid & (tda - 1), y0 = tid / tda, step = blockDim.x / tda;
+    if (x < na)
+      for (uint32_t b = y0; b < nb; b += step)
+        lds_st<E>(lds + (size_t)(x * pitch + b) * E, ld<E>(s + (size_t)x * E + (int64_t)b * spb));
+  }
   __syncthreads();
-  if (x < nb)
-    for (uint32_t a = y0; a < na; a += step)
-      st<E>(d + (size_t)x * E + (int64_t)a * dpa, lds_ld<E>(lds + (size_t)(x * pitch + a) * E));
+  {
+    const uint32_t x = tid & (tdb - 1), y0 = tid / tdb, step = blockDim.x / tdb;
+    if (x < nb)
+      for (uint32_t a = y0; a < na; a += step)
+        st<E>(d + (size_t)x * E + (int64_t)a * dpa, lds_ld<E>(lds + (size_t)(a * pitch + x) * E));
+  }
   __syncthreads();  // the staging area is free again
 }
 
@@ -197,54 +213,130 @@ __device__ __forceinline__ void set_elem(u32x4& v, uint32_t i, typename Granule<
   else v[i >> 2] |= (uint32_t)x << (8 * (i & 3));
 }
 
-// Same transpose with 16-byte global accesses on both sides: a lane loads 16/E elements that are
-// consecutive along a and scatters them into LDS rows a; after the barrier a lane gathers 16/E
-// elements consecutive along b from one LDS row and stores them with one 16-byte store.  Needs
-// na and nb to be multiples of 16/E and 16-byte aligned bases and pitches.
+// The same with 16-byte global accesses on both sides.  Going in, a lane loads a vector of 16/E
+// elements consecutive along a and scatters them into LDS rows a .. a + 16/E; coming out, it
+// gathers 16/E elements consecutive along b from one LDS row and stores them as one vector.  In
+// both directions the 64 lanes of a wave form 8 x 8 blocks: 8 consecutive vectors (128 bytes of
+// one row in memory) by 8 rows, which with the odd LDS pitch puts the lanes of a 4-byte access on
+// different banks.  Needs na and nb to be multiples of 16/E and 16-byte aligned bases and pitches.
 template <int E>
 __device__ __forceinline__ void transpose_tile_vec(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na,
-                                                   uint32_t nb, int64_t spb, int64_t dpa, uint32_t td, char* lds) {
+                                                   uint32_t nb, int64_t spb, int64_t dpa, uint32_t tdb, char* lds) {
   constexpr uint32_t VE = 16 / E;
-  const uint32_t pitch = td + 1, nt = blockDim.x, tid = threadIdx.x;
-  const uint32_t vpr = na / VE, total = vpr * nb;
-  for (uint32_t base = 0; base < total; base += 4 * nt) {
-    u32x4 v[4];
-    uint32_t bb[4], aa[4];
+  constexpr int U = 4;
+  uint32_t tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));  // opaque, see transpose_full_tile
+  const uint32_t pitch = tdb + 1, nt = blockDim.x;
+  const uint32_t lo = tid & 7u, hi = (tid >> 3) & 7u, blk0 = tid >> 6, dblk = nt >> 6;
+  {  // in: blocks of 8 vectors along a by 8 rows b, wave after wave, U per thread at a time
+    const uint32_t vpr = na / VE, chunks_a = (vpr + 7) >> 3, n_blk = chunks_a * ((nb + 7) >> 3);
+    for (uint32_t base = 0; base < n_blk; base += U * dblk) {
+      u32x4 v[U];
+      uint32_t pos[U];  // of v[u]: vector index along a | row << 16, ~0: nothing loaded
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint32_t idx = base + u * nt + tid;
-      bb[u] = idx / vpr;
-      aa[u] = (idx - bb[u] * vpr) * VE;
-      if (idx < total) v[u] = ld<16>(s + (size_t)aa[u] * E + (int64_t)bb[u] * spb);
-    }
+      for (int u = 0; u < U; ++u) {
+        const uint32_t blk = base + blk0 + u * dblk;
+        const uint32_t cb = blk / chunks_a, ca = blk - cb * chunks_a;
+        const uint32_t va = ca * 8 + lo, b = cb * 8 + hi;
+        pos[u] = ~0u;
+        if (va < vpr && b < nb) {
+          pos[u] = va | (b << 16);
+          v[u] = ld<16>(s + (size_t)va * 16 + (int64_t)b * spb);
+        }
+      }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (base + u * nt + tid < total) {
+      for (int u = 0; u < U; ++u) {
+        if (pos[u] != ~0u) {
+          const uint32_t a0 = (pos[u] & 0xffffu) * VE, b = pos[u] >> 16;
 #pragma unroll
-        for (uint32_t i = 0; i < VE; ++i)
-          lds_st<E>(lds + (size_t)((aa[u] + i) * pitch + bb[u]) * E, get_elem<E>(v[u], i));
+          for (uint32_t i = 0; i < VE; ++i)
+            lds_st<E>(lds + (size_t)((a0 + i) * pitch + b) * E, get_elem<E>(v[u], i));
+        }
       }
     }
   }
   __syncthreads();
-  const uint32_t wpr = nb / VE, totw = wpr * na;
-  for (uint32_t w = tid; w < totw; w += nt) {
-    const uint32_t a = w / wpr, b0 = (w - a * wpr) * VE;
-    u32x4 out = {0u, 0u, 0u, 0u};
+  {  // out: blocks of 8 vectors along b by 8 rows a
+    const uint32_t wpr = nb / VE, chunks_b = (wpr + 7) >> 3, n_blk = chunks_b * ((na + 7) >> 3);
+    for (uint32_t blk = blk0; blk < n_blk; blk += dblk) {
+      const uint32_t ca = blk / chunks_b, cb = blk - ca * chunks_b;
+      const uint32_t vb = cb * 8 + lo, a = ca * 8 + hi;
+      if (vb < wpr && a < na) {
+        u32x4 out = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (uint32_t i = 0; i < VE; ++i) set_elem<E>(out, i, lds_ld<E>(lds + (size_t)(a * pitch + b0 + i) * E));
-    st<16>(d + (size_t)b0 * E + (int64_t)a * dpa, out);
+        for (uint32_t i = 0; i < VE; ++i) set_elem<E>(out, i, lds_ld<E>(lds + (size_t)(a * pitch + vb * VE + i) * E));
+        st<16>(d + (size_t)vb * 16 + (int64_t)a * dpa, out);
+      }
+    }
   }
   __syncthreads();  // the staging area is free again
 }
 
+// A full tile with everything known at compile time (1024 threads, both edges full for this element
+// size).  Every wave owns a block of the tile, 8 vectors along a by 32 rows along b (4 KiB), loads
+// it, passes it through its own part of the staging area and stores it: no wave waits for another
+// one's loads, so memory latency overlaps across the 16 waves as it does in a plain copy.
+__device__ __forceinline__ void wave_lds_sync() {  // LDS operations of a wave execute in order; this
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // keeps the compiler from moving them
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int E>
+__device__ __forceinline__ void transpose_full_tile(gsrc_t __restrict__ s, gdst_t __restrict__ d, int64_t spb,
+                                                    int64_t dpa, char* lds) {
+  constexpr uint32_t VE = 16 / E, TDA = transpose_edge_a(E), TDB = transpose_edge_b(E), P = TDB + 1;
+  constexpr uint32_t WA = TDA / (8 * VE);  // waves side by side along a; the others stack up along b
+  constexpr uint32_t VB = 32 / VE;         // coming out: vectors per row of the block,
+  constexpr uint32_t RB = 64 / VB;         //             rows per pass of the wave
+  static_assert(TDA * TDB * E == 4 * kMaxThreads * 16 && (kMaxThreads / 64 / WA) * 32 == TDB, "16 blocks of 4 KiB");
+  uint32_t tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));  // opaque: keeps the index arithmetic of the instances of this function, one per
+                                 // element size, inside their branches instead of hoisted above all of them
+                                 // (which costs the whole kernel registers)
+  const uint32_t lane = tid & 63u, w = tid >> 6;
+  const uint32_t a_w = (w % WA) * 8 * VE, b_w = (w / WA) * 32;
+  const uint32_t lo = lane & 7u, hi = lane >> 3;          // in: vector lo of rows hi + 8 u
+  const uint32_t lo2 = lane & (VB - 1), hi2 = lane / VB;  // out: vector lo2 of rows hi2 + RB u
+  gsrc_t sp = s + (size_t)(a_w + lo * VE) * E + (int64_t)(b_w + hi) * spb;
+  gdst_t dp = d + (size_t)(b_w + lo2 * VE) * E + (int64_t)(a_w + hi2) * dpa;
+  const int64_t s_step = 8 * spb, d_step = (int64_t)RB * dpa;
+  char* l_in = lds + (size_t)((a_w + lo * VE) * P + b_w + hi) * E;
+  const char* l_out = lds + (size_t)((a_w + hi2) * P + b_w + lo2 * VE) * E;
+  u32x4 v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) v[u] = ld<16>(sp + u * s_step);
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (uint32_t i = 0; i < VE; ++i) lds_st<E>(l_in + (size_t)(i * P + u * 8) * E, get_elem<E>(v[u], i));
+  wave_lds_sync();
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    u32x4 out = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (uint32_t i = 0; i < VE; ++i) set_elem<E>(out, i, lds_ld<E>(l_out + (size_t)(u * RB * P + i) * E));
+    st<16>(dp + u * d_step, out);
+  }
+  wave_lds_sync();  // the block's part of the staging area is free again
+}
+
 template <int E>
 __device__ __forceinline__ void transpose_any(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na, uint32_t nb,
-                                              int64_t spb, int64_t dpa, uint32_t td, char* lds) {
+                                              int64_t spb, int64_t dpa, uint32_t tda, uint32_t tdb, char* lds) {
   constexpr uint32_t VE = 16 / E;
   const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
-  if ((al & 15u) == 0 && na % VE == 0 && nb % VE == 0) transpose_tile_vec<E>(s, d, na, nb, spb, dpa, td, lds);
-  else transpose_tile<E>(s, d, na, nb, spb, dpa, td, lds);
+  // Per-wave blocks pay off from 4-byte elements on; a 4 KiB block of smaller ones is only 64 or 32
+  // bytes long on its short side, and the workgroup-wide path moves those faster.
+  if constexpr (E >= 4) {
+    if ((al & 15u) == 0 && blockDim.x == kMaxThreads && tda == transpose_edge_a(E) && tdb == transpose_edge_b(E) &&
+        na == tda && nb == tdb) {
+      transpose_full_tile<E>(s, d, spb, dpa, lds);
+      return;
+    }
+  }
+  if ((al & 15u) == 0 && na % VE == 0 && nb % VE == 0) transpose_tile_vec<E>(s, d, na, nb, spb, dpa, tdb, lds);
+  else transpose_tile<E>(s, d, na, nb, spb, dpa, tda, tdb, lds);
 }
 
 // rows of `run` bytes where 16-byte alignment does not hold everywhere: unaligned 16-byte vectors
@@ -263,30 +355,206 @@ __device__ __forceinline__ void copy_rows_unaligned(gsrc_t __restrict__ s, gdst_
   }
 }
 
+// ---- small tiles ---------------------------------------------------------------------------------
+// A few threads copy a tile of a few hundred bytes: what such a copy costs is memory round trips,
+// not bandwidth.  Every thread therefore issues all loads of a round of kRound items before the
+// first store of the round, so a tile takes one round trip per round instead of one per item, and
+// a tile is given one thread per round of items it consists of (small_tile_threads).
+constexpr int kRound = 4;
+
+// rows x run_g granules of |GG| bytes, as copy_rows
+template <int GG>
+__device__ __forceinline__ void small_rows(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
+                                           uint32_t run_g, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
+  constexpr int G = GG < 0 ? -GG : GG;
+  constexpr int R = kRound;
+  typedef typename Granule<GG>::type V;
+  const uint32_t total = nrows * run_g;
+  for (uint32_t base = tid; base < total; base += R * nt) {
+    V v[R];
+    int64_t dof[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      const uint32_t i = base + u * nt;
+      if (i < total) {
+        const uint32_t row = nrows == 1 ? 0 : i / run_g, col = i - row * run_g;
+        v[u] = ld<GG>(s + (int64_t)row * sp + (int64_t)col * G);
+        dof[u] = (int64_t)row * dp + (int64_t)col * G;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      if (base + u * nt < total) st<GG>(d + dof[u], v[u]);
+  }
+}
+
+// One contiguous run whose two sides disagree modulo 16, as copy_run_misaligned; the bytes before
+// the destination's first and after its last 16-byte boundary move as items of E bytes (4 when
+// both addresses and the length allow it) together with the first round of 16-byte items.
+template <int E>
+__device__ __forceinline__ void small_run_misaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t run,
+                                                     uint32_t tid, uint32_t nt) {
+  typedef typename Granule<E>::type EV;
+  constexpr int RE = E == 4 ? 2 : kRound, RB = kRound;
+  uint32_t head = (uint32_t)(-(uintptr_t)d) & 15u;
+  if (head > run) head = run;
+  const uint32_t body = (run - head) >> 4, done = head + (body << 4);
+  const uint32_t nh = head / E, ne = nh + (run - done) / E;  // edge items: at most 30 / E
+  auto edge_off = [&](uint32_t e) -> uint32_t { return e < nh ? e * E : done + (e - nh) * E; };
+  gsrc_t s2 = s + head;
+  gdst_t d2 = d + head;
+  EV ev[RE];
+  u32x4 bv[RB];
+#pragma unroll
+  for (int u = 0; u < RE; ++u) {
+    const uint32_t e = tid + u * nt;
+    if (e < ne) ev[u] = ld<E>(s + edge_off(e));
+  }
+#pragma unroll
+  for (int u = 0; u < RB; ++u) {
+    const uint32_t i = tid + u * nt;
+    if (i < body) bv[u] = ld<-16>(s2 + i * 16u);
+  }
+#pragma unroll
+  for (int u = 0; u < RE; ++u) {
+    const uint32_t e = tid + u * nt;
+    if (e < ne) st<E>(d + edge_off(e), ev[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < RB; ++u) {
+    const uint32_t i = tid + u * nt;
+    if (i < body) st<16>(d2 + i * 16u, bv[u]);
+  }
+  // what the first round did not reach (few threads on a long or byte-aligned run)
+  for (uint32_t e = tid + RE * nt; e < ne; e += nt) st<E>(d + edge_off(e), ld<E>(s + edge_off(e)));
+  for (uint32_t base = tid + RB * nt; base < body; base += RB * nt) {
+#pragma unroll
+    for (int u = 0; u < RB; ++u) {
+      const uint32_t i = base + u * nt;
+      if (i < body) bv[u] = ld<-16>(s2 + i * 16u);
+    }
+#pragma unroll
+    for (int u = 0; u < RB; ++u) {
+      const uint32_t i = base + u * nt;
+      if (i < body) st<16>(d2 + i * 16u, bv[u]);
+    }
+  }
+}
+
+// rows of `run` >= 16 bytes where 16-byte alignment does not hold everywhere, as copy_rows_unaligned
+__device__ __forceinline__ void small_rows_unaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
+                                                     uint32_t run, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
+  const uint32_t body = run >> 4, tail = run & 15u;
+  small_rows<-16>(s, d, nrows, body, sp, dp, tid, nt);
+  if (tail) {
+    const size_t off = (size_t)body << 4;
+    const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run | (uintptr_t)sp | (uintptr_t)dp;
+    if ((al & 3u) == 0) small_rows<4>(s + off, d + off, nrows, tail >> 2, sp, dp, tid, nt);
+    else small_rows<1>(s + off, d + off, nrows, tail, sp, dp, tid, nt);
+  }
+}
+
+// na x nb elements of `e` bytes moved as granules of E bytes (E == e, or E == 1 when the addresses
+// are not aligned to the element size); source contiguous along a, destination along b
+template <int E>
+__device__ __forceinline__ void small_transpose(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na,
+                                                uint32_t nb, uint32_t e, int64_t spb, int64_t dpa, uint32_t tid,
+                                                uint32_t nt) {
+  constexpr int R = kRound;
+  typedef typename Granule<E>::type V;
+  const uint32_t per = e / E, total = na * nb * per;
+  for (uint32_t base = tid; base < total; base += R * nt) {
+    V v[R];
+    int64_t dof[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      const uint32_t i = base + u * nt;
+      if (i < total) {
+        const uint32_t el = i / per, by = (i - el * per) * E;
+        const uint32_t b = el / na, a = el - b * na;
+        v[u] = ld<E>(s + (int64_t)a * e + (int64_t)b * spb + by);
+        dof[u] = (int64_t)a * dpa + (int64_t)b * e + by;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      if (base + u * nt < total) st<E>(d + dof[u], v[u]);
+  }
+}
+
+// threads a small tile wants: one per kRound items of the granule its alignment allows (the
+// choice of granule mirrors process_tile)
+__device__ __forceinline__ uint32_t small_tile_threads(const TileDesc& T, gsrc_t s, gdst_t d) {
+  uint32_t items;
+  if ((T.kind & 0xffu) == kTranspose) {
+    const uint32_t e = (T.kind >> 8) & 0xffu;
+    const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)T.p0 | (uintptr_t)T.p1;
+    items = T.a * T.b * ((al & (e - 1)) == 0 ? 1u : e);
+  } else {
+    const uint32_t run = T.a, nrows = T.b;
+    uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
+    if (nrows > 1) al |= (uintptr_t)T.p0 | (uintptr_t)T.p1;
+    if ((al & 15u) == 0) items = nrows * (run >> 4);
+    else if (run >= 64) items = max(nrows * (run >> 4), nrows == 1 ? 3u * kRound : 0u);  // 3 threads cover the
+                                                                // pieces at the two ends of a single run
+    else items = nrows * (run >> ((al & 7u) == 0 ? 3 : (al & 3u) == 0 ? 2 : (al & 1u) == 0 ? 1 : 0));
+  }
+  return (items + kRound - 1) / kRound;
+}
+
 // `nt` threads (tid in [0, nt)) copy one tile: the whole workgroup (WG == true, may use the LDS
-// staging area and barriers) or a single wave (WG == false, no barriers).
-template <bool WG>
+// staging area and barriers) or any group of threads that need not agree on the tile (WG == false,
+// no barriers, nothing assumed uniform across a wave).
+// TR == false: the plan holds no transposed tile that needs the staging area, and the code for
+// them is left out (it would cost the other paths registers).
+template <bool WG, bool TR>
 __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t d, char* lds, uint32_t tid,
                                              uint32_t nt) {
   if ((T.kind & 0xffu) == kTranspose) {
-    const uint32_t e = (T.kind >> 8) & 0xffu, td = T.kind >> 16, na = T.a, nb = T.b;
+    const uint32_t e = (T.kind >> 8) & 0xffu, na = T.a, nb = T.b;
+    const uint32_t tda = 1u << ((T.kind >> 16) & 0xffu), tdb = 1u << (T.kind >> 24);
     const int64_t spb = T.p0, dpa = T.p1;
     const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
-    if (WG && (al & (e - 1)) == 0) {
+    if (WG && TR && (al & (e - 1)) == 0) {
       switch (e) {
-        case 1: transpose_any<1>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 2: transpose_any<2>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 4: transpose_any<4>(s, d, na, nb, spb, dpa, td, lds); break;
-        case 8: transpose_any<8>(s, d, na, nb, spb, dpa, td, lds); break;
-        default: transpose_any<16>(s, d, na, nb, spb, dpa, td, lds); break;
+        case 1: transpose_any<1>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
+        case 2: transpose_any<2>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
+        case 4: transpose_any<4>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
+        case 8: transpose_any<8>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
+        default: transpose_any<16>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
       }
-    } else {  // single wave, or elements not aligned to their own size: plain byte moves
-      const uint32_t total = na * nb * e;
-      for (uint32_t i = tid; i < total; i += nt) {
-        const uint32_t el = i / e, by = i - el * e;
-        const uint32_t b = el / na, a = el - b * na;
-        d[(int64_t)a * dpa + (int64_t)b * e + by] = s[(int64_t)a * e + (int64_t)b * spb + by];
+    } else if (!WG && (al & (e - 1)) == 0) {  // a small tile: no staging, element by element
+      switch (e) {
+        case 1: small_transpose<1>(s, d, na, nb, e, spb, dpa, tid, nt); break;
+        case 2: small_transpose<2>(s, d, na, nb, e, spb, dpa, tid, nt); break;
+        case 4: small_transpose<4>(s, d, na, nb, e, spb, dpa, tid, nt); break;
+        case 8: small_transpose<8>(s, d, na, nb, e, spb, dpa, tid, nt); break;
+        default: small_transpose<16>(s, d, na, nb, e, spb, dpa, tid, nt); break;
       }
+    } else {  // elements not aligned to their own size: byte moves
+      small_transpose<1>(s, d, na, nb, e, spb, dpa, tid, nt);
+    }
+    return;
+  }
+  if (!WG) {
+    const uint32_t run = T.a, nrows = T.b;
+    const int64_t sp = T.p0, dp = T.p1;
+    uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
+    if (nrows > 1) al |= (uintptr_t)sp | (uintptr_t)dp;
+    if ((al & 15u) == 0) {
+      small_rows<16>(s, d, nrows, run >> 4, sp, dp, tid, nt);
+    } else if (run >= 64) {
+      if (nrows > 1) small_rows_unaligned(s, d, nrows, run, sp, dp, tid, nt);
+      else if ((al & 3u) == 0) small_run_misaligned<4>(s, d, run, tid, nt);
+      else small_run_misaligned<1>(s, d, run, tid, nt);
+    } else if ((al & 7u) == 0) {
+      small_rows<8>(s, d, nrows, run >> 3, sp, dp, tid, nt);
+    } else if ((al & 3u) == 0) {
+      small_rows<4>(s, d, nrows, run >> 2, sp, dp, tid, nt);
+    } else if ((al & 1u) == 0) {
+      small_rows<2>(s, d, nrows, run >> 1, sp, dp, tid, nt);
+    } else {
+      small_rows<1>(s, d, nrows, run, sp, dp, tid, nt);
     }
     return;
   }
@@ -319,12 +587,12 @@ struct PtrArgs {
 
 // queue[0]: next batch index; queue[1]: workgroups that are done.  The last workgroup to finish
 // puts both back to zero, so the next launch on this plan needs no memset.
-template <typename PTRS>
+template <bool TR, typename PTRS>
 __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads, uint32_t n_batches,
                                              const TileDesc* __restrict__ tiles, const PTRS& ptr_table,
                                              uint32_t n_src, uint32_t n_ptrs, unsigned long long* queue,
                                              int persistent) {
-  __shared__ __attribute__((aligned(16))) char lds[kLdsBytes];
+  extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ uint64_t lds_ptrs[kLdsPtrs];
   __shared__ uint32_t slot[2];
   // ranged launch (a chunk of a source blob has arrived): the lookup kernel left the first batch in
@@ -341,17 +609,55 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
     const uint64_t p = ptrs_in_lds ? lds_ptrs[n_src + T.dst_buf] : ptr_table[n_src + T.dst_buf];
     return (gdst_t)p + T.dst_off;
   };
-  // one batch: a single tile for the whole workgroup, or several small tiles dealt to the waves
+  // One batch: a single tile for the whole workgroup, or several small tiles.  Small tiles are
+  // latency bound (descriptor load, then data load, then store, a few hundred bytes each), so the
+  // whole batch is kept in flight at once: the threads fetch one descriptor each into LDS, every
+  // tile is given one thread per round of items (a scan over the workgroup turns the counts into
+  // thread ranges), and each thread looks up the tile it works for.
   auto run_batch = [&](const TileDesc& H) {
     if (H.count == 1) {
-      process_tile<true>(H, src_of(H), dst_of(H), lds, threadIdx.x, blockDim.x);
-    } else {
-      const uint32_t wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6, lane = threadIdx.x & 63u;
-      for (uint32_t j = wave; j < H.count; j += n_waves) {
-        const uint32_t t = __builtin_amdgcn_readfirstlane(H.first + j);
-        const TileDesc T = tiles[t];
-        process_tile<false>(T, src_of(T), dst_of(T), lds, lane, 64);
+      process_tile<true, TR>(H, src_of(H), dst_of(H), lds, threadIdx.x, blockDim.x);
+      return;
+    }
+    const uint32_t nthr = blockDim.x, tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    TileDesc* ldesc = reinterpret_cast<TileDesc*>(lds);                              // [nthr]
+    uint32_t* lstart = reinterpret_cast<uint32_t*>(lds + sizeof(TileDesc) * nthr);   // [nthr + 1]
+    uint32_t* lwave = lstart + nthr + 1;                                             // [waves]
+    for (uint32_t base = 0; base < H.count; base += nthr) {
+      const uint32_t n = min(nthr, H.count - base);
+      uint32_t c = 0;
+      if (tid < n) {
+        const TileDesc T = tiles[H.first + base + tid];
+        ldesc[tid] = T;
+        c = small_tile_threads(T, src_of(T), dst_of(T));
+        c = c < 1 ? 1u : (c > nthr ? nthr : c);
       }
+      uint32_t x = c;  // inclusive scan of c: within the wave, then over the waves' totals
+#pragma unroll
+      for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
+        const uint32_t y = __shfl_up(x, dlt);
+        if (lane >= dlt) x += y;
+      }
+      if (lane == 63) lwave[wave] = x;
+      __syncthreads();
+      uint32_t before = 0;
+      for (uint32_t w = 0; w < wave; ++w) before += lwave[w];
+      lstart[tid + 1] = before + x;
+      if (tid == 0) lstart[0] = 0;
+      __syncthreads();
+      const uint32_t total = lstart[n];
+      for (uint32_t v = tid; v < total; v += nthr) {
+        uint32_t lo = 0, hi = n;  // the tile j with lstart[j] <= v < lstart[j + 1]
+        while (hi - lo > 1) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (lstart[mid] <= v) lo = mid;
+          else hi = mid;
+        }
+        const TileDesc T = ldesc[lo];
+        const uint32_t t0 = lstart[lo];
+        process_tile<false, TR>(T, src_of(T), dst_of(T), lds, v - t0, lstart[lo + 1] - t0);
+      }
+      __syncthreads();  // the staging area is written again by the next slice or batch
     }
   };
   if (!persistent) {
@@ -398,19 +704,21 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
   }
 }
 
+template <bool TR>
 __global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restrict__ heads, uint32_t n_batches,
                                                          const TileDesc* __restrict__ tiles, PtrArgs ptrs,
                                                          uint32_t n_src, uint32_t n_ptrs, unsigned long long* queue,
                                                          int persistent) {
-  reshard_body(heads, n_batches, tiles, ptrs.p, n_src, n_ptrs, queue, persistent);
+  reshard_body<TR>(heads, n_batches, tiles, ptrs.p, n_src, n_ptrs, queue, persistent);
 }
 
+template <bool TR>
 __global__ __launch_bounds__(kMaxThreads) void k_reshard_table(const TileDesc* __restrict__ heads, uint32_t n_batches,
                                                                const TileDesc* __restrict__ tiles,
                                                                const uint64_t* __restrict__ ptr_table, uint32_t n_src,
                                                                uint32_t n_ptrs, unsigned long long* queue,
                                                                int persistent) {
-  reshard_body(heads, n_batches, tiles, ptr_table, n_src, n_ptrs, queue, persistent);
+  reshard_body<TR>(heads, n_batches, tiles, ptr_table, n_src, n_ptrs, queue, persistent);
 }
 
 // Batches of a source-ordered plan whose key lies in [key_lo, key_hi): the queue starts at the
@@ -486,16 +794,34 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_
     grid = (unsigned)plan.n_batches;
   }
   const uint32_t n_ptrs = (uint32_t)(n_src + n_dst);
+  const uint32_t lds_bytes = (std::max(small_batch_lds_bytes((uint32_t)cfg.threads), plan.lds_transpose) + 15u) & ~15u;
+  if (lds_bytes > kMaxDynamicLds) {
+    set_error("the plan needs more LDS than a workgroup can have");
+    return BCP_ERR_INVALID_ARG;
+  }
+  static const hipError_t lds_attr = [] {
+    const void* fns[] = {reinterpret_cast<const void*>(&k_reshard<false>), reinterpret_cast<const void*>(&k_reshard<true>),
+                         reinterpret_cast<const void*>(&k_reshard_table<false>),
+                         reinterpret_cast<const void*>(&k_reshard_table<true>)};
+    for (const void* f : fns) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxDynamicLds);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }();
+  BCP_HIP(lds_attr);
+  const bool tr = plan.lds_transpose != 0;
+  const dim3 g(grid), b((unsigned)cfg.threads);
   if (!table) {
     PtrArgs args;
     for (int32_t i = 0; i < n_src; ++i) args.p[i] = (uint64_t)(uintptr_t)src[i];
     for (int32_t i = 0; i < n_dst; ++i) args.p[n_src + i] = (uint64_t)(uintptr_t)dst[i];
     for (uint32_t i = n_ptrs; i < (uint32_t)kArgPtrs; ++i) args.p[i] = 0;
-    hipLaunchKernelGGL(k_reshard, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.heads,
+    hipLaunchKernelGGL(tr ? k_reshard<true> : k_reshard<false>, g, b, lds_bytes, stream, plan.heads,
                        (uint32_t)plan.n_batches, plan.tiles, args, (uint32_t)n_src, n_ptrs, plan.queue,
                        cfg.persistent);
   } else {
-    hipLaunchKernelGGL(k_reshard_table, dim3(grid), dim3((unsigned)cfg.threads), 0, stream, plan.heads,
+    hipLaunchKernelGGL(tr ? k_reshard_table<true> : k_reshard_table<false>, g, b, lds_bytes, stream, plan.heads,
                        (uint32_t)plan.n_batches, plan.tiles, (const uint64_t*)table, (uint32_t)n_src, n_ptrs,
                        plan.queue, cfg.persistent);
   }

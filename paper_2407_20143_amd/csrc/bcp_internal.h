@@ -45,7 +45,8 @@ struct Region {
   uint32_t rows_per_tile;    // kRows, run < tile_bytes: rows of the last row dimension per tile
   uint32_t segs_per_row;     // kRows, run >= tile_bytes: tiles per row
   uint32_t tiles_per_group;  // tiles per index of the leading row dimensions
-  uint32_t tdim;             // kTranspose: tile edge in elements
+  uint32_t tdim_a, tdim_b;   // kTranspose: tile edges in elements (powers of two) along the
+                             // source-contiguous / destination-contiguous dimension
   uint32_t tiles_b;          // kTranspose: tiles along the last dimension
   uint32_t lead_mod;         // kRows, long rows: cut segments where the destination offset is a
                              // multiple of this (0: offsets are aligned anyway, cut at multiples of
@@ -68,7 +69,7 @@ struct TileDesc {
   int64_t p0, p1;
   uint32_t a, b;
   uint32_t src_buf, dst_buf;
-  uint32_t kind;             // RegionKind | esize << 8 | tile edge (kTranspose) << 16
+  uint32_t kind;             // RegionKind | esize << 8 | kTranspose: log2 of the full tile's edges, a << 16, b << 24
   uint32_t first;            // heads[] only: index of the batch's first tile
   uint32_t count;            // heads[] only: tiles in the batch
   uint32_t pad_;
@@ -91,6 +92,7 @@ struct Ctl {
   long long max_src_buf, max_dst_buf;
   unsigned long long dims_hist[kDims + 1];
   unsigned long long max_src_end;  // one past the highest source byte offset any region reads
+  unsigned long long lds_transpose;  // LDS staging bytes the largest transposed tile needs
 };
 
 // device error codes carried in err_key's low byte (mapped to bcp_status on the host)
@@ -131,6 +133,7 @@ struct PlanDevice {
   int64_t n_regions = 0;
   int64_t n_tiles = 0;
   int64_t n_batches = 0;
+  uint32_t lds_transpose = 0;  // LDS staging bytes of the largest transposed tile (0: none)
 };
 
 struct PlannerResult {
@@ -145,6 +148,15 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
 
 // ---- copy (bcp_copy.hip) ---------------------------------------------------------------------
 constexpr int kMaxKernargPtrs = 256;  // buffer pointers that travel as kernel arguments
+// Edges, in elements, of the tiles of a transposed region, by element size: 64 KiB of payload,
+// runs of 512 bytes on both sides where that allows it.
+constexpr uint32_t transpose_edge_a(uint32_t esize) { return esize <= 2 ? 256u : (esize <= 8 ? 128u : 64u); }
+constexpr uint32_t transpose_edge_b(uint32_t esize) { return esize <= 2 ? 256u : (esize <= 4 ? 128u : 64u); }
+// LDS staging of one tile: tdim_a rows (one per index along a) of tdim_b elements plus one
+// element of padding, which spreads a column over the banks
+constexpr uint32_t transpose_lds_bytes(uint32_t tdim_a, uint32_t tdim_b, uint32_t esize) {
+  return tdim_a * (tdim_b + 1) * esize;
+}
 bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
                           int32_t n_dst, const void* table, hipStream_t stream,
                           const uint64_t* key_range = nullptr);

@@ -456,7 +456,8 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   R->tile_bytes = tile_bytes;
   R->rows_per_tile = 1;
   R->segs_per_row = 1;
-  R->tdim = 0;
+  R->tdim_a = 0;
+  R->tdim_b = 0;
   R->tiles_b = 0;
   R->lead_mod = 0;
   for (int k = 0; k < kDims; ++k) {
@@ -491,12 +492,12 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
       ++nd;
     }
     R->ndim = nd;
-    // tile edge: the longest runs on both sides that the LDS staging area (128 x 129 x 8 bytes) holds
-    const uint32_t td = e <= 2 ? 256u : (e <= 8 ? 128u : 64u);
-    R->tdim = td;
-    const uint64_t ta = ((uint64_t)L[a] + td - 1) / td, tb = ((uint64_t)L[b] + td - 1) / td;
+    const uint32_t tda = transpose_edge_a((uint32_t)e), tdb = transpose_edge_b((uint32_t)e);
+    R->tdim_a = tda;
+    R->tdim_b = tdb;
     uint64_t groups = 1;
     for (int k = 0; k < nd - 2; ++k) groups *= (uint64_t)R->len[k];
+    const uint64_t ta = ((uint64_t)L[a] + tda - 1) / tda, tb = ((uint64_t)L[b] + tdb - 1) / tdb;
     R->tiles_b = (uint32_t)(tb < 0xffffffffull ? tb : 0xffffffffull);
     const uint64_t tpg = ta * tb;
     R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
@@ -548,7 +549,7 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
 // plan statistics are summed per workgroup in LDS first: one global atomic per counter and
 // workgroup instead of one per region
 struct BlockStats {
-  ull payload, transposed, dims[kDims + 1], src_end;
+  ull payload, transposed, dims[kDims + 1], src_end, lds_transpose;
   long long max_src, max_dst;
 };
 
@@ -568,6 +569,7 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
     for (int k = 0; k <= kDims; ++k) bs.dims[k] = 0;
     bs.max_src = bs.max_dst = -1;
     bs.src_end = 0;
+    bs.lds_transpose = 0;
   }
   const uint64_t p = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   bool hit = false;
@@ -604,7 +606,10 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
     atomicAdd(&cov[tb->rec], (ull)vol);
     atomicAdd(&bs.payload, (ull)vol * (ull)tb->itemsize);
     atomicAdd(&bs.dims[R.ndim + (R.kind == kRows && R.run_bytes > tb->itemsize ? 1 : 0)], 1ull);
-    if (R.kind == kTranspose) atomicAdd(&bs.transposed, 1ull);
+    if (R.kind == kTranspose) {
+      atomicAdd(&bs.transposed, 1ull);
+      atomicMax(&bs.lds_transpose, (ull)transpose_lds_bytes(R.tdim_a, R.tdim_b, (uint32_t)R.run_bytes));
+    }
     ull send = (ull)(R.src_base + R.run_bytes);
     for (int k = 0; k < R.ndim; ++k) send += (ull)((R.len[k] - 1) * R.spitch[k]);
     atomicMax(&bs.src_end, send);
@@ -615,7 +620,10 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
   __syncthreads();
   if (threadIdx.x == 0 && (wcnt[0] | wcnt[1] | wcnt[2] | wcnt[3])) {
     atomicAdd(&ctl->payload_bytes, bs.payload);
-    if (bs.transposed) atomicAdd(&ctl->n_transposed, bs.transposed);
+    if (bs.transposed) {
+      atomicAdd(&ctl->n_transposed, bs.transposed);
+      atomicMax(&ctl->lds_transpose, bs.lds_transpose);
+    }
     for (int k = 0; k <= kDims; ++k)
       if (bs.dims[k]) atomicAdd(&ctl->dims_hist[k], bs.dims[k]);
     atomicMax(&ctl->max_src_end, bs.src_end);
@@ -660,15 +668,16 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
       so += (int64_t)c * R.spitch[k];
       dof += (int64_t)c * R.dpitch[k];
     }
-    const uint32_t td = R.tdim;
+    const uint32_t tda = R.tdim_a, tdb = R.tdim_b;
     const uint32_t ta = w / R.tiles_b, tb = w - ta * R.tiles_b;
-    const uint64_t a0 = (uint64_t)ta * td, b0 = (uint64_t)tb * td;
+    const uint64_t a0 = (uint64_t)ta * tda, b0 = (uint64_t)tb * tdb;
     const uint64_t ra = (uint64_t)R.len[nd - 2] - a0, rb = (uint64_t)R.len[nd - 1] - b0;
-    t.a = (uint32_t)(ra < td ? ra : td);
-    t.b = (uint32_t)(rb < td ? rb : td);
+    t.a = (uint32_t)(ra < tda ? ra : tda);
+    t.b = (uint32_t)(rb < tdb ? rb : tdb);
     t.p0 = R.spitch[nd - 1];
     t.p1 = R.dpitch[nd - 2];
-    t.kind |= ((uint32_t)R.run_bytes << 8) | (td << 16);
+    t.kind |= ((uint32_t)R.run_bytes << 8) | ((uint32_t)(31 - __clz((int)tda)) << 16) |
+              ((uint32_t)(31 - __clz((int)tdb)) << 24);
     bytes = (uint64_t)t.a * t.b * (uint64_t)R.run_bytes;
     so += (int64_t)a0 * R.spitch[nd - 2] + (int64_t)b0 * R.spitch[nd - 1];
     dof += (int64_t)a0 * R.dpitch[nd - 2] + (int64_t)b0 * R.dpitch[nd - 1];
@@ -883,8 +892,9 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   BCP_HIP(ws.alloc(&recs, (size_t)n_total));
   BCP_HIP(ws.alloc(&ctl, 1));
   BCP_HIP(ws.alloc(&box_start, (size_t)n_total + 1));
-  if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, hipMemcpyHostToDevice, st));
-  BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, hipMemcpyHostToDevice, st));
+  const hipMemcpyKind up = (flags & BCP_META_ON_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+  if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, up, st));
+  BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, up, st));
   BCP_HIP(hipMemcpyAsync(ctl, &init, sizeof(Ctl), hipMemcpyHostToDevice, st));
   BCP_HIP(hipEventRecord(ev0, st));
 
@@ -1101,6 +1111,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     out->dev.heads = heads;
     out->dev.n_tiles = (int64_t)n_tiles;
     out->dev.n_batches = (int64_t)n_batches;
+    out->dev.lds_transpose = (uint32_t)h.lds_transpose;
   } else {
     hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
                        (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);

@@ -102,6 +102,25 @@ def test_strided_every_itemsize(dtype):
         assert st["n_transposed"] == 2
 
 
+def test_metadata_already_on_the_device():
+    case = synth.cfg4(layers=2, hidden=136, ffn=344, vocab=1000, dp_s=16, dp_t=12, n_states=1)
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    a = binding.plan(sm, tm)
+    ds, ns = binding.meta_to_device(sm)
+    dt, nt = binding.meta_to_device(tm)
+    b = binding.plan_from_device_meta(ds, ns, dt, nt)
+    assert a.regions().tobytes() == b.regions().tobytes()
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    dsrc = [x.cuda() for x in src]
+    ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    binding.reshard(b, dsrc, ddst)
+    torch.cuda.synchronize()
+    assert_same([t.cpu().numpy() for t in ddst], want, "device metadata")
+    a.destroy()
+    b.destroy()
+
+
 def test_plans_are_reproducible():
     case = synth.cfg5(layers=1, hidden=128, experts=8, ffn=44, n_small=2000)
     sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
