@@ -151,7 +151,11 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved,
  * completed and must not overlap each other.  Asynchronous: enqueues on `stream` (hipStream_t)
  * and returns; errors detectable on the host are returned synchronously.  Calls on one plan must
  * be ordered by the caller (same stream, or synchronised) because they share the plan's pointer
- * tables and queue counter. */
+ * tables and queue counter.
+ * With at most 256 buffers in all (n_src + n_dst of the plan) the call is exactly one kernel launch
+ * that leaves the plan ready for the next one, and may be captured into a HIP graph (call it once
+ * outside the capture first); with more buffers it stages a pointer table through pinned memory
+ * (allocations on first use, a host-to-device copy, possibly a wait) and must not be captured. */
 bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src,
                        void* const* dst_buffers, int32_t n_dst, void* stream);
 
@@ -193,6 +197,13 @@ bcp_status bcp_plan_destroy(bcp_plan_t plan);
  * < 0 keeps the setting.  threads: 256, 512 or 1024 per workgroup (default 1024).  tile_bytes,
  * wg_per_cu, threads <= 0 keep the current setting. */
 bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu, int32_t threads);
+
+/* bcp_plan keeps its temporaries (records, boxes, sort keys, scans) in a process-wide workspace in
+ * device memory that only grows, so that a later plan of the same size allocates nothing.  This
+ * call frees it (it is allocated again on demand); *freed_bytes, if not null, receives what was
+ * released.  Plans already built are not affected.  Waits for no stream: the caller makes sure no
+ * bcp_plan call is in flight on another thread (it would block until that call returned). */
+bcp_status bcp_release_workspace(int64_t* freed_bytes);
 
 /* Plain device-to-device streaming copy with the same vector width and launch shape as the reshard
  * kernel: the practical ceiling the bench reports beside it.  dst/src: device, 16-byte aligned. */

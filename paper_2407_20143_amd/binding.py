@@ -45,7 +45,8 @@ BCP_META_ON_DEVICE = 8
 EXPORTS = [
     "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_dedup_worst_fit", "bcp_plan", "bcp_reshard", "bcp_reshard_arrived",
     "bcp_reshard_from_host", "bcp_plan_stats",
-    "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy", "bcp_configure", "bcp_copy_baseline", "bcp_last_error",
+    "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy", "bcp_configure", "bcp_release_workspace",
+    "bcp_copy_baseline", "bcp_last_error",
     "bcp_status_name", "bcp_abi_version", "bcp_sizeof_shard_meta",
 ]
 
@@ -82,6 +83,7 @@ def lib():
         L.bcp_plan_destroy.argtypes = [vp]
         L.bcp_configure.argtypes = [i64, i32, i32, i32]
         L.bcp_copy_baseline.argtypes = [vp, vp, i64, vp]
+        L.bcp_release_workspace.argtypes = [ctypes.POINTER(ctypes.c_int64)]
         for f in EXPORTS:
             getattr(L, f).restype = ctypes.c_int
         L.bcp_last_error.restype = ctypes.c_char_p
@@ -318,6 +320,13 @@ def reshard_from_host(p: Plan, host_blobs: Sequence, src_blobs: Sequence, dst_bu
 
 def configure(tile_bytes: int = 0, persistent: int = -1, wg_per_cu: int = 0, threads: int = 0) -> None:
     _check(lib().bcp_configure(tile_bytes, persistent, wg_per_cu, threads))
+
+
+def release_workspace() -> int:
+    """bcp_release_workspace: free the planner's grow-only device workspace; returns the bytes released."""
+    n = ctypes.c_int64(0)
+    _check(lib().bcp_release_workspace(ctypes.byref(n)))
+    return n.value
 
 
 DEFAULT_CONFIG = dict(tile_bytes=65536, persistent=1, wg_per_cu=1, threads=1024)

@@ -26,7 +26,10 @@ bcp_status hip_fail(hipError_t e, const char* what) {
   return BCP_ERR_HIP;
 }
 
-PlanConfig& config() { return g_config; }
+PlanConfig config() {
+  std::lock_guard<std::mutex> g(g_config_mu);
+  return g_config;
+}
 
 }  // namespace bcp
 
@@ -77,6 +80,8 @@ const char* bcp_status_name(bcp_status s) {
 
 int32_t bcp_abi_version(void) { return 1; }
 int64_t bcp_sizeof_shard_meta(void) { return (int64_t)sizeof(bcp_shard_meta); }
+
+bcp_status bcp_release_workspace(int64_t* freed_bytes) { return release_workspace(freed_bytes); }
 
 bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu, int32_t threads) {
   std::lock_guard<std::mutex> g(g_config_mu);

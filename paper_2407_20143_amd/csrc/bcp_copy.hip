@@ -2,8 +2,8 @@
 // every payload byte is read once and written once; there is no contraction, hence no MFMA.
 //
 // A tile is at most tile_bytes of payload: a segment of one long row, or a few whole short
-// rows, decoded at plan time into one 64-byte descriptor.  One workgroup per tile.  Per tile the
-// kernel picks, workgroup-uniformly and from the actual addresses, one of
+// rows, decoded at plan time into one 64-byte descriptor.  Per tile the kernel picks, from the
+// actual addresses, one of
 //   * 16-byte vector path   -- bases, run length and pitches all 16-byte aligned;
 //   * misaligned-run path   -- long runs whose source and destination disagree modulo 16 (ZeRO
 //                              slice boundaries): peel to a 16-byte aligned destination, then
@@ -12,11 +12,11 @@
 //   * LDS-staged transpose  -- the source-contiguous and destination-contiguous dimensions
 //                              differ (strided shards): both global sides stay coalesced.
 // Scheduling: a persistent grid of (CU count x wg_per_cu) workgroups pops batch indices from an
-// atomic queue; a batch is one big tile (whole workgroup) or a run of small tiles whose waves
-// each take tiles of their own, so 100k tiny tensors do not cost one queue pop each.  Measured on
-// MI355X, ONE 1024-thread workgroup per CU streaming 64 KiB tiles with non-temporal accesses
-// sustains the highest copy bandwidth: fewer concurrent streams keep more DRAM pages open than a
-// grid of one workgroup per tile.  The head descriptor of the next batch is fetched (scalar loads)
+// atomic queue; a batch is one big tile (whole workgroup) or a run of small tiles that share the
+// workgroup's threads in proportion to their size, so 100k tiny tensors do not cost one queue pop
+// each.  Measured on MI355X, ONE 1024-thread workgroup per CU streaming 64 KiB tiles with
+// non-temporal accesses sustains the highest copy bandwidth of all launch shapes, persistent or
+// one workgroup per tile.  The head descriptor of the next batch is fetched (scalar loads)
 // while the current batch is being copied, and the buffer-pointer table is staged in LDS once per
 // workgroup, so no dependent global load sits between two batches.
 #include <algorithm>

@@ -112,7 +112,7 @@ struct PlanConfig {
   int32_t wg_per_cu = 1;   // persistent grid = wg_per_cu * number of CUs
   int32_t threads = 1024;  // threads per workgroup
 };
-PlanConfig& config();
+PlanConfig config();  // a snapshot of the process-wide setting
 
 void set_error(const std::string& msg);
 bcp_status hip_fail(hipError_t e, const char* what);
@@ -143,6 +143,7 @@ struct PlannerResult {
   float device_ms = 0.f;
 };
 
+bcp_status release_workspace(int64_t* freed_bytes);
 bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shard_meta* target,
                        int64_t n_target, uint32_t flags, hipStream_t stream, PlannerResult* out);
 

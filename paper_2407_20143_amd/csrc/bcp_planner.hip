@@ -172,6 +172,24 @@ struct Workspace {
   }
 };
 Workspace g_ws;
+}  // namespace
+
+bcp_status release_workspace(int64_t* freed_bytes) {
+  std::lock_guard<std::mutex> lock(g_ws.mu);
+  int64_t total = 0;
+  hipError_t first = hipSuccess;
+  for (Workspace::Chunk& c : g_ws.chunks) {
+    total += (int64_t)c.size;
+    const hipError_t e = hipFree(c.base);
+    if (first == hipSuccess) first = e;
+  }
+  g_ws.chunks.clear();
+  if (freed_bytes) *freed_bytes = total;
+  BCP_HIP(first);
+  return BCP_OK;
+}
+
+namespace {
 
 inline unsigned blocks_for(int64_t n, int per_block = kBlock) {
   return (unsigned)std::max<int64_t>(1, (n + per_block - 1) / per_block);

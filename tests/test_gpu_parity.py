@@ -287,6 +287,66 @@ def test_launch_configurations(tile_bytes, persistent, wg, threads):
                                  granules=(4, 16)))
 
 
+@pytest.mark.parametrize("tile_bytes,threads", [(1 << 20, 256), (4 << 20, 1024), (65536, 512), (4096, 1024)])
+def test_small_tile_batches_longer_than_a_workgroup(tile_bytes, threads):
+    """Thousands of tiny tiles per batch: the batch is taken in slices of one tile per thread, and a
+    tile's threads may fall into two rounds of the workgroup."""
+    binding.configure(tile_bytes=tile_bytes, persistent=1, wg_per_cu=1, threads=threads)
+    specs, saved, target = synth.small_tensor_case(3000, seed=77, n_bufs=5, max_shards=12, lo=1, hi=600)
+    case = Case("small_batches", 77, specs, saved, target)
+    st = check_case(case)
+    assert st["n_tiles"] > 4 * st["n_batches"]
+    if tile_bytes >= 1 << 20:
+        assert st["n_tiles"] / st["n_batches"] > threads  # slices really happen
+    # the same through byte-granular packing (1- and 2-byte aligned runs)
+    specs, saved, target = synth.small_tensor_case(800, seed=78, n_bufs=3, max_shards=8, lo=1, hi=300,
+                                                   dtype=torch.uint8, granule=1)
+    check_case(Case("small_batches_u8", 78, specs, saved, target))
+
+
+def test_workspace_can_be_released_and_comes_back():
+    case = synth.cfg2(layers=2, hidden=128, ffn=344, vocab=1000)
+    check_case(case)
+    freed = binding.release_workspace()
+    assert freed > 0
+    assert binding.release_workspace() == 0
+    check_case(case)  # allocated again on demand
+    assert binding.release_workspace() > 0
+
+
+def test_reshard_captured_in_a_hip_graph():
+    """One launch, no memset: a captured bcp_reshard replays correctly, with eager work and other
+    launches on the same plan in between (the kernel's queue rearms itself)."""
+    case = synth.cfg2(layers=2, hidden=256, ffn=688, vocab=2000)
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    p = binding.plan(sm, tm)
+    dsrc = [b.cuda() for b in src]
+    ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    binding.reshard(p, dsrc, ddst)  # eager first: sets the kernel up outside the capture
+    torch.cuda.synchronize()
+    assert_same([t.cpu().numpy() for t in ddst], want, "eager")
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        binding.reshard(p, dsrc, ddst, stream=torch.cuda.current_stream(), check_sizes=False)
+    for i in range(4):
+        for t in ddst:
+            t.fill_(POISON)
+        if i == 2:  # an eager launch on the same plan between two replays
+            binding.reshard(p, dsrc, ddst)
+            torch.cuda.synchronize()
+            for t in ddst:
+                t.fill_(POISON)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert_same([t.cpu().numpy() for t in ddst], want, f"replay {i}")
+    del g
+    p.destroy()
+
+
 def test_plan_replay_on_other_buffers():
     case = synth.cfg2(layers=2, hidden=128, ffn=344, vocab=1000)
     sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)

@@ -23,6 +23,10 @@ def declared_functions():
     return sorted(set(re.findall(r"\b(bcp_[a-z_0-9]+)\s*\(", text)))
 
 
+def test_releasing_an_unused_workspace_is_a_no_op():
+    assert binding.release_workspace() == 0
+
+
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert "bcp_plan" in names and "bcp_reshard" in names and len(names) >= 10
