@@ -188,6 +188,10 @@ bcp_status bcp_plan_regions(bcp_plan_t plan, bcp_region_info* out, int64_t capac
 bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t n_src,
                                    int64_t* dst_extent, int32_t n_dst);
 
+/* Releases the plan.  May be called as soon as the last bcp_reshard* call on the plan has returned,
+ * also while that work is still queued or running: the plan's device blocks go to a small pool from
+ * which later plans are served, ordered behind the work that still reads them (so a plan / destroy
+ * cycle allocates nothing); what the pool does not keep is freed, which waits for the device. */
 bcp_status bcp_plan_destroy(bcp_plan_t plan);
 
 /* Launch configuration of the copy kernel (process-wide; takes effect at the next bcp_plan /
@@ -199,8 +203,9 @@ bcp_status bcp_plan_destroy(bcp_plan_t plan);
 bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu, int32_t threads);
 
 /* bcp_plan keeps its temporaries (records, boxes, sort keys, scans) in a process-wide workspace in
- * device memory that only grows, so that a later plan of the same size allocates nothing.  This
- * call frees it (it is allocated again on demand); *freed_bytes, if not null, receives what was
+ * device memory that only grows, so that a later plan of the same size allocates nothing, and
+ * bcp_plan_destroy keeps a few device blocks of destroyed plans (at most 1 GiB) for the next ones.
+ * This call frees both (they come back on demand); *freed_bytes, if not null, receives what was
  * released.  Plans already built are not affected.  Waits for no stream: the caller makes sure no
  * bcp_plan call is in flight on another thread (it would block until that call returned). */
 bcp_status bcp_release_workspace(int64_t* freed_bytes);

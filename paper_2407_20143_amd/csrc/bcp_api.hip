@@ -55,6 +55,8 @@ struct bcp_plan_s {
   std::mutex mu;
   std::vector<hipEvent_t> chunk_events;  // bcp_reshard_from_host: one per chunk in flight, reused
   std::mutex chunk_mu;
+  bool used = false;                 // a copy kernel was launched on this plan,
+  hipStream_t last_stream = nullptr; // most recently on this stream
 };
 
 extern "C" {
@@ -360,8 +362,9 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
 
 bcp_status bcp_plan_destroy(bcp_plan_t plan) {
   if (!plan) return BCP_OK;
-  if (plan->dev.regions) (void)hipFree(plan->dev.regions);
-  if (plan->dev.heads) (void)hipFree(plan->dev.heads);  // heads, tiles and queue are one allocation
+  // back to the block pool, ordered behind the last launch that reads them
+  block_free(plan->dev.regions, plan->dev.regions_bytes, plan->used, plan->last_stream);
+  block_free(plan->dev.heads, plan->dev.desc_bytes, plan->used, plan->last_stream);  // heads | tiles | queue
   if (plan->table_dev) (void)hipFree(plan->table_dev);
   if (plan->table_host) (void)hipHostFree(plan->table_host);
   for (int i = 0; i < kSlots; ++i)
@@ -469,6 +472,8 @@ static bcp_status reshard_impl(bcp_plan_t plan, const void* const* src_blobs, in
     return BCP_ERR_INVALID_ARG;
   }
   hipStream_t st = (hipStream_t)stream;
+  plan->used = true;
+  plan->last_stream = st;
   if (plan->n_src + plan->n_dst <= kMaxKernargPtrs)
     return launch_reshard(plan->dev, src_blobs, plan->n_src, dst_buffers, plan->n_dst, nullptr, st, key_range);
   std::lock_guard<std::mutex> g(plan->mu);

@@ -134,7 +134,19 @@ struct PlanDevice {
   int64_t n_tiles = 0;
   int64_t n_batches = 0;
   uint32_t lds_transpose = 0;  // LDS staging bytes of the largest transposed tile (0: none)
+  size_t regions_bytes = 0, desc_bytes = 0;  // sizes of the two allocations (regions; heads | tiles | queue | keys)
 };
+
+// Device blocks that plans own.  A destroyed plan's blocks are kept (a few, up to a byte limit) and
+// handed to the next plan that they fit: a plan / destroy cycle then allocates nothing, and
+// allocation is the one step of plan building whose duration is not predictable.
+//   block_alloc: *got receives the block's real size (at least `bytes`); a recycled block is
+//                ordered behind its previous user through an event that `st` waits for.
+//   block_free:  `last_use`: the stream the block's last user ran on (`used` false: none).
+//   block_pool_release: frees the kept blocks, returns their bytes.
+hipError_t block_alloc(void** p, size_t bytes, size_t* got, hipStream_t st);
+void block_free(void* p, size_t bytes, bool used, hipStream_t last_use);
+int64_t block_pool_release();
 
 struct PlannerResult {
   PlanDevice dev;

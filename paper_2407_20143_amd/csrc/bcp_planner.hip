@@ -16,6 +16,7 @@
 // Temporaries live in a process-wide, grow-only workspace, so a plan costs three device
 // allocations of its own (regions, descriptors, queue words) and four host synchronisations.
 #include <algorithm>
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -139,6 +140,7 @@ struct Workspace {
   std::vector<Chunk> chunks;
   std::mutex mu;
   int device = -1;
+  void* landing = nullptr;  // pinned host memory the planner's read-backs arrive in (kLandingBytes)
 
   void reset(int dev) {
     if (dev != device) {  // another device: drop everything (rare)
@@ -184,6 +186,12 @@ bcp_status release_workspace(int64_t* freed_bytes) {
     if (first == hipSuccess) first = e;
   }
   g_ws.chunks.clear();
+  if (g_ws.landing) {
+    const hipError_t e = hipHostFree(g_ws.landing);
+    if (first == hipSuccess) first = e;
+    g_ws.landing = nullptr;
+  }
+  total += block_pool_release();
   if (freed_bytes) *freed_bytes = total;
   BCP_HIP(first);
   return BCP_OK;
@@ -859,13 +867,135 @@ bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
 }
 
 // device memory a plan keeps; freed here on any early return
-struct Owned {
-  void* p[3] = {nullptr, nullptr, nullptr};
+struct Owned {  // plan blocks until the plan takes them over
+  void* p[2] = {nullptr, nullptr};
+  size_t bytes[2] = {0, 0};
+  hipStream_t st = nullptr;
   ~Owned() {
-    for (void* q : p)
-      if (q) (void)hipFree(q);
+    for (int i = 0; i < 2; ++i)
+      if (p[i]) block_free(p[i], bytes[i], true, st);
   }
 };
+
+struct BlockPool {
+  struct Entry {
+    void* p;
+    size_t bytes;
+    int device;
+    hipEvent_t after;  // null: free to use at once
+  };
+  static constexpr size_t kMaxEntries = 8;
+  static constexpr size_t kMaxBytes = (size_t)1 << 30;
+  std::vector<Entry> kept;
+  size_t kept_bytes = 0;
+  std::mutex mu;
+};
+BlockPool g_pool;
+
+}  // namespace
+
+hipError_t block_alloc(void** p, size_t bytes, size_t* got, hipStream_t st) {
+  bytes = std::max<size_t>(bytes, 256);
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  {
+    std::lock_guard<std::mutex> lock(g_pool.mu);
+    int best = -1;
+    for (size_t i = 0; i < g_pool.kept.size(); ++i) {
+      const BlockPool::Entry& c = g_pool.kept[i];
+      if (c.device != dev || c.bytes < bytes || c.bytes > 2 * bytes + ((size_t)1 << 20)) continue;
+      if (best < 0 || c.bytes < g_pool.kept[best].bytes) best = (int)i;
+    }
+    if (best >= 0) {
+      const BlockPool::Entry c = g_pool.kept[best];
+      g_pool.kept.erase(g_pool.kept.begin() + best);
+      g_pool.kept_bytes -= c.bytes;
+      if (c.after) {
+        e = hipStreamWaitEvent(st, c.after, 0);
+        (void)hipEventDestroy(c.after);  // released once the wait has gone through
+        if (e != hipSuccess) {
+          (void)hipFree(c.p);
+          return e;
+        }
+      }
+      *p = c.p;
+      *got = c.bytes;
+      return hipSuccess;
+    }
+  }
+  *got = bytes;
+  return hipMalloc(p, bytes);
+}
+
+void block_free(void* p, size_t bytes, bool used, hipStream_t last_use) {
+  if (!p) return;
+  int dev = 0;
+  bool keep = hipGetDevice(&dev) == hipSuccess;
+  hipEvent_t ev = nullptr;
+  if (keep && used) {
+    keep = hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess;
+    if (keep && hipEventRecord(ev, last_use) != hipSuccess) {
+      (void)hipEventDestroy(ev);
+      keep = false;
+    }
+  }
+  if (keep) {
+    std::lock_guard<std::mutex> lock(g_pool.mu);
+    if (g_pool.kept.size() < BlockPool::kMaxEntries && g_pool.kept_bytes + bytes <= BlockPool::kMaxBytes) {
+      g_pool.kept.push_back(BlockPool::Entry{p, bytes, dev, ev});
+      g_pool.kept_bytes += bytes;
+      return;
+    }
+  }
+  if (ev) (void)hipEventDestroy(ev);
+  (void)hipFree(p);  // waits for the device, so a block still in use is safe here too
+}
+
+int64_t block_pool_release() {
+  std::lock_guard<std::mutex> lock(g_pool.mu);
+  const int64_t total = (int64_t)g_pool.kept_bytes;
+  for (BlockPool::Entry& c : g_pool.kept) {
+    if (c.after) (void)hipEventDestroy(c.after);
+    (void)hipFree(c.p);
+  }
+  g_pool.kept.clear();
+  g_pool.kept_bytes = 0;
+  return total;
+}
+
+namespace {
+
+// What the host needs between two phases -- the control block and up to three totals that sit at
+// the end of scanned arrays -- gathered into one struct, so that it comes back with a single copy
+// into pinned memory instead of one staged copy per value.
+struct Readback {
+  Ctl ctl;
+  uint64_t v[3];
+};
+constexpr size_t kLandingBytes = 4096;
+static_assert(sizeof(Readback) <= kLandingBytes, "landing buffer");
+
+__global__ void k_readback(const Ctl* ctl, const void* p0, int w0, const void* p1, int w1, const void* p2, int w2,
+                           Readback* out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  out->ctl = *ctl;
+  const void* p[3] = {p0, p1, p2};
+  const int w[3] = {w0, w1, w2};
+  for (int i = 0; i < 3; ++i)
+    out->v[i] = !p[i] ? 0 : (w[i] == 8 ? *(const uint64_t*)p[i] : (uint64_t) * (const uint32_t*)p[i]);
+}
+
+// Synchronises the stream.  pK: device address of a 4-byte (wK == 4) or 8-byte value, or null.
+bcp_status read_back(Workspace& ws, hipStream_t st, const Ctl* ctl, Readback* dev, Readback* host, const void* p0 = nullptr,
+                     int w0 = 4, const void* p1 = nullptr, int w1 = 4, const void* p2 = nullptr, int w2 = 4) {
+  hipLaunchKernelGGL(k_readback, dim3(1), dim3(1), 0, st, ctl, p0, w0, p1, w1, p2, w2, dev);
+  BCP_HIP(hipGetLastError());
+  BCP_HIP(hipMemcpyAsync(ws.landing, dev, sizeof(Readback), hipMemcpyDeviceToHost, st));
+  BCP_HIP(hipStreamSynchronize(st));
+  std::memcpy(host, ws.landing, sizeof(Readback));
+  return BCP_OK;
+}
 
 }  // namespace
 
@@ -892,6 +1022,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   Workspace& ws = g_ws;
   ws.reset(dev);
   Owned owned;
+  owned.st = st;
 
   hipEvent_t ev0, ev1;
   BCP_HIP(hipEventCreate(&ev0));
@@ -904,11 +1035,15 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     }
   } evg{ev0, ev1};
 
+  if (!ws.landing) BCP_HIP(hipHostMalloc(&ws.landing, kLandingBytes, hipHostMallocDefault));
   bcp_shard_meta* recs = nullptr;
   Ctl* ctl = nullptr;
+  Readback* rb_dev = nullptr;
+  Readback rb;
   uint32_t* box_start = nullptr;
   BCP_HIP(ws.alloc(&recs, (size_t)n_total));
   BCP_HIP(ws.alloc(&ctl, 1));
+  BCP_HIP(ws.alloc(&rb_dev, 1));
   BCP_HIP(ws.alloc(&box_start, (size_t)n_total + 1));
   const hipMemcpyKind up = (flags & BCP_META_ON_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
   if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, up, st));
@@ -920,14 +1055,10 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total)), dim3(kBlock), 0, st, recs, n_saved, n_total, box_start, ctl);
   BCP_HIP(hipGetLastError());
   if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, ws, st)) return s;
-  Ctl h{};
-  uint32_t nb_host[2] = {0, 0};
-  BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-  BCP_HIP(hipMemcpyAsync(&nb_host[0], box_start + n_saved, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-  BCP_HIP(hipMemcpyAsync(&nb_host[1], box_start + n_total, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-  BCP_HIP(hipStreamSynchronize(st));
+  if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, box_start + n_saved, 4, box_start + n_total, 4)) return s;
+  Ctl h = rb.ctl;
   if (bcp_status s = device_error(h, n_saved)) return s;
-  const int64_t nbs = nb_host[0], nbt = (int64_t)nb_host[1] - nb_host[0], nbx = nb_host[1];
+  const int64_t nbs = (int64_t)rb.v[0], nbt = (int64_t)(rb.v[1] - rb.v[0]), nbx = (int64_t)rb.v[1];
   out->n_saved_boxes = nbs;
   out->n_target_boxes = nbt;
   if (nbt == 0) {
@@ -984,10 +1115,9 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
                        (flags & BCP_SKIP_OVERLAP_CHECK) ? 0 : 1, ctl);
     BCP_HIP(hipGetLastError());
   }
-  uint64_t n_pairs = 0;
-  BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-  BCP_HIP(hipMemcpyAsync(&n_pairs, pair_start + nbt, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-  BCP_HIP(hipStreamSynchronize(st));
+  if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, pair_start + nbt, 8)) return s;
+  h = rb.ctl;
+  const uint64_t n_pairs = rb.v[0];
   if (bcp_status s = device_error(h, n_saved)) return s;
   if (n_pairs >= (1ull << 31) * kBlock) {
     set_error("too many candidate pairs");
@@ -1010,11 +1140,11 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk_pairs, ws, st)) return s;
     size_t cap = (size_t)n_pairs;
     if (cap * sizeof(Region) > ((size_t)64 << 20)) {
-      BCP_HIP(hipMemcpyAsync(&n_regions, blk + nblk_pairs, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-      BCP_HIP(hipStreamSynchronize(st));
+      if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, blk + nblk_pairs, 4)) return s;
+      n_regions = (uint32_t)rb.v[0];
       cap = n_regions;
     }
-    BCP_HIP(hipMalloc(&owned.p[0], std::max<size_t>(cap, 1) * sizeof(Region)));
+    BCP_HIP(block_alloc(&owned.p[0], std::max<size_t>(cap, 1) * sizeof(Region), &owned.bytes[0], st));
     regions = (Region*)owned.p[0];
     BCP_HIP(ws.alloc(&tile_start, cap + 1));
     // slots beyond the region count stay zero so that the scan below may run over `cap` entries
@@ -1027,11 +1157,10 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     BCP_HIP(hipGetLastError());
     if (bcp_status s = device_scan<uint64_t, uint64_t>(tile_start, tile_start, (int64_t)cap, ws, st)) return s;
     // tile total and region count                                                         (sync 4)
-    uint64_t n_tiles = 0;
-    BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-    BCP_HIP(hipMemcpyAsync(&n_tiles, tile_start + cap, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-    BCP_HIP(hipMemcpyAsync(&n_regions, blk + nblk_pairs, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-    BCP_HIP(hipStreamSynchronize(st));
+    if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, tile_start + cap, 8, blk + nblk_pairs, 4)) return s;
+    h = rb.ctl;
+    const uint64_t n_tiles = rb.v[0];
+    n_regions = (uint32_t)rb.v[1];
     if (bcp_status s = device_error(h, n_saved)) return s;
     if (n_tiles >= 0xffffffffull) {
       set_error("too many tiles; raise tile_bytes with bcp_configure");
@@ -1046,7 +1175,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       const bool by_source = (flags & BCP_ORDER_BY_SOURCE) != 0;
       // one allocation: heads | tiles | queue words | (source-ordered plans) one key per batch
       const size_t desc_bytes = sizeof(TileDesc) * 2 * (size_t)n_tiles;
-      BCP_HIP(hipMalloc(&owned.p[1], desc_bytes + 64 + (by_source ? sizeof(uint64_t) * (size_t)n_tiles : 0)));
+      BCP_HIP(block_alloc(&owned.p[1], desc_bytes + 64 + (by_source ? sizeof(uint64_t) * (size_t)n_tiles : 0),
+                          &owned.bytes[1], st));
       heads = (TileDesc*)owned.p[1];
       tiles = heads + n_tiles;
       out->dev.queue = (unsigned long long*)(tiles + n_tiles);
@@ -1119,10 +1249,11 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, regions, tile_region, tile_local, weight,
                          bflags, bstart, n_tiles, tiles, heads, key, out->dev.batch_key);
       BCP_HIP(hipGetLastError());
-      BCP_HIP(hipMemcpyAsync(&n_batches, bflags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+      BCP_HIP(hipMemcpyAsync(ws.landing, bflags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     }
     BCP_HIP(hipEventRecord(ev1, st));
     BCP_HIP(hipStreamSynchronize(st));                                                 // (final sync)
+    if (n_tiles > 0) std::memcpy(&n_batches, ws.landing, sizeof(uint32_t));
     BCP_HIP(hipEventElapsedTime(&out->device_ms, ev0, ev1));
     h.n_tiles = n_tiles;
     out->dev.tiles = tiles;
@@ -1134,8 +1265,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
                        (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);
     BCP_HIP(hipGetLastError());
-    BCP_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-    BCP_HIP(hipStreamSynchronize(st));
+    if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb)) return s;
+    h = rb.ctl;
     if (bcp_status s = device_error(h, n_saved)) return s;
   }
 
@@ -1144,6 +1275,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   out->ctl = h;
   out->dev.regions = regions;
   out->dev.n_regions = n_regions;
+  out->dev.regions_bytes = owned.bytes[0];
+  out->dev.desc_bytes = owned.bytes[1];
   owned.p[0] = owned.p[1] = nullptr;  // the plan owns them now
   return BCP_OK;
 }

@@ -304,6 +304,32 @@ def test_small_tile_batches_longer_than_a_workgroup(tile_bytes, threads):
     check_case(Case("small_batches_u8", 78, specs, saved, target))
 
 
+def test_plan_destroyed_right_after_its_launch():
+    """Destroying a plan while its copy is still queued is legal: its device blocks are recycled by the
+    next plan (same sizes here, so it does take them), ordered behind the copy that still reads them."""
+    binding.release_workspace()
+    case = synth.cfg2(layers=4, hidden=512, ffn=1376, vocab=3000)
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    dsrc = [b.cuda() for b in src]
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for rnd in range(6):
+        st = s1 if rnd % 2 == 0 else s2
+        ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+        torch.cuda.synchronize()
+        p = binding.plan(sm, tm, stream=st)
+        for _ in range(3):  # keep the stream busy past the destroy
+            binding.reshard(p, dsrc, ddst, stream=st)
+        p.destroy()
+        outs.append(ddst)
+    torch.cuda.synchronize()
+    for rnd, ddst in enumerate(outs):
+        assert_same([t.cpu().numpy() for t in ddst], want, f"round {rnd}")
+    assert binding.release_workspace() > 0
+
+
 def test_workspace_can_be_released_and_comes_back():
     case = synth.cfg2(layers=2, hidden=128, ffn=344, vocab=1000)
     check_case(case)
