@@ -61,7 +61,7 @@ struct Region {
 //               p0 along b, the destination contiguous along b with pitch p1 along a
 //
 // The queue of the copy kernel hands out BATCHES: one big tile, or a run of consecutive small
-// tiles (each below kSmallTileBytes, together about one tile budget) that the waves of a
+// tiles (each below kSmallTileBytes, together about one tile budget) that the threads of a
 // workgroup share.  `heads[batch]` is a copy of the batch's first tile descriptor with `first`
 // and `count` filled in, so the kernel still needs one descriptor load per queue pop.
 struct TileDesc {

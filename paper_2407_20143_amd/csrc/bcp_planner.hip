@@ -141,11 +141,17 @@ struct Workspace {
   std::mutex mu;
   int device = -1;
   void* landing = nullptr;  // pinned host memory the planner's read-backs arrive in (kLandingBytes)
+  hipEvent_t ev[2] = {nullptr, nullptr};  // bracket the planner's device work (reused from plan to plan)
 
   void reset(int dev) {
-    if (dev != device) {  // another device: drop everything (rare)
+    if (dev != device) {  // another device: drop everything that belongs to the old one (rare)
       for (Chunk& c : chunks) (void)hipFree(c.base);
       chunks.clear();
+      for (hipEvent_t& e : ev)
+        if (e) {
+          (void)hipEventDestroy(e);
+          e = nullptr;
+        }
       device = dev;
     }
     for (Chunk& c : chunks) c.used = 0;
@@ -191,6 +197,11 @@ bcp_status release_workspace(int64_t* freed_bytes) {
     if (first == hipSuccess) first = e;
     g_ws.landing = nullptr;
   }
+  for (hipEvent_t& e : g_ws.ev)
+    if (e) {
+      (void)hipEventDestroy(e);
+      e = nullptr;
+    }
   total += block_pool_release();
   if (freed_bytes) *freed_bytes = total;
   BCP_HIP(first);
@@ -1024,16 +1035,9 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   Owned owned;
   owned.st = st;
 
-  hipEvent_t ev0, ev1;
-  BCP_HIP(hipEventCreate(&ev0));
-  BCP_HIP(hipEventCreate(&ev1));
-  struct EvGuard {
-    hipEvent_t a, b;
-    ~EvGuard() {
-      (void)hipEventDestroy(a);
-      (void)hipEventDestroy(b);
-    }
-  } evg{ev0, ev1};
+  for (hipEvent_t& e : ws.ev)
+    if (!e) BCP_HIP(hipEventCreate(&e));
+  const hipEvent_t ev0 = ws.ev[0], ev1 = ws.ev[1];
 
   if (!ws.landing) BCP_HIP(hipHostMalloc(&ws.landing, kLandingBytes, hipHostMallocDefault));
   bcp_shard_meta* recs = nullptr;
