@@ -136,7 +136,7 @@ bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_o
 
 /* Build a copy plan on the current HIP device (Sec. 3.3 Step 2 on the GPU).
  * saved/target: host arrays (device arrays with BCP_META_ON_DEVICE), borrowed for the duration of
- * the call.  stream: hipStream_t
+ * the call; with very many records (the upload is 304 bytes each) pinned host memory pays.  stream: hipStream_t
  * (0 == default stream) the planner kernels run on; the call returns after they finished, so
  * the plan is usable on any stream.  On success *out_plan owns device memory until
  * bcp_plan_destroy.  Saved FQNs no target asks for are ignored.  A plan is immutable and may be
