@@ -54,8 +54,13 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        # ORACLE_LIB_OVERRIDE: the mutation test (tests/test_oracle_mutants.py) runs the pins against
+        # deliberately broken builds of the oracle to show that they notice
+        path = os.environ.get("ORACLE_LIB_OVERRIDE")
+        if not path:
+            build()
+            path = _LIB
+        _lib = ctypes.CDLL(path)
         _lib.orc_reshard.restype = ctypes.c_int
         _lib.orc_reshard.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
