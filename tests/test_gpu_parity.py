@@ -62,6 +62,20 @@ def test_random_layouts(seed, modes):
     check_case(synth.random_case(100 + seed, n_tensors=8, max_elems=20000, saved_mode=modes[0], target_mode=modes[1]))
 
 
+def test_random_soak():
+    """120 more random cases in one test: every mix of grid / flat sides, ranks up to 6, strided
+    shards, all packing granules, under the default launch shape and a small-tile one."""
+    modes = ("grid", "flat")
+    for i in range(120):
+        seed = 9000 + i
+        if i == 60:
+            binding.configure(tile_bytes=4096, persistent=1, wg_per_cu=2, threads=256)
+        sm, tm = modes[i & 1], modes[(i >> 1) & 1]
+        strided = 0.5 if (sm, tm) == ("grid", "grid") and i % 3 == 0 else 0.0
+        check_case(synth.random_case(seed, n_tensors=4 + i % 5, max_elems=2000 + 500 * (i % 7), saved_mode=sm,
+                                     target_mode=tm, max_rank=2 + i % 5, p_strided=strided))
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_random_strided(seed):
     check_case(synth.random_case(200 + seed, n_tensors=6, max_elems=30000, p_strided=0.6, granules=(4, 8, 16)))
