@@ -31,6 +31,28 @@ PlanConfig config() {
   return g_config;
 }
 
+// No exception leaves the library: every entry point that can allocate on the host is a function
+// try block that ends here.
+static bcp_status on_exception(const char* who) noexcept {
+  try {
+    throw;
+  } catch (const std::bad_alloc&) {
+    try {
+      set_error(std::string(who) + ": out of host memory");
+    } catch (...) {
+    }
+    return BCP_ERR_OOM;
+  } catch (const std::exception& e) {
+    try {
+      set_error(std::string(who) + ": " + e.what());
+    } catch (...) {
+    }
+    return BCP_ERR_INVALID_ARG;
+  } catch (...) {
+    return BCP_ERR_INVALID_ARG;
+  }
+}
+
 }  // namespace bcp
 
 using namespace bcp;
@@ -85,7 +107,7 @@ int64_t bcp_sizeof_shard_meta(void) { return (int64_t)sizeof(bcp_shard_meta); }
 
 bcp_status bcp_release_workspace(int64_t* freed_bytes) { return release_workspace(freed_bytes); }
 
-bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu, int32_t threads) {
+bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_cu, int32_t threads) try {
   std::lock_guard<std::mutex> g(g_config_mu);
   if (tile_bytes > 0) {
     if (tile_bytes < 4096 || tile_bytes > (4 << 20) || (tile_bytes & (tile_bytes - 1))) {
@@ -110,11 +132,13 @@ bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_
     g_config.threads = threads;
   }
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_configure");
 }
 
 // ---- a1: flat slice of a concatenation -> per-tensor records ----------------------------------
 bcp_status bcp_meta_from_flat_slice(const bcp_shard_meta* params, int64_t n_params, int64_t A, int64_t B,
-                                    int32_t buf, int64_t byte_offset, bcp_shard_meta* out, int64_t* inout_n) {
+                                    int32_t buf, int64_t byte_offset, bcp_shard_meta* out, int64_t* inout_n) try {
   if (!inout_n || n_params < 0 || (n_params > 0 && !params) || A < 0 || B < A || buf < 0 || byte_offset < 0) {
     set_error("bcp_meta_from_flat_slice: bad argument");
     return BCP_ERR_INVALID_ARG;
@@ -167,10 +191,12 @@ bcp_status bcp_meta_from_flat_slice(const bcp_shard_meta* params, int64_t n_para
     return BCP_ERR_INVALID_ARG;
   }
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_meta_from_flat_slice");
 }
 
 // ---- a2: host mirror of the device decomposer ---------------------------------------------------
-bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, int64_t* inout_n) {
+bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, int64_t* inout_n) try {
   if (!rec || !inout_n) {
     set_error("bcp_decompose: null argument");
     return BCP_ERR_INVALID_ARG;
@@ -224,6 +250,8 @@ bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, i
     out_boxes[j] = b;
   }
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_decompose");
 }
 
 // ---- save-side deduplication (Worst-Fit) ----------------------------------------------------------
@@ -257,7 +285,7 @@ struct ShardIdentityHash {
 }  // namespace
 
 bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_of, int64_t n, int32_t n_ranks,
-                               uint8_t* keep, int64_t* load) {
+                               uint8_t* keep, int64_t* load) try {
   if (n < 0 || n_ranks <= 0 || (n > 0 && (!recs || !rank_of || !keep))) {
     set_error("bcp_dedup_worst_fit: bad argument");
     return BCP_ERR_INVALID_ARG;
@@ -292,11 +320,13 @@ bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_o
   if (load)
     for (int32_t r = 0; r < n_ranks; ++r) load[r] = assigned[(size_t)r];
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_dedup_worst_fit");
 }
 
 // ---- plan ------------------------------------------------------------------------------------
 bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shard_meta* target, int64_t n_target,
-                    uint32_t flags, void* stream, bcp_plan_t* out_plan) {
+                    uint32_t flags, void* stream, bcp_plan_t* out_plan) try {
   const auto t0 = std::chrono::steady_clock::now();
   if (!out_plan) {
     set_error("bcp_plan: out_plan is null");
@@ -321,6 +351,12 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     set_error("bcp_plan: host allocation failed");
     return BCP_ERR_OOM;
   }
+  struct Guard {  // an exception on the way must not leak the plan
+    bcp_plan_s* p;
+    ~Guard() {
+      if (p) bcp_plan_destroy(p);
+    }
+  } guard{plan};
   bcp_status s = BCP_OK;
   PlannerResult res;
   do {
@@ -349,18 +385,16 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     plan->n_dst = (int32_t)(st.max_dst_buf + 1);
     plan->table_bytes = sizeof(void*) * (size_t)(plan->n_src + plan->n_dst);
   } while (0);
-  if (s != BCP_OK) {
-    const std::string keep = g_error;
-    bcp_plan_destroy(plan);
-    g_error = keep;
-    return s;
-  }
+  if (s != BCP_OK) return s;  // the guard destroys the plan; destroying sets no error text
   plan->stats.plan_wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  guard.p = nullptr;
   *out_plan = plan;
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_plan");
 }
 
-bcp_status bcp_plan_destroy(bcp_plan_t plan) {
+bcp_status bcp_plan_destroy(bcp_plan_t plan) try {
   if (!plan) return BCP_OK;
   // back to the block pool, ordered behind the last launch that reads them
   block_free(plan->dev.regions, plan->dev.regions_bytes, plan->used, plan->last_stream);
@@ -372,18 +406,22 @@ bcp_status bcp_plan_destroy(bcp_plan_t plan) {
   for (hipEvent_t e : plan->chunk_events) (void)hipEventDestroy(e);
   delete plan;
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_plan_destroy");
 }
 
-bcp_status bcp_plan_stats(bcp_plan_t plan, bcp_stats* out) {
+bcp_status bcp_plan_stats(bcp_plan_t plan, bcp_stats* out) try {
   if (!plan || !out) {
     set_error("bcp_plan_stats: null argument");
     return BCP_ERR_INVALID_ARG;
   }
   *out = plan->stats;
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_plan_stats");
 }
 
-bcp_status bcp_plan_regions(bcp_plan_t plan, bcp_region_info* out, int64_t capacity, int64_t* n_regions) {
+bcp_status bcp_plan_regions(bcp_plan_t plan, bcp_region_info* out, int64_t capacity, int64_t* n_regions) try {
   if (!plan || !n_regions || capacity < 0 || (capacity > 0 && !out)) {
     set_error("bcp_plan_regions: bad argument");
     return BCP_ERR_INVALID_ARG;
@@ -413,10 +451,12 @@ bcp_status bcp_plan_regions(bcp_plan_t plan, bcp_region_info* out, int64_t capac
     o.saved_index = r.srec;
   }
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_plan_regions");
 }
 
 bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t n_src, int64_t* dst_extent,
-                                   int32_t n_dst) {
+                                   int32_t n_dst) try {
   if (!plan || n_src < plan->n_src || n_dst < plan->n_dst || (n_src > 0 && !src_extent) || (n_dst > 0 && !dst_extent)) {
     set_error("bcp_plan_buffer_extents: bad argument");
     return BCP_ERR_INVALID_ARG;
@@ -441,6 +481,8 @@ bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t
     }
   }
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_plan_buffer_extents");
 }
 
 // ---- reshard ---------------------------------------------------------------------------------
@@ -496,12 +538,14 @@ static bcp_status reshard_impl(bcp_plan_t plan, const void* const* src_blobs, in
 }
 
 bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
-                       int32_t n_dst, void* stream) {
+                       int32_t n_dst, void* stream) try {
   return reshard_impl(plan, src_blobs, n_src, dst_buffers, n_dst, stream, nullptr, "bcp_reshard");
+} catch (...) {
+  return on_exception("bcp_reshard");
 }
 
 bcp_status bcp_reshard_arrived(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
-                               int32_t n_dst, int32_t src_buf, int64_t byte_begin, int64_t byte_end, void* stream) {
+                               int32_t n_dst, int32_t src_buf, int64_t byte_begin, int64_t byte_end, void* stream) try {
   if (src_buf < 0 || byte_begin < 0 || byte_end < byte_begin || (byte_end >> kKeyShift)) {
     set_error("bcp_reshard_arrived: bad source range");
     return BCP_ERR_INVALID_ARG;
@@ -513,11 +557,13 @@ bcp_status bcp_reshard_arrived(bcp_plan_t plan, const void* const* src_blobs, in
   const uint64_t range[2] = {((uint64_t)src_buf << kKeyShift) | (uint64_t)byte_begin,
                              ((uint64_t)src_buf << kKeyShift) | (uint64_t)byte_end};
   return reshard_impl(plan, src_blobs, n_src, dst_buffers, n_dst, stream, range, "bcp_reshard_arrived");
+} catch (...) {
+  return on_exception("bcp_reshard_arrived");
 }
 
 bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs, const int64_t* blob_bytes,
                                  void* const* src_blobs, int32_t n_src, void* const* dst_buffers, int32_t n_dst,
-                                 int64_t chunk_bytes, void* copy_stream, void* stream) {
+                                 int64_t chunk_bytes, void* copy_stream, void* stream) try {
   if (!plan || !host_blobs || !blob_bytes || chunk_bytes <= 0) {
     set_error("bcp_reshard_from_host: bad argument");
     return BCP_ERR_INVALID_ARG;
@@ -564,14 +610,18 @@ bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs,
     }
   }
   return BCP_OK;
+} catch (...) {
+  return on_exception("bcp_reshard_from_host");
 }
 
-bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream) {
+bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream) try {
   if (!dst || !src || nbytes < 0) {
     set_error("bcp_copy_baseline: bad argument");
     return BCP_ERR_INVALID_ARG;
   }
   return launch_copy_baseline(dst, src, nbytes, (hipStream_t)stream);
+} catch (...) {
+  return on_exception("bcp_copy_baseline");
 }
 
 }  // extern "C"
