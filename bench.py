@@ -201,6 +201,8 @@ def main():
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--order-by-source", action="store_true",
+                    help="build the plan with BCP_ORDER_BY_SOURCE (work ordered by source blob and source byte)")
     ap.add_argument("--meta-on-device", action="store_true",
                     help="upload the shard records once and plan from device memory (BCP_META_ON_DEVICE)")
     ap.add_argument("--raw-inputs", action="store_true",
@@ -242,14 +244,15 @@ def main():
     payload = case.target.payload_bytes()
     stream = torch.cuda.current_stream()
 
+    plan_flags = binding.BCP_ORDER_BY_SOURCE if args.order_by_source else 0
     if args.meta_on_device:
         (dev_s, n_s), (dev_t, n_t) = binding.meta_to_device(saved_meta), binding.meta_to_device(target_meta)
 
         def make_plan():
-            return binding.plan_from_device_meta(dev_s, n_s, dev_t, n_t, stream=stream)
+            return binding.plan_from_device_meta(dev_s, n_s, dev_t, n_t, flags=plan_flags, stream=stream)
     else:
         def make_plan():
-            return binding.plan(saved_meta, target_meta, stream=stream)
+            return binding.plan(saved_meta, target_meta, flags=plan_flags, stream=stream)
 
     def step():
         p = make_plan()
@@ -352,7 +355,8 @@ def main():
         "config": {"workload": f"{args.workload}: {desc}", "payload_GB_one_way": round(payload / 1e9, 3),
                    "tile_bytes": args.tile_bytes or "default", "persistent": args.persistent,
                    "wg_per_cu": args.wg_per_cu or "default", "threads": args.threads or "default",
-                   "metadata": "device" if args.meta_on_device else "host"},
+                   "metadata": "device" if args.meta_on_device else "host",
+                   "order": "by source" if args.order_by_source else "by target"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "plan_build_ms": {"wall_median": round(sorted(iso_ms)[len(iso_ms) // 2], 4), "wall_min": round(min(iso_ms), 4),
                           "in_loop_avg_incl_wait_for_previous_copy": round(sum(plan_ms) / len(plan_ms), 4)},
