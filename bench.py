@@ -339,6 +339,9 @@ def main():
         torch.cuda.synchronize()
     p.destroy()
 
+    # the instance of the copy kernel this plan runs on, as the profiler names it
+    kernel_name = ("k_reshard_table" if stats["max_src_buf"] + stats["max_dst_buf"] + 2 > 256 else "k_reshard") + \
+                  ("<true>" if stats["n_transposed"] else "<false>")
     out = {
         "metric": "reshard GB/s (read+written), plan + copy per step",
         "value": round(value, 2),
@@ -365,7 +368,7 @@ def main():
                                        "n_batches", "n_transposed")},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args.workload),
-                     "kernel": "k_reshard", "bytes_per_launch": 2 * payload},
+                     "kernel": kernel_name, "bytes_per_launch": 2 * payload},
         "ceiling": ceil,
         "input_generation_s": round(t_gen, 1),
     }
