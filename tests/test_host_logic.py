@@ -6,6 +6,7 @@ import ctypes
 import itertools
 import os
 import re
+import sys
 
 import numpy as np
 import pytest
@@ -182,3 +183,22 @@ def test_configure_rejects_bad_values():
     with pytest.raises(binding.BcpError):
         binding.configure(threads=100)
     binding.configure(**binding.DEFAULT_CONFIG)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
+
+
+def test_measured_traffic_is_tied_to_the_kernel_sources():
+    """roofline.traffic is reported only while the sources are the ones the counters were taken on."""
+    sys.path.insert(0, ROOT)
+    import bench
+    m = bench.MEASURED_TRAFFIC["cfg3"]
+    assert len(m["csrc_sha256"]) == 64
+    algorithmic = 2 * 94341545984
+    assert 0.99 * algorithmic < m["bytes_per_launch"] < 1.05 * algorithmic
+    assert bench.measured_traffic("no such workload") is None
