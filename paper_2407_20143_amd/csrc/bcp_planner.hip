@@ -254,10 +254,22 @@ __device__ inline unsigned validate_record(const bcp_shard_meta& r) {
   }
   if (r.flat_begin < 0 || r.flat_end < r.flat_begin) return kErrInvalid;
   if (r.flat_end > vol) return kErrBounds;
+  // byte addresses inside the buffer must stay far from the 64-bit limit: at most 2^56 elements of
+  // storage behind byte_offset < 2^60
+  constexpr int64_t kMaxSpan = (int64_t)1 << 56;
+  if (r.byte_offset >= ((int64_t)1 << 60)) return kErrInvalid;
   if (strided) {
     if (!(r.flat_begin == 0 && r.flat_end == vol)) return kErrInvalid;  // flat shards are packed
-    for (int k = 0; k < r.ndim; ++k)
+    int64_t span = 0;  // element offset of the last element
+    for (int k = 0; k < r.ndim; ++k) {
       if (r.lengths[k] > 1 && r.strides[k] == 0) return kErrInvalid;
+      if (r.lengths[k] > 1) {
+        if (r.strides[k] > (kMaxSpan - span) / (r.lengths[k] - 1)) return kErrInvalid;
+        span += (r.lengths[k] - 1) * r.strides[k];
+      }
+    }
+  } else if (vol > kMaxSpan) {
+    return kErrInvalid;
   }
   return 0;
 }

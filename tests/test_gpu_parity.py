@@ -478,6 +478,22 @@ def test_error_statuses():
     def flat(sm, tm):
         tm["flat_end"][0] = 33
     assert _plan_error(ok_s, ok_t, flat) == "BCP_ERR_OUT_OF_BOUNDS"
+    # byte addresses that would leave the 64-bit range are refused, not wrapped
+    def huge_stride(sm, tm):
+        tm["strides"][0, 0] = 1 << 58
+        tm["strides"][0, 1] = 1
+    assert _plan_error(ok_s, ok_t, huge_stride) == "BCP_ERR_INVALID_ARG"
+
+    def huge_offset(sm, tm):
+        sm["byte_offset"][0] = 1 << 61
+    assert _plan_error(ok_s, ok_t, huge_offset) == "BCP_ERR_INVALID_ARG"
+
+    def huge_volume(sm, tm):
+        for m in (sm, tm):
+            m["global_shape"][0, :2] = (1 << 30, 1 << 30)
+            m["lengths"][0, :2] = (1 << 30, 1 << 30)
+            m["flat_end"][0] = 1 << 60
+    assert _plan_error(ok_s, ok_t, huge_volume) == "BCP_ERR_INVALID_ARG"
     # too few buffers at reshard time
     p = binding.plan(binding.layout_to_meta(over.__class__([over.shards[0]], [80])),
                      binding.layout_to_meta(Layout([regular(Part(0, (8, 4), (0, 0), (5, 4)), 4, 2, 0)], [0, 0, 80])))
