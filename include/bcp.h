@@ -31,7 +31,9 @@ extern "C" {
  * Storage: element j of that range sits at byte_offset + itemsize*j of buffer `buf` (packed),
  * unless `strides` is non-zero, in which case the shard must be regular and the element with
  * box-local coordinates y sits at byte_offset + itemsize * sum_k y[k]*strides[k].
- * ndim == 0 is a scalar (volume 1).  Zero-volume shards are legal and produce no work. */
+ * ndim == 0 is a scalar (volume 1).  Zero-volume shards are legal and produce no work.
+ * Limits (BCP_ERR_INVALID_ARG beyond them): byte_offset < 2^60, and the storage of one shard spans
+ * at most 2^56 elements (volume for packed shards, offset of the last element for strided ones). */
 typedef struct bcp_shard_meta {
   int64_t fqn_id;                     /* >= 0; identifies the tensor (string table stays with the caller) */
   int32_t ndim;                       /* 0..BCP_MAX_DIMS */
