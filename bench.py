@@ -343,7 +343,8 @@ def main():
     kernel_name = ("k_reshard_table" if stats["max_src_buf"] + stats["max_dst_buf"] + 2 > 256 else "k_reshard") + \
                   ("<true>" if stats["n_transposed"] else "<false>")
     out = {
-        "metric": "reshard GB/s (read+written), plan + copy per step",
+        "metric": "reshard GB/s (read+written)" + ("; 7B TP4PP2->TP2PP4" if args.workload == "cfg3" else "") +
+                  "; plan + copy per step (% of HBM peak and plan-build ms alongside)",
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
