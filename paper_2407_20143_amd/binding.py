@@ -178,9 +178,28 @@ def dedup_worst_fit(meta: np.ndarray, rank_of, n_ranks: int):
     return keep[:len(meta)].astype(bool), load
 
 
-def layout_to_meta(layout) -> np.ndarray:
-    """synth.Layout -> array of bcp_shard_meta.  Multi-part (flat ZeRO) shards go through
-    bcp_meta_from_flat_slice; everything else is a field-by-field copy."""
+def pinned_meta(meta: np.ndarray) -> np.ndarray:
+    """A copy of a bcp_shard_meta array in pinned host memory (bcp_plan uploads 304 bytes per record;
+    from pinned memory that runs at the full host-to-device rate).  Without a GPU: the array itself."""
+    import torch
+    if not torch.cuda.is_available() or len(meta) == 0:
+        return meta
+    raw = np.ascontiguousarray(meta, dtype=SHARD_META).view(np.uint8).reshape(-1)
+    t = torch.empty(raw.size, dtype=torch.uint8, pin_memory=True)
+    out = t.numpy()  # keeps the tensor alive
+    out[:] = raw
+    return out.view(SHARD_META)
+
+
+def layout_to_meta(layout, pinned: bool = True) -> np.ndarray:
+    """synth.Layout -> array of bcp_shard_meta (in pinned host memory when there is a GPU).
+    Multi-part (flat ZeRO) shards go through bcp_meta_from_flat_slice; everything else is a
+    field-by-field copy."""
+    meta = _layout_to_meta(layout)
+    return pinned_meta(meta) if pinned else meta
+
+
+def _layout_to_meta(layout) -> np.ndarray:
     chunks: List[np.ndarray] = [_records_bulk([sh for sh in layout.shards if len(sh.parts) == 1])]
     cache = {}
     for sh in layout.shards:
