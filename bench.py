@@ -63,6 +63,8 @@ def build_case(name: str):
         return synth.cfg4(), "7B fp32 optimizer states, ZeRO flat DP16 -> TP2 x DP12"
     if name == "cfg4_1state":
         return synth.cfg4(n_states=1), "7B fp32 optimizer state (one of three), ZeRO flat DP16 -> TP2 x DP12"
+    if name == "cfg5":
+        return synth.cfg5(), "MoE expert weights bf16 EP8TP2 -> EP4TP4 plus 100k small fp32 tensors (random bytes as values)"
     if name == "cfg5_experts":
         return synth.cfg5(n_small=0), "MoE expert weights bf16, EP8TP2 -> EP4TP4"
     if name == "cfg5_small":
@@ -112,7 +114,7 @@ def cpu_baseline(workload: str):
     elif workload == "cfg5_experts":
         case = synth.cfg5(layers=1, n_small=0)
         what = "one of 16 MoE layers of expert weights"
-    elif workload == "cfg5_small":
+    elif workload in ("cfg5_small", "cfg5"):
         case = synth.cfg5(include_experts=False, n_small=20000)
         what = "20000 of the 100000 small tensors"
     elif workload.startswith("copy"):
@@ -230,7 +232,7 @@ def main():
     note(f"workload {args.workload}: generating inputs on the GPU")
     t0 = time.perf_counter()
     small = args.workload == "cfg5_small"
-    if args.raw_inputs:
+    if args.raw_inputs or args.workload == "cfg5":  # (generating 100k tiny tensors one by one on the GPU takes minutes)
         src = [torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda") for n in case.saved.buf_bytes]
     else:
         src = synth.materialize(case.saved, case.tensors, case.seed, device="cpu" if small else "cuda")
