@@ -99,12 +99,12 @@ def cpu_baseline(workload: str):
     from oracle import oracle
     from paper_2407_20143_amd import synth
     if workload.startswith("cfg3"):
-        model = synth.llama_tensors(2, 4096, 11008, 32000)[1:19]  # the 18 tensors of two decoder layers
+        model = synth.llama_tensors(8, 4096, 11008, 32000)[1:73]  # the 72 tensors of eight decoder layers
         states = synth.CFG3_STATES
         case = synth.Case("sample", synth.BASE_SEED + 3, synth._specs(model, states),
-                          synth.megatron_layout(model, states, 2, 4, 1, replicate_norms=False),
-                          synth.megatron_layout(model, states, 2, 2, 1, replicate_norms=True))
-        what = "two of the 32 decoder layers (18 tensors x 4 states, 5.67 GB one way) of the 7B workload, TP4 -> TP2"
+                          synth.megatron_layout(model, states, 8, 4, 1, replicate_norms=False),
+                          synth.megatron_layout(model, states, 8, 2, 1, replicate_norms=True))
+        what = "eight of the 32 decoder layers (72 tensors x 4 states, 22.7 GB one way) of the 7B workload, TP4 -> TP2"
     elif workload.startswith("cfg4"):
         case = synth.cfg4(layers=1, n_states=1)
         what = "embedding + one decoder layer + lm_head of one fp32 state, ZeRO flat DP16 -> TP2 x DP12"
