@@ -83,6 +83,14 @@ def build_case(name: str):
         return synth.transpose_case(), "fp32 [16384,16384], 4 row blocks -> 4 column blocks stored column-major (LDS-staged transpose)"
     if name == "transpose_bf16":
         return synth.transpose_case(dtype=__import__("torch").bfloat16), "bf16 [16384,16384] row blocks -> column-major column blocks"
+    if name in ("strided_read", "strided_write", "rows_1gib"):
+        # fp32 [16384,16384] without a transposition: column blocks of 128 columns (512-byte runs at a
+        # 64 KiB pitch) on the read or the write side; rows_1gib: no split at all (contiguous, same size)
+        if name == "rows_1gib":
+            return synth.column_blocks_case(cols=16384), "fp32 [16384,16384] copied whole (1 GiB, contiguous)"
+        side = name.split("_")[1]
+        return (synth.column_blocks_case(strided_side=side),
+                f"fp32 [16384,16384] <-> 128 column blocks, 512-byte runs at a 64 KiB pitch on the {side} side, no transposition")
     if name == "fused_qkv":
         return synth.fused_qkv_case(), "fused GQA QKV blobs (32 layers, h4096, 32q/8kv heads) TP4 -> separate q,k,v TP2"
     if name.startswith("copy"):  # copy, copy_s4 (source shifted 4 bytes), copy_d4, copy_d2 ...

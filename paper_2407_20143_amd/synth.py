@@ -622,6 +622,26 @@ def transpose_case(n: int = 16384, m: int = 16384, dtype: torch.dtype = torch.fl
     return Case(f"transpose_{n}x{m}", BASE_SEED + 9, {0: spec}, saved, target)
 
 
+def column_blocks_case(n: int = 16384, m: int = 16384, cols: int = 128, strided_side: str = "read",
+                       dtype: torch.dtype = torch.float32) -> Case:
+    """A [n, m] tensor held whole (row-major) on one side and as m/cols column blocks [n, cols], packed
+    one after the other into a single buffer, on the other: a plain row copy with runs of cols elements
+    at a pitch of m elements on the strided side and none on the other -- the access pattern of
+    `transpose_case` without the transposition.  strided_side "read": the whole tensor is the source."""
+    e = dtype.itemsize
+    spec = TensorSpec(0, "w", (n, m), dtype, ("bits",))
+    whole = Layout([regular(Part(0, (n, m), (0, 0), (n, m)), e, 0, 0)], [n * m * e])
+    split = Layout()
+    off = 0
+    for c in range(m // cols):
+        part = Part(0, (n, m), (0, c * cols), (n, cols))
+        split.shards.append(regular(part, e, 0, off))
+        off += part.volume * e
+    split.buf_bytes.append(off)
+    saved, target = (whole, split) if strided_side == "read" else (split, whole)
+    return Case(f"column_blocks_{strided_side}_{cols}", BASE_SEED + 10, {0: spec}, saved, target)
+
+
 def copy_case(nbytes: int = 8 << 30, src_shift: int = 0, dst_shift: int = 0) -> Case:
     """One byte tensor saved whole and loaded whole: the reshard degenerates to a plain copy
     (the practical bandwidth ceiling of the copy kernel).  Shifts move the shard inside its

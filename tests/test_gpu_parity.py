@@ -62,6 +62,14 @@ def test_random_layouts(seed, modes):
     check_case(synth.random_case(100 + seed, n_tensors=8, max_elems=20000, saved_mode=modes[0], target_mode=modes[1]))
 
 
+@pytest.mark.parametrize("side", ["read", "write"])
+def test_column_blocks_in_one_buffer(side):
+    """Row copies with short runs at a long pitch on one side only (the access pattern of the
+    transposed case without the transposition), all blocks packed into one buffer."""
+    check_case(synth.column_blocks_case(200, 384, 32, side))
+    check_case(synth.column_blocks_case(130, 96, 3, side, dtype=torch.bfloat16))
+
+
 def test_random_soak():
     """120 more random cases in one test: every mix of grid / flat sides, ranks up to 6, strided
     shards, all packing granules, under the default launch shape and a small-tile one."""
