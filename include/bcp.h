@@ -9,8 +9,11 @@
  * the new sharding specification).  Storage I/O is outside: saved blobs are byte buffers that
  * already sit in device memory.
  *
- * All functions are thread-compatible (no global state besides a thread-local error string),
- * return a bcp_status and never throw.  "host" / "device" below says where a pointer must point.
+ * All functions return a bcp_status and never throw.  They may be called from several threads:
+ * the process-wide state (the launch configuration of bcp_configure, the planner's workspace, the
+ * pool of plan blocks) is guarded by locks -- concurrent bcp_plan calls take turns -- and the error
+ * text is per thread; calls on ONE plan must be ordered by the caller.  "host" / "device" below
+ * says where a pointer must point.
  */
 #ifndef BCP_H_
 #define BCP_H_
