@@ -352,6 +352,45 @@ def test_plan_destroyed_right_after_its_launch():
     assert binding.release_workspace() > 0
 
 
+def test_threads_plan_and_reshard_side_by_side():
+    """The library's process-wide state is behind locks: four host threads, each with its own stream,
+    case and plans, build, run and destroy plans at the same time (ctypes drops the GIL in the calls)."""
+    import threading
+    cases = [synth.cfg2(layers=2, hidden=128 * (i + 1), ffn=344 * (i + 1), vocab=1000) for i in range(2)]
+    cases += [synth.random_case(7100 + i, n_tensors=8, max_elems=30000, saved_mode="flat", target_mode="grid") for i in range(2)]
+    prepared = []
+    for c in cases:
+        src = synth.materialize(c.saved, c.tensors, c.seed)
+        prepared.append((c, [b.cuda() for b in src], oracle.reshard(c.saved, c.target, src, poison=POISON),
+                         binding.layout_to_meta(c.saved), binding.layout_to_meta(c.target)))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(k):
+        try:
+            c, dsrc, want, sm, tm = prepared[k]
+            st = torch.cuda.Stream()
+            for rnd in range(5):
+                ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in c.target.buf_bytes]
+                st.wait_stream(torch.cuda.current_stream())
+                p = binding.plan(sm, tm, stream=st)
+                binding.reshard(p, dsrc, ddst, stream=st)
+                p.destroy()
+                st.synchronize()
+                for got, w in zip(ddst, want):
+                    if not np.array_equal(got.cpu().numpy(), w):
+                        errors.append(f"thread {k} round {rnd}: mismatch")
+        except Exception as e:  # noqa: BLE001 - reported below
+            errors.append(f"thread {k}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(len(prepared))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 def test_workspace_can_be_released_and_comes_back():
     case = synth.cfg2(layers=2, hidden=128, ffn=344, vocab=1000)
     check_case(case)
