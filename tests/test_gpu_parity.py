@@ -124,6 +124,16 @@ def test_strided_every_itemsize(dtype):
         assert st["n_transposed"] == 2
 
 
+@pytest.mark.parametrize("dtype", [torch.uint8, torch.bfloat16, torch.float32, torch.float64, torch.complex128])
+@pytest.mark.parametrize("n,m", [(512, 768), (528, 784), (520, 776), (515, 771)])
+def test_transposed_full_and_ragged_tiles(dtype, n, m):
+    """Column-major targets with everything 16-byte aligned: whole tiles (the per-wave path of 4-byte and
+    wider elements, the workgroup-wide vector path of the narrower ones), ragged tiles at the edges
+    (multiples of 16 and of 8 elements), and extents that leave only the element-by-element path."""
+    st = check_case(synth.transpose_case(n - n % 2, m - m % 2, dtype, shards=2))  # two shards: even extents
+    assert st["n_transposed"] == 4
+
+
 def test_metadata_already_on_the_device():
     case = synth.cfg4(layers=2, hidden=136, ffn=344, vocab=1000, dp_s=16, dp_t=12, n_states=1)
     sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
