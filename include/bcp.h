@@ -181,6 +181,20 @@ bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs,
                                  void* const* src_blobs, int32_t n_src, void* const* dst_buffers, int32_t n_dst,
                                  int64_t chunk_bytes, void* copy_stream, void* stream);
 
+/* bcp_reshard for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result.  What bcp_reshard
+ * keeps in memory the library allocates -- the queue words of the persistent grid, and the table of
+ * buffer pointers when there are more than 256 buffers -- lives in a static array in device memory
+ * instead (64 KiB + 256 bytes per GPU, held until the process ends), so the call is a few kernel
+ * launches on `stream` and nothing else: no hipMalloc, no hipFree, no host-to-device copy, no wait.
+ * Limit: n_src + n_dst of the plan at most BCP_NOALLOC_MAX_BUFFERS, else BCP_ERR_INVALID_ARG.
+ * Every call on one GPU uses that GPU's one array (its words are put back to zero at the start of
+ * each call, in stream order): calls that overlap in time on one GPU -- on different streams, or on
+ * different plans -- race and must be ordered by the caller. */
+#define BCP_NOALLOC_MAX_BUFFERS 8192
+bcp_status bcp_reshard_noalloc(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src,
+                               void* const* dst_buffers, int32_t n_dst, void* stream);
+
 bcp_status bcp_plan_stats(bcp_plan_t plan, bcp_stats* out);
 
 /* Copy up to `capacity` regions to out (host); *n_regions receives the plan's region count. */

@@ -43,7 +43,8 @@ BCP_ORDER_BY_SOURCE = 4
 BCP_META_ON_DEVICE = 8
 
 EXPORTS = [
-    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_dedup_worst_fit", "bcp_plan", "bcp_reshard", "bcp_reshard_arrived",
+    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_dedup_worst_fit", "bcp_plan", "bcp_reshard", "bcp_reshard_noalloc",
+    "bcp_reshard_arrived",
     "bcp_reshard_from_host", "bcp_plan_stats",
     "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy", "bcp_configure", "bcp_release_workspace",
     "bcp_copy_baseline", "bcp_last_error",
@@ -75,6 +76,7 @@ def lib():
         L.bcp_dedup_worst_fit.argtypes = [vp, vp, i64, i32, vp, vp]
         L.bcp_plan.argtypes = [vp, i64, vp, i64, u32, vp, ctypes.POINTER(vp)]
         L.bcp_reshard.argtypes = [vp, vp, i32, vp, i32, vp]
+        L.bcp_reshard_noalloc.argtypes = [vp, vp, i32, vp, i32, vp]
         L.bcp_reshard_arrived.argtypes = [vp, vp, i32, vp, i32, i32, i64, i64, vp]
         L.bcp_reshard_from_host.argtypes = [vp, vp, vp, vp, i32, vp, i32, i64, vp, vp]
         L.bcp_plan_stats.argtypes = [vp, vp]
@@ -313,6 +315,13 @@ def reshard(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, stream=None, ch
                         raise ValueError(f"{what}[{i}] holds {have} bytes, the plan touches {int(need)}")
     _check(lib().bcp_reshard(p._h, _ptrs(src_blobs), len(src_blobs), _ptrs(dst_buffers), len(dst_buffers),
                              _stream_ptr(stream)))
+
+
+def reshard_noalloc(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, stream=None) -> None:
+    """bcp_reshard_noalloc: bcp_reshard with the queue words and the pointer table in the library's
+    static device array (no allocation of any kind; at most BCP_NOALLOC_MAX_BUFFERS buffers)."""
+    _check(lib().bcp_reshard_noalloc(p._h, _ptrs(src_blobs), len(src_blobs), _ptrs(dst_buffers), len(dst_buffers),
+                                     _stream_ptr(stream)))
 
 
 def reshard_arrived(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, src_buf: int, byte_begin: int,

@@ -486,8 +486,9 @@ bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t
 }
 
 // ---- reshard ---------------------------------------------------------------------------------
-static bcp_status reshard_impl(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
-                               int32_t n_dst, void* stream, const uint64_t* key_range, const char* who) {
+// argument checks shared by the reshard entry points (a plan without tiles accepts anything)
+static bcp_status check_reshard_args(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src,
+                                     void* const* dst_buffers, int32_t n_dst, const char* who) {
   if (!plan) {
     set_error(std::string(who) + ": plan is null");
     return BCP_ERR_INVALID_ARG;
@@ -513,6 +514,13 @@ static bcp_status reshard_impl(bcp_plan_t plan, const void* const* src_blobs, in
     set_error(std::string(who) + ": the plan belongs to another device");
     return BCP_ERR_INVALID_ARG;
   }
+  return BCP_OK;
+}
+
+static bcp_status reshard_impl(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
+                               int32_t n_dst, void* stream, const uint64_t* key_range, const char* who) {
+  if (bcp_status s = check_reshard_args(plan, src_blobs, n_src, dst_buffers, n_dst, who)) return s;
+  if (plan->dev.n_tiles == 0) return BCP_OK;
   hipStream_t st = (hipStream_t)stream;
   plan->used = true;
   plan->last_stream = st;
@@ -542,6 +550,17 @@ bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_
   return reshard_impl(plan, src_blobs, n_src, dst_buffers, n_dst, stream, nullptr, "bcp_reshard");
 } catch (...) {
   return on_exception("bcp_reshard");
+}
+
+bcp_status bcp_reshard_noalloc(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
+                               int32_t n_dst, void* stream) try {
+  if (bcp_status s = check_reshard_args(plan, src_blobs, n_src, dst_buffers, n_dst, "bcp_reshard_noalloc")) return s;
+  if (plan->dev.n_tiles == 0) return BCP_OK;
+  plan->used = true;
+  plan->last_stream = (hipStream_t)stream;
+  return launch_reshard_noalloc(plan->dev, src_blobs, plan->n_src, dst_buffers, plan->n_dst, (hipStream_t)stream);
+} catch (...) {
+  return on_exception("bcp_reshard_noalloc");
 }
 
 bcp_status bcp_reshard_arrived(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,

@@ -20,6 +20,8 @@
 // while the current batch is being copied, and the buffer-pointer table is staged in LDS once per
 // workgroup, so no dependent global load sits between two batches.
 #include <algorithm>
+#include <mutex>
+#include <string>
 
 #include "bcp_internal.h"
 
@@ -827,6 +829,80 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_
   }
   BCP_HIP(hipGetLastError());
   return BCP_OK;
+}
+
+// ---- the variant that allocates nothing ----------------------------------------------------------
+// Queue words and pointer table of a launch in a static array in device memory: [4 queue words, padded
+// to 256 bytes | BCP_NOALLOC_MAX_BUFFERS pointers].  Each GPU holds its own copy at its own address,
+// looked up once per device; host code only ever uses that address, never the array's name.
+namespace {
+constexpr size_t kScratchQueueBytes = 256;
+constexpr size_t kScratchBytes = kScratchQueueBytes + sizeof(uint64_t) * BCP_NOALLOC_MAX_BUFFERS;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_addr[kMaxDevices];  // per device, null until looked up
+
+// the current device's copy of the array
+bcp_status scratch_address(void** out) {
+  int dev = -1;
+  BCP_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) {
+    set_error("device index beyond the static scratch table");
+    return BCP_ERR_INVALID_ARG;
+  }
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  if (!g_scratch_addr[dev]) {
+    void* p = nullptr;
+    BCP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) {
+      set_error("hipGetSymbolAddress returned no address for the static scratch array");
+      return BCP_ERR_HIP;
+    }
+    g_scratch_addr[dev] = p;
+  }
+  *out = g_scratch_addr[dev];
+  return BCP_OK;
+}
+
+// table[base + i] = chunk.p[i] for i < n; with `queue` also puts the queue words back to zero (a fill
+// kernel rather than a memset node, so that the sequence may be recorded into a HIP graph)
+__global__ __launch_bounds__(kArgPtrs) void k_scratch_store(uint64_t* __restrict__ table, PtrArgs chunk, uint32_t base,
+                                                            uint32_t n, unsigned long long* queue) {
+  const uint32_t i = threadIdx.x;
+  if (i < n) table[base + i] = chunk.p[i];
+  if (queue && i < 4) queue[i] = 0ull;
+}
+}  // namespace
+
+bcp_status launch_reshard_noalloc(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
+                                  int32_t n_dst, hipStream_t stream) {
+  if (plan.n_batches == 0) return BCP_OK;
+  if ((int64_t)n_src + n_dst > BCP_NOALLOC_MAX_BUFFERS) {
+    set_error("bcp_reshard_noalloc: the plan uses " + std::to_string((int64_t)n_src + n_dst) +
+              " buffers, the static pointer table holds " + std::to_string(BCP_NOALLOC_MAX_BUFFERS));
+    return BCP_ERR_INVALID_ARG;
+  }
+  void* base = nullptr;
+  if (bcp_status s = scratch_address(&base)) return s;
+  unsigned long long* queue = reinterpret_cast<unsigned long long*>(base);
+  uint64_t* table = reinterpret_cast<uint64_t*>(static_cast<char*>(base) + kScratchQueueBytes);
+  const int32_t n_ptrs = n_src + n_dst;
+  for (int32_t first = 0; first < n_ptrs || first == 0; first += kArgPtrs) {
+    PtrArgs args;
+    const int32_t n = std::min<int32_t>(kArgPtrs, n_ptrs - first);
+    for (int32_t i = 0; i < kArgPtrs; ++i) {
+      const int32_t j = first + i;
+      args.p[i] = i >= n ? 0 : (uint64_t)(uintptr_t)(j < n_src ? src[j] : dst[j - n_src]);
+    }
+    hipLaunchKernelGGL(k_scratch_store, dim3(1), dim3(kArgPtrs), 0, stream, table, args, (uint32_t)first, (uint32_t)n,
+                       first == 0 ? queue : nullptr);
+    BCP_HIP(hipGetLastError());
+  }
+  PlanDevice view = plan;  // same tiles and batches, the queue words of the static array
+  view.queue = queue;
+  return launch_reshard(view, nullptr, n_src, nullptr, n_dst, table, stream, nullptr);
 }
 
 bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream) {

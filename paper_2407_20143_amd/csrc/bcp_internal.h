@@ -173,6 +173,9 @@ constexpr uint32_t transpose_lds_bytes(uint32_t tdim_a, uint32_t tdim_b, uint32_
 bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
                           int32_t n_dst, const void* table, hipStream_t stream,
                           const uint64_t* key_range = nullptr);
+// bcp_reshard_noalloc: pointer table and queue words in a static device array, no allocation
+bcp_status launch_reshard_noalloc(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
+                                  int32_t n_dst, hipStream_t stream);
 bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream);
 int device_cu_count();
 
