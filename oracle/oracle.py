@@ -66,7 +66,9 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
-            ctypes.c_char_p, ctypes.c_int]
+            ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
+        _lib.orc_f32_to_bf16.restype = None
+        _lib.orc_f32_to_bf16.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         assert _lib.orc_max_dims() == MAX_DIMS
     return _lib
 
@@ -131,12 +133,14 @@ def _as_np(t) -> np.ndarray:
 
 def reshard(saved, target, src_blobs, dst_init: Optional[List] = None, poison: int = 0xA5,
             allow_uncovered: bool = False, threads: Optional[int] = None, want_written: bool = False,
-            only_fqns: Optional[Sequence[int]] = None, dst_inplace: Optional[List[np.ndarray]] = None):
+            only_fqns: Optional[Sequence[int]] = None, dst_inplace: Optional[List[np.ndarray]] = None,
+            convert: int = 0):
     """Run the oracle.  saved/target: synth.Layout.  src_blobs: CPU uint8 buffers (torch or numpy).
     Returns the destination buffers as numpy uint8 arrays (bytes no target shard covers keep
     `poison`), and with want_written also per-byte write counters.  only_fqns: produce just these
     tensors (everything else in the destination keeps its initial bytes).  dst_inplace: write into
-    these numpy buffers instead of fresh ones (large sparse checks)."""
+    these numpy buffers instead of fresh ones (large sparse checks).  convert=1: tensors saved with
+    4-byte elements and asked for with 2-byte elements are narrowed binary32 -> bfloat16."""
     lib = _load()
     sparts, sshards = _marshal(saved)
     tparts, tshards = _marshal(target)
@@ -160,7 +164,16 @@ def reshard(saved, target, src_blobs, dst_init: Optional[List] = None, poison: i
                          tparts.ctypes.data, tshards.ctypes.data, len(target.shards), dp, dst_sizes.ctypes.data,
                          wp, int(allow_uncovered), int(threads),
                          only.ctypes.data if only is not None else None, len(only) if only is not None else 0,
-                         err, len(err))
+                         int(convert), err, len(err))
     if rc != 0:
         raise OracleError(rc, err.value.decode())
     return (dst, written) if want_written else dst
+
+
+def f32_to_bf16(bits: np.ndarray) -> np.ndarray:
+    """The oracle's binary32 -> bfloat16 narrowing on an array of uint32 bit patterns -> uint16 patterns."""
+    lib = _load()
+    src = np.ascontiguousarray(bits, dtype=np.uint32)
+    out = np.empty(src.shape, dtype=np.uint16)
+    lib.orc_f32_to_bf16(src.ctypes.data, out.ctypes.data, src.size)
+    return out

@@ -14,11 +14,21 @@
 // target element from G.  Every element goes through its global index; there is no box
 // intersection and no decomposition of flat ranges here.
 //
+// Dtype-converting load (Sec. 2.2: evaluation jobs load model states only, so fp32 master weights
+// are read as bf16): with `convert` set, a tensor saved with 4-byte elements and asked for with 2-byte
+// elements is narrowed element by element, binary32 -> bfloat16, round to nearest, ties to even,
+// written out below from the IEEE 754 definition (the two neighbouring bfloat16 values are decoded
+// and compared in fp64, where the differences are exact).
+//
 // Parity status: pinned (tests/test_oracle_pins.py: library-slicing closed form, the paper's
 // (3,2) worked example, reassembly / round-trip / exactly-once invariants, brute force).
+// The narrowing: tests/test_oracle_convert.py (hand values in tests/golden/bf16_rounding.txt, the
+// library cast on every upper half x chosen lower halves and on random bits, closed form through the
+// whole transform).
 // The region list of a plan has no counterpart here: many region lists are correct.
 #include <algorithm>
 #include <atomic>
+#include <cmath>
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
@@ -83,6 +93,47 @@ int64_t ravel(const int64_t* x, const int64_t* shape, int n) {
   int64_t f = 0;
   for (int k = 0; k < n; ++k) f = f * shape[k] + x[k];
   return f;
+}
+
+// ---- binary32 -> bfloat16, IEEE 754 roundTiesToEven ------------------------------------------------
+// bfloat16 is the upper half of the binary32 encoding: 1 sign bit, 8 exponent bits (bias 127), 7
+// fraction bits.  Magnitudes only below; the sign is carried over.
+//
+// value of a binary32 magnitude pattern (31 bits), finite
+double f32_magnitude(uint32_t m) {
+  const int exp = (int)(m >> 23);
+  const double frac = (double)(m & 0x7fffffu);
+  if (exp == 0) return std::ldexp(frac, -149);               // subnormal: frac * 2^-149
+  return std::ldexp(8388608.0 + frac, exp - 150);            // (2^23 + frac) * 2^(exp - 127 - 23)
+}
+// value of a bfloat16 magnitude pattern (15 bits).  The pattern of infinity (exponent field 255,
+// fraction 0) is given the value its binade would have, 2^128: rounding to nearest goes to infinity
+// exactly when the value is at least half an ulp beyond the largest finite number, i.e. nearer to
+// 2^128 than to it (IEEE 754-2019, 4.3.1).
+double bf16_magnitude(uint32_t m) {
+  const int exp = (int)(m >> 7);
+  const double frac = (double)(m & 0x7fu);
+  if (exp == 0) return std::ldexp(frac, -133);               // subnormal: frac * 2^-126 * 2^-7
+  return std::ldexp(128.0 + frac, exp - 134);                // (2^7 + frac) * 2^(exp - 127 - 7)
+}
+
+uint16_t f32_to_bf16(uint32_t bits) {
+  const uint32_t sign = bits >> 31, mag = bits & 0x7fffffffu;
+  if (mag > 0x7f800000u) {
+    // NaN: stays NaN.  Sign and the upper seven fraction bits are kept and the result is quiet
+    // (IEEE 754-2019, 6.2.3: payload preserved as far as the narrower format holds it).
+    return (uint16_t)((sign << 15) | 0x7f80u | ((mag >> 16) & 0x7fu) | 0x40u);
+  }
+  if (mag == 0x7f800000u) return (uint16_t)((sign << 15) | 0x7f80u);  // infinity
+  const uint32_t below = mag >> 16;      // the bfloat16 neighbour towards zero (truncation) ...
+  const uint32_t above = below + 1;      // ... and the next one away from zero
+  const double x = f32_magnitude(mag), a = bf16_magnitude(below), b = bf16_magnitude(above);
+  const double down = x - a, up = b - x;  // exact in fp64
+  uint32_t pick;
+  if (down < up) pick = below;
+  else if (up < down) pick = above;
+  else pick = (below & 1u) == 0 ? below : above;  // tie: the neighbour whose last fraction bit is 0
+  return (uint16_t)((sign << 15) | pick);
 }
 
 struct Ref {  // one part of one shard, with the position of its first element in the concatenation
@@ -172,6 +223,7 @@ struct Job {
   const int64_t* dst_bytes;
   uint8_t* const* dst_written;  // optional per-byte write counters (saturating), may be null
   bool allow_uncovered;
+  int convert;  // 0: element sizes must agree; 1: 4-byte saved elements -> 2-byte target elements as f32 -> bf16
   Error err;
 };
 
@@ -180,19 +232,24 @@ void do_fqn(Job& job, int64_t fqn, const std::vector<Ref>& trefs) {
   // shape / dtype agreement over every part that names this FQN
   const orc_part& t0 = job.target.parts[trefs[0].part];
   const int n = t0.ndim;
-  const int e = job.target.shards[trefs[0].shard].itemsize;
-  auto agrees = [&](const Side& s, const Ref& r) {
+  const int et = job.target.shards[trefs[0].shard].itemsize;  // element size asked for
+  int e = et;                                                 // element size saved
+  if (it != job.saved.by_fqn.end() && !it->second.empty()) {
+    const int es = job.saved.shards[it->second[0].shard].itemsize;
+    if (job.convert == 1 && es == 4 && et == 2) e = es;
+  }
+  auto agrees = [&](const Side& s, const Ref& r, int esize) {
     const orc_part& p = s.parts[r.part];
-    if (p.ndim != n || s.shards[r.shard].itemsize != e) return false;
+    if (p.ndim != n || s.shards[r.shard].itemsize != esize) return false;
     for (int d = 0; d < n; ++d)
       if (p.global_shape[d] != t0.global_shape[d]) return false;
     return true;
   };
   for (const Ref& r : trefs)
-    if (!agrees(job.target, r)) return job.err.set(ORC_MISMATCH, "target shards disagree on fqn " + std::to_string(fqn));
+    if (!agrees(job.target, r, et)) return job.err.set(ORC_MISMATCH, "target shards disagree on fqn " + std::to_string(fqn));
   if (it != job.saved.by_fqn.end())
     for (const Ref& r : it->second)
-      if (!agrees(job.saved, r)) return job.err.set(ORC_MISMATCH, "saved/target disagree on fqn " + std::to_string(fqn));
+      if (!agrees(job.saved, r, e)) return job.err.set(ORC_MISMATCH, "saved/target disagree on fqn " + std::to_string(fqn));
 
   const int64_t gvol = volume(t0.global_shape, n);
   std::vector<uint8_t> G((size_t)gvol * e);
@@ -238,12 +295,19 @@ void do_fqn(Job& job, int64_t fqn, const std::vector<Ref>& trefs) {
                                                " needed by target shard " + std::to_string(r.shard));
       }
       const int64_t b = stored_byte(sh, p, ci, y);
-      if (b < 0 || b + e > job.dst_bytes[sh.buf])
+      if (b < 0 || b + et > job.dst_bytes[sh.buf])
         return job.err.set(ORC_BOUNDS, "target shard " + std::to_string(r.shard) + " writes outside its buffer");
-      std::memcpy(job.dst[sh.buf] + b, &G[(size_t)gi * e], e);
+      if (e == et) {
+        std::memcpy(job.dst[sh.buf] + b, &G[(size_t)gi * e], e);
+      } else {  // 4-byte saved element, 2-byte target element: narrow
+        uint32_t wide;
+        std::memcpy(&wide, &G[(size_t)gi * e], 4);
+        const uint16_t narrow = f32_to_bf16(wide);
+        std::memcpy(job.dst[sh.buf] + b, &narrow, 2);
+      }
       if (job.dst_written) {
         uint8_t* w = job.dst_written[sh.buf] + b;
-        for (int k = 0; k < e; ++k)
+        for (int k = 0; k < et; ++k)
           if (w[k] != 255) ++w[k];  // distinct FQNs never share bytes in a sane layout; tests check == 1
       }
     }
@@ -258,6 +322,8 @@ extern "C" {
 // Reshard on the host.  src[i] / dst[i] are host byte buffers of src_bytes[i] / dst_bytes[i]
 // bytes.  dst_written (optional): per-byte counters the caller zeroed, incremented for every
 // byte written.  Returns ORC_OK or an error code and copies a message into err (if non-null).
+// convert: 0, or 1 to narrow tensors saved with 4-byte elements and asked for with 2-byte elements as
+// binary32 -> bfloat16 (other tensors are moved as they are).
 // Threads work on disjoint FQNs; dst_written increments can only collide if two FQNs share a
 // destination byte, which is itself a layout bug the counters then may under-report.
 int orc_reshard(const orc_part* sparts, const orc_shard* saved, int64_t n_saved,
@@ -265,7 +331,7 @@ int orc_reshard(const orc_part* sparts, const orc_shard* saved, int64_t n_saved,
                 const orc_part* tparts, const orc_shard* target, int64_t n_target,
                 uint8_t* const* dst, const int64_t* dst_bytes, uint8_t* const* dst_written,
                 int allow_uncovered, int n_threads, const int64_t* only_fqns, int64_t n_only,
-                char* err, int err_len) {
+                int convert, char* err, int err_len) {
   Job job;
   job.saved = Side{sparts, saved, n_saved, {}};
   job.target = Side{tparts, target, n_target, {}};
@@ -275,6 +341,7 @@ int orc_reshard(const orc_part* sparts, const orc_shard* saved, int64_t n_saved,
   job.dst_bytes = dst_bytes;
   job.dst_written = dst_written;
   job.allow_uncovered = allow_uncovered != 0;
+  job.convert = convert;
   if (index_side(job.saved, job.err) && index_side(job.target, job.err)) {
     std::vector<const std::pair<const int64_t, std::vector<Ref>>*> work;
     for (auto& kv : job.target.by_fqn) {
@@ -300,6 +367,11 @@ int orc_reshard(const orc_part* sparts, const orc_shard* saved, int64_t n_saved,
     std::snprintf(err, (size_t)err_len, "%s", job.err.msg.c_str());
   }
   return job.err.code;
+}
+
+// the narrowing alone, for its pins: out[i] = bfloat16 pattern of the binary32 pattern in[i]
+void orc_f32_to_bf16(const uint32_t* in, uint16_t* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = f32_to_bf16(in[i]);
 }
 
 int orc_max_dims(void) { return kMaxDims; }

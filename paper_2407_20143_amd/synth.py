@@ -87,6 +87,7 @@ class Case:
     tensors: Dict[int, TensorSpec]
     saved: Layout
     target: Layout
+    convert: int = 0  # 1: the target asks for fp32 tensors as bf16 (2-byte elements), see narrowed()
 
 
 def regular(part: Part, itemsize: int, buf: int, byte_offset: int, strides=None) -> Shard:
@@ -133,6 +134,13 @@ def global_tensor(spec: TensorSpec, seed: int, device="cpu") -> torch.Tensor:
         n = max(1, math.prod(shape)) * spec.dtype.itemsize
         raw = torch.randint(0, 256, (n,), generator=gen, device=device, dtype=torch.uint8)
         return raw.view(spec.dtype).reshape(shape)
+    elif kind == "bits_no_nan":  # float32 only: arbitrary bit patterns with every NaN turned into an infinity
+        assert spec.dtype == torch.float32
+        n = max(1, math.prod(shape))
+        raw = torch.randint(0, 256, (4 * n,), generator=gen, device=device, dtype=torch.uint8).view(torch.int32)
+        nan = (raw & 0x7FFFFFFF) > 0x7F800000
+        raw = torch.where(nan, raw & -8388608, raw)   # keep sign and exponent: +-infinity
+        return raw.view(torch.float32).reshape(shape)
     elif kind == "fill":  # every byte == dist[1] (coverage masks)
         n = max(1, math.prod(shape)) * spec.dtype.itemsize
         return torch.full((n,), spec.dist[1], device=device, dtype=torch.uint8).view(spec.dtype).reshape(shape)
@@ -148,6 +156,10 @@ def _box(G: torch.Tensor, p: Part) -> torch.Tensor:
 
 
 def _store(buf: torch.Tensor, sh: Shard, vals: torch.Tensor, dtype: torch.dtype) -> None:
+    if vals.dtype == torch.float32 and sh.itemsize == 2:
+        # a dtype-converting load: the shard holds the fp32 tensor as bf16 (the library's own cast)
+        vals, dtype = vals.to(torch.bfloat16), torch.bfloat16
+    assert vals.element_size() == sh.itemsize, (vals.dtype, sh.itemsize)
     if sh.strides is None:
         n = vals.numel() * sh.itemsize
         if n:
@@ -662,6 +674,30 @@ def llama_case(name: str, seed: int, layers: int, hidden: int, ffn: int, vocab: 
                                 only_ranks=only_target_ranks))
 
 
+def narrowed(layout: Layout) -> Layout:
+    """The same layout asked for with 2-byte elements instead of 4-byte ones (an evaluation job that
+    loads fp32 master weights as bf16, Sec. 2.2): same boxes, flat ranges and element strides, every
+    byte offset and buffer size halved (shards that were disjoint stay disjoint)."""
+    shards = []
+    for sh in layout.shards:
+        assert sh.itemsize == 4
+        shards.append(Shard(sh.parts, sh.flat_begin, sh.flat_end, 2, sh.buf, sh.byte_offset // 2, sh.strides, sh.group))
+    return Layout(shards, [max(1, (n + 1) // 2) for n in layout.buf_bytes])
+
+
+def eval_load_case(layers: int = 32, hidden: int = 4096, ffn: int = 11008, vocab: int = 32000,
+                   zero_saved: bool = False) -> Case:
+    """An evaluation job loads the model only (Sec. 2.2): the fp32 master weights of the 7B-shaped
+    decoder, saved TP4 PP2 (or, zero_saved, as a ZeRO flat buffer cut over DP16), are loaded as bf16
+    weights under TP2 PP4.  Every tensor is converted on the way."""
+    model = llama_tensors(layers, hidden, ffn, vocab)
+    states = [STATE_FP32_MASTER]
+    saved = (zero_layout(model, states, 1, 16, replicate_norms=False) if zero_saved
+             else megatron_layout(model, states, layers, 4, 2, replicate_norms=False))
+    target = narrowed(megatron_layout(model, states, layers, 2, 4, replicate_norms=True))
+    return Case("eval_load" + ("_zero" if zero_saved else ""), BASE_SEED + 6, _specs(model, states), saved, target, convert=1)
+
+
 def cfg2(layers: int = 24, hidden: int = 2048, ffn: int = 5504, vocab: int = 32000) -> Case:
     """bf16 decoder saved TP4 PP2, loaded TP2 PP4, all target shards."""
     return llama_case("cfg2", BASE_SEED + 2, layers, hidden, ffn, vocab, [STATE_BF16_WEIGHT], 4, 2, 2, 4)
@@ -871,10 +907,12 @@ RANDOM_DTYPES = (torch.uint8, torch.bfloat16, torch.float32, torch.float64, torc
 
 def random_case(seed: int, n_tensors: int = 5, max_elems: int = 3000, saved_mode: str = "grid",
                 target_mode: str = "grid", max_rank: int = 4, granules=(1, 2, 4, 8, 16, 256),
-                p_strided: float = 0.0, dtype: Optional[torch.dtype] = None) -> Case:
+                p_strided: float = 0.0, dtype: Optional[torch.dtype] = None, narrow_target: bool = False) -> Case:
     """Small random tensors (rank 0..max_rank, arbitrary bit patterns) under random saved and
     target layouts.  'grid': boxes from random cuts in every dimension; 'flat': ZeRO-like slices
-    of concatenated pieces (single dtype for the whole case)."""
+    of concatenated pieces (single dtype for the whole case).  narrow_target (dtype float32 only):
+    the target asks for every tensor as bf16."""
+    assert not narrow_target or dtype == torch.float32
     rng = np.random.default_rng(seed)
     flat = "flat" in (saved_mode, target_mode)
     one_dtype = dtype if dtype is not None else (RANDOM_DTYPES[int(rng.integers(0, len(RANDOM_DTYPES)))] if flat else None)
@@ -902,4 +940,7 @@ def random_case(seed: int, n_tensors: int = 5, max_elems: int = 3000, saved_mode
         return _random_flat_layout(rng, specs, int(rng.integers(1, 4)), int(rng.integers(1, 7)), g,
                                    int(rng.integers(1, 4)))
 
-    return Case(f"random{seed}", seed, specs, side(saved_mode), side(target_mode))
+    saved, target = side(saved_mode), side(target_mode)
+    if narrow_target:
+        return Case(f"random{seed}_narrow", seed, specs, saved, narrowed(target), convert=1)
+    return Case(f"random{seed}", seed, specs, saved, target)

@@ -46,6 +46,45 @@ MUTANTS = [
 ]
 
 
+# mistakes in the dtype-converting load; its pins are tests/test_oracle_convert.py
+CONVERT_MUTANTS = [
+    ("ties go away from zero instead of to even",
+     "else pick = (below & 1u) == 0 ? below : above;", "else pick = above;"),
+    ("truncation instead of rounding",
+     "if (down < up) pick = below;\n  else if (up < down) pick = above;", "if (down <= up || up < down) pick = below;\n  else if (up < down) pick = above;"),
+    ("bfloat16 subnormals one binade off",
+     "if (exp == 0) return std::ldexp(frac, -133);", "if (exp == 0) return std::ldexp(frac, -134);"),
+    ("binary32 subnormals one binade off",
+     "if (exp == 0) return std::ldexp(frac, -149);", "if (exp == 0) return std::ldexp(frac, -150);"),
+    ("seven fraction bits taken as eight",
+     "return std::ldexp(128.0 + frac, exp - 134);", "return std::ldexp(256.0 + frac, exp - 135);"),
+    ("sign dropped",
+     "return (uint16_t)((sign << 15) | pick);", "return (uint16_t)(pick);"),
+    ("NaN rounded like a number",
+     "if (mag > 0x7f800000u) {", "if (false) {"),
+    ("narrowing applied with the wrong element size in the global image",
+     "std::memcpy(&wide, &G[(size_t)gi * e], 4);", "std::memcpy(&wide, &G[(size_t)gi * et], 4);"),
+    ("conversion without the flag",
+     "if (job.convert == 1 && es == 4 && et == 2) e = es;", "if (es == 4 && et == 2) e = es;"),
+    ("any wider element size converts",
+     "if (job.convert == 1 && es == 4 && et == 2) e = es;", "if (job.convert == 1 && es > et) e = es;"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", CONVERT_MUTANTS, ids=[m[0] for m in CONVERT_MUTANTS])
+def test_convert_pins_catch_the_mutant(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation site for '{name}' not found exactly once"
+    mutant_src = tmp_path / "mutant.cpp"
+    mutant_src.write_text(text.replace(old, new))
+    lib = tmp_path / "libmutant.so"
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", "-pthread", str(mutant_src), "-o", str(lib)])
+    env = dict(os.environ, ORACLE_LIB_OVERRIDE=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_convert.py"), "-x", "-q",
+                        "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode != 0, f"the pins did not notice: {name}\n{r.stdout[-2000:]}"
+
+
 @pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
 def test_pins_catch_the_mutant(tmp_path, name, old, new):
     text = open(SRC).read()
@@ -66,6 +105,7 @@ def test_unmodified_oracle_passes_the_same_run(tmp_path):
     lib = tmp_path / "liborig.so"
     subprocess.check_call(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", "-pthread", SRC, "-o", str(lib)])
     env = dict(os.environ, ORACLE_LIB_OVERRIDE=str(lib))
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                        os.path.join(ROOT, "tests", "test_oracle_convert.py"), "-x", "-q",
                         "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stdout[-2000:]
