@@ -40,7 +40,8 @@ extern "C" {
 typedef struct bcp_shard_meta {
   int64_t fqn_id;                     /* >= 0; identifies the tensor (string table stays with the caller) */
   int32_t ndim;                       /* 0..BCP_MAX_DIMS */
-  int32_t itemsize;                   /* bytes per element: 1, 2, 4, 8 or 16; dtype is opaque, no casting */
+  int32_t itemsize;                   /* bytes per element: 1, 2, 4, 8 or 16; the dtype itself is opaque (the one
+                                         cast there is: BCP_CONVERT_F32_TO_BF16) */
   int64_t global_shape[BCP_MAX_DIMS]; /* shape before sharding */
   int64_t offsets[BCP_MAX_DIMS];      /* nD_offsets */
   int64_t lengths[BCP_MAX_DIMS];      /* nD_lengths */
@@ -58,7 +59,7 @@ typedef enum bcp_status {
   BCP_OK = 0,
   BCP_ERR_INVALID_ARG = -1,     /* null pointer, negative count, bad ndim/itemsize/flat range/strides */
   BCP_ERR_SHAPE_MISMATCH = -2,  /* records of one FQN disagree on ndim or global shape */
-  BCP_ERR_DTYPE_MISMATCH = -3,  /* records of one FQN disagree on itemsize */
+  BCP_ERR_DTYPE_MISMATCH = -3,  /* records of one FQN disagree on itemsize (and no conversion covers the pair) */
   BCP_ERR_OUT_OF_BOUNDS = -4,   /* offsets+lengths beyond the global shape, or flat range beyond the box */
   BCP_ERR_SAVED_OVERLAP = -5,   /* two saved shards hold the same element (Sec. 4.1: one saver per shard) */
   BCP_ERR_UNCOVERED = -6,       /* a target element no saved shard holds */
@@ -76,6 +77,13 @@ typedef enum bcp_status {
                                        while the blobs arrive: see bcp_reshard_arrived */
 #define BCP_META_ON_DEVICE 8u       /* saved / target point to DEVICE memory (metadata produced or kept on the
                                        GPU): no host-to-device upload of the records */
+#define BCP_CONVERT_F32_TO_BF16 16u /* dtype-converting load (Sec. 2.2: evaluation jobs load the model only, so
+                                       fp32 master weights are read as bf16): a tensor whose saved records have
+                                       itemsize 4 and whose target records have itemsize 2 is narrowed on the way,
+                                       binary32 -> bfloat16, round to nearest, ties to even; infinities stay, NaN
+                                       stays NaN (sign and upper seven fraction bits kept, quiet bit set).  Tensors
+                                       whose sizes agree are moved as they are; any other disagreement stays
+                                       BCP_ERR_DTYPE_MISMATCH */
 
 typedef struct bcp_stats {
   int64_t n_saved_boxes;   /* regular boxes after decomposing the saved records */
@@ -91,6 +99,8 @@ typedef struct bcp_stats {
   double plan_device_ms;   /* device time of the planner kernels (HIP events) */
   double plan_wall_ms;     /* wall time of bcp_plan */
   int64_t n_batches;       /* queue items of the copy kernel: one big tile or a run of small ones */
+  int64_t src_bytes;       /* bytes the copy reads: payload_bytes (which counts bytes written) unless tensors are
+                              converted on the way */
 } bcp_stats;
 
 /* Region as the copy kernel sees it (for inspection and tests; many region lists are valid). */
@@ -139,6 +149,17 @@ bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, i
 bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_of, int64_t n, int32_t n_ranks,
                                uint8_t* keep, int64_t* load);
 
+/* The checks bcp_plan makes on the shard metadata, on the host and without a GPU: every record on its
+ * own (fields, box inside the global shape, flat range inside the box: Sec. 3.2), the records of one
+ * FQN against each other (rank, global shape, element size), saved shards pairwise disjoint (Sec. 4.1:
+ * one saver per shard), every target element held by a saved shard.  Returns what bcp_plan would return
+ * for the same arrays and flags (BCP_ALLOW_UNCOVERED, BCP_SKIP_OVERLAP_CHECK, BCP_CONVERT_F32_TO_BF16 are
+ * honoured, BCP_ORDER_BY_SOURCE is accepted), with the offending record in bcp_last_error().  Host
+ * arrays only.  Quadratic in the number of shards of one tensor: meant for checking metadata where no
+ * GPU is at hand (a planning or CI host), not as a step before every bcp_plan. */
+bcp_status bcp_validate_meta(const bcp_shard_meta* saved, int64_t n_saved,
+                             const bcp_shard_meta* target, int64_t n_target, uint32_t flags);
+
 /* Build a copy plan on the current HIP device (Sec. 3.3 Step 2 on the GPU).
  * saved/target: host arrays (device arrays with BCP_META_ON_DEVICE), borrowed for the duration of
  * the call; with very many records (the upload is 304 bytes each) pinned host memory pays.  stream: hipStream_t
@@ -151,6 +172,9 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved,
                     uint32_t flags, void* stream, bcp_plan_t* out_plan);
 
 /* Move the bytes: for every region, dst_buffers[dst_buf][...] = src_blobs[src_buf][...].
+ * This is where the paper's load pipeline puts the deserialised bytes of the matching segments into the
+ * new shards (Sec. 3.3 Step 5 and the read -> deserialize -> H2D pipeline of Sec. 4.2), with the saved
+ * blobs already in device memory.
  * src_blobs / dst_buffers: HOST arrays of DEVICE pointers (n_src > max_src_buf, n_dst >
  * max_dst_buf), owned by the caller; buffers must stay valid until the work queued on `stream`
  * completed and must not overlap each other.  Asynchronous: enqueues on `stream` (hipStream_t)
@@ -164,6 +188,14 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved,
 bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src,
                        void* const* dst_buffers, int32_t n_dst, void* stream);
 
+/* bcp_reshard for callers that know their buffer sizes: src_bytes[i] / dst_bytes[i] (host arrays, n_src /
+ * n_dst entries) are the sizes of src_blobs[i] / dst_buffers[i].  A buffer shorter than what the plan
+ * reads from or writes to it is BCP_ERR_OUT_OF_BOUNDS, returned before anything is launched (the extents
+ * are computed once, when the plan is built: the check costs a loop over the buffers on the host).
+ * bcp_reshard itself never sees sizes: there an undersized buffer is a GPU memory fault. */
+bcp_status bcp_reshard_checked(bcp_plan_t plan, const void* const* src_blobs, const int64_t* src_bytes, int32_t n_src,
+                               void* const* dst_buffers, const int64_t* dst_bytes, int32_t n_dst, void* stream);
+
 /* Chunked arrival (the step before this path in the paper's load pipeline, Sec. 4.2: read ->
  * deserialize -> H2D): run the part of a BCP_ORDER_BY_SOURCE plan whose LAST source byte lies in
  * bytes [byte_begin, byte_end) of src_blobs[src_buf].  Valid once bytes [0, byte_end) of that blob
@@ -173,10 +205,12 @@ bcp_status bcp_reshard_arrived(bcp_plan_t plan, const void* const* src_blobs, in
                                void* const* dst_buffers, int32_t n_dst,
                                int32_t src_buf, int64_t byte_begin, int64_t byte_end, void* stream);
 
-/* The whole overlapped loop: blob by blob, chunk by chunk, copy host_blobs[i] (HOST memory, pinned
- * for real overlap, blob_bytes[i] bytes) into src_blobs[i] (device) on copy_stream and run
- * bcp_reshard_arrived for the chunk on `stream` as soon as it has landed.  Enqueues everything and
- * returns; both streams keep their default priority.  The plan must be BCP_ORDER_BY_SOURCE. */
+/* The whole overlapped loop (the H2D stage of the load pipeline of Sec. 4.2 run against the reshard):
+ * blob by blob, chunk by chunk, copy host_blobs[i] (HOST memory, pinned for real overlap, blob_bytes[i]
+ * bytes) into src_blobs[i] (device, at least as large) on copy_stream and run bcp_reshard_arrived for
+ * the chunk on `stream` as soon as it has landed.  Enqueues everything and returns; both streams keep
+ * their default priority.  The plan must be BCP_ORDER_BY_SOURCE.  A blob shorter than what the plan
+ * reads from it is BCP_ERR_OUT_OF_BOUNDS (its last regions would never run). */
 bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs, const int64_t* blob_bytes,
                                  void* const* src_blobs, int32_t n_src, void* const* dst_buffers, int32_t n_dst,
                                  int64_t chunk_bytes, void* copy_stream, void* stream);
@@ -202,8 +236,8 @@ bcp_status bcp_plan_regions(bcp_plan_t plan, bcp_region_info* out, int64_t capac
 
 /* Smallest buffer sizes the plan is safe on: src_extent[i] / dst_extent[i] (host arrays of n_src /
  * n_dst entries, at least max_*_buf + 1) receive one past the highest byte any region touches in
- * src_blobs[i] / dst_buffers[i] (0 if unused).  bcp_reshard itself never sees buffer sizes, so a
- * caller that is not sure its buffers match the planned layout checks here first. */
+ * src_blobs[i] / dst_buffers[i] (0 if unused).  Computed when the plan is built; this call only
+ * copies them out. */
 bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t n_src,
                                    int64_t* dst_extent, int32_t n_dst);
 
@@ -228,10 +262,6 @@ bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_
  * released.  Plans already built are not affected.  Waits for no stream: the caller makes sure no
  * bcp_plan call is in flight on another thread (it would block until that call returned). */
 bcp_status bcp_release_workspace(int64_t* freed_bytes);
-
-/* Plain device-to-device streaming copy with the same vector width and launch shape as the reshard
- * kernel: the practical ceiling the bench reports beside it.  dst/src: device, 16-byte aligned. */
-bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream);
 
 const char* bcp_last_error(void); /* thread-local text of the last failure on this thread */
 const char* bcp_status_name(bcp_status s);

@@ -26,7 +26,7 @@ STATS = np.dtype([
     ("n_saved_boxes", "<i8"), ("n_target_boxes", "<i8"), ("n_pairs", "<i8"), ("n_regions", "<i8"),
     ("n_tiles", "<i8"), ("payload_bytes", "<i8"), ("n_transposed", "<i8"), ("max_src_buf", "<i8"),
     ("max_dst_buf", "<i8"), ("region_dims_hist", "<i8", (MAX_DIMS + 1,)),
-    ("plan_device_ms", "<f8"), ("plan_wall_ms", "<f8"), ("n_batches", "<i8"),
+    ("plan_device_ms", "<f8"), ("plan_wall_ms", "<f8"), ("n_batches", "<i8"), ("src_bytes", "<i8"),
 ], align=True)
 
 REGION_INFO = np.dtype([
@@ -41,14 +41,19 @@ BCP_ALLOW_UNCOVERED = 1
 BCP_SKIP_OVERLAP_CHECK = 2
 BCP_ORDER_BY_SOURCE = 4
 BCP_META_ON_DEVICE = 8
+BCP_CONVERT_F32_TO_BF16 = 16
+NOALLOC_MAX_BUFFERS = 8192
 
-EXPORTS = [
-    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_dedup_worst_fit", "bcp_plan", "bcp_reshard", "bcp_reshard_noalloc",
-    "bcp_reshard_arrived",
-    "bcp_reshard_from_host", "bcp_plan_stats",
-    "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy", "bcp_configure", "bcp_release_workspace",
-    "bcp_copy_baseline", "bcp_last_error",
+# entry points that need no GPU (csrc/bcp_host.cpp) ...
+HOST_EXPORTS = [
+    "bcp_meta_from_flat_slice", "bcp_decompose", "bcp_dedup_worst_fit", "bcp_validate_meta", "bcp_last_error",
     "bcp_status_name", "bcp_abi_version", "bcp_sizeof_shard_meta",
+]
+# ... and the rest of include/bcp.h
+EXPORTS = HOST_EXPORTS + [
+    "bcp_plan", "bcp_reshard", "bcp_reshard_checked", "bcp_reshard_noalloc", "bcp_reshard_arrived",
+    "bcp_reshard_from_host", "bcp_plan_stats", "bcp_plan_regions", "bcp_plan_buffer_extents", "bcp_plan_destroy",
+    "bcp_configure", "bcp_release_workspace",
 ]
 
 
@@ -62,36 +67,52 @@ class BcpError(RuntimeError):
 _lib = None
 
 
+def _signatures():
+    vp, i64, i32, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32
+    p64 = ctypes.POINTER(i64)
+    return {
+        "bcp_meta_from_flat_slice": [vp, i64, i64, i64, i32, i64, vp, p64],
+        "bcp_decompose": [vp, vp, p64],
+        "bcp_dedup_worst_fit": [vp, vp, i64, i32, vp, vp],
+        "bcp_validate_meta": [vp, i64, vp, i64, u32],
+        "bcp_plan": [vp, i64, vp, i64, u32, vp, ctypes.POINTER(vp)],
+        "bcp_reshard": [vp, vp, i32, vp, i32, vp],
+        "bcp_reshard_checked": [vp, vp, vp, i32, vp, vp, i32, vp],
+        "bcp_reshard_noalloc": [vp, vp, i32, vp, i32, vp],
+        "bcp_reshard_arrived": [vp, vp, i32, vp, i32, i32, i64, i64, vp],
+        "bcp_reshard_from_host": [vp, vp, vp, vp, i32, vp, i32, i64, vp, vp],
+        "bcp_plan_stats": [vp, vp],
+        "bcp_plan_regions": [vp, vp, i64, p64],
+        "bcp_plan_buffer_extents": [vp, vp, i32, vp, i32],
+        "bcp_plan_destroy": [vp],
+        "bcp_configure": [i64, i32, i32, i32],
+        "bcp_release_workspace": [p64],
+        "bcp_status_name": [ctypes.c_int],
+    }
+
+
 def lib():
-    """Load libbcp.so (built beforehand by paper_2407_20143_amd.build / __graft_entry__.build)."""
+    """Load libbcp.so (built beforehand by paper_2407_20143_amd.build / __graft_entry__.build).
+
+    BCP_HOST_LIB_OVERRIDE names a build of the host-only part alone (csrc/bcp_host.cpp compiled with a
+    plain C++ compiler, e.g. with sanitizers, for the CPU tests): then only HOST_EXPORTS exist."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2407_20143_amd.build); "
+        host_only = os.environ.get("BCP_HOST_LIB_OVERRIDE")
+        path = host_only or LIB_PATH
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it first (python -m paper_2407_20143_amd.build); "
                                "there is no fallback path")
-        L = ctypes.CDLL(LIB_PATH)
-        vp, i64, i32, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32
-        L.bcp_meta_from_flat_slice.argtypes = [vp, i64, i64, i64, i32, i64, vp, ctypes.POINTER(i64)]
-        L.bcp_decompose.argtypes = [vp, vp, ctypes.POINTER(i64)]
-        L.bcp_dedup_worst_fit.argtypes = [vp, vp, i64, i32, vp, vp]
-        L.bcp_plan.argtypes = [vp, i64, vp, i64, u32, vp, ctypes.POINTER(vp)]
-        L.bcp_reshard.argtypes = [vp, vp, i32, vp, i32, vp]
-        L.bcp_reshard_noalloc.argtypes = [vp, vp, i32, vp, i32, vp]
-        L.bcp_reshard_arrived.argtypes = [vp, vp, i32, vp, i32, i32, i64, i64, vp]
-        L.bcp_reshard_from_host.argtypes = [vp, vp, vp, vp, i32, vp, i32, i64, vp, vp]
-        L.bcp_plan_stats.argtypes = [vp, vp]
-        L.bcp_plan_regions.argtypes = [vp, vp, i64, ctypes.POINTER(i64)]
-        L.bcp_plan_buffer_extents.argtypes = [vp, vp, i32, vp, i32]
-        L.bcp_plan_destroy.argtypes = [vp]
-        L.bcp_configure.argtypes = [i64, i32, i32, i32]
-        L.bcp_copy_baseline.argtypes = [vp, vp, i64, vp]
-        L.bcp_release_workspace.argtypes = [ctypes.POINTER(ctypes.c_int64)]
-        for f in EXPORTS:
-            getattr(L, f).restype = ctypes.c_int
+        L = ctypes.CDLL(path)
+        sig = _signatures()
+        for f in (HOST_EXPORTS if host_only else EXPORTS):
+            fn = getattr(L, f)
+            fn.restype = ctypes.c_int
+            if f in sig:
+                fn.argtypes = sig[f]
         L.bcp_last_error.restype = ctypes.c_char_p
         L.bcp_status_name.restype = ctypes.c_char_p
-        L.bcp_status_name.argtypes = [ctypes.c_int]
-        L.bcp_sizeof_shard_meta.restype = i64
+        L.bcp_sizeof_shard_meta.restype = ctypes.c_int64
         if L.bcp_sizeof_shard_meta() != SHARD_META.itemsize:
             raise RuntimeError("bcp_shard_meta layout mismatch between binding and library")
         _lib = L
@@ -180,6 +201,14 @@ def dedup_worst_fit(meta: np.ndarray, rank_of, n_ranks: int):
     return keep[:len(meta)].astype(bool), load
 
 
+def validate_meta(saved_meta: np.ndarray, target_meta: np.ndarray, flags: int = 0) -> None:
+    """bcp_validate_meta: the metadata checks of bcp_plan on the host, without a GPU (raises BcpError)."""
+    saved_meta = np.ascontiguousarray(saved_meta, dtype=SHARD_META)
+    target_meta = np.ascontiguousarray(target_meta, dtype=SHARD_META)
+    _check(lib().bcp_validate_meta(saved_meta.ctypes.data if len(saved_meta) else None, len(saved_meta),
+                                   target_meta.ctypes.data if len(target_meta) else None, len(target_meta), flags))
+
+
 def pinned_meta(meta: np.ndarray) -> np.ndarray:
     """A copy of a bcp_shard_meta array in pinned host memory (bcp_plan uploads 304 bytes per record;
     from pinned memory that runs at the full host-to-device rate).  Without a GPU: the array itself."""
@@ -221,18 +250,15 @@ def _layout_to_meta(layout) -> np.ndarray:
 class Plan:
     def __init__(self, handle):
         self._h = handle
-        self._extents = None
 
     def buffer_extents(self):
-        """(src, dst): per buffer, one past the highest byte the plan touches (cached)."""
-        if self._extents is None:
-            st = self.stats()
-            ns, nd = st["max_src_buf"] + 1, st["max_dst_buf"] + 1
-            s = np.zeros(max(ns, 1), dtype=np.int64)
-            d = np.zeros(max(nd, 1), dtype=np.int64)
-            _check(lib().bcp_plan_buffer_extents(self._h, s.ctypes.data, ns, d.ctypes.data, nd))
-            self._extents = (s[:ns], d[:nd])
-        return self._extents
+        """(src, dst): per buffer, one past the highest byte the plan touches."""
+        st = self.stats()
+        ns, nd = st["max_src_buf"] + 1, st["max_dst_buf"] + 1
+        s = np.zeros(max(ns, 1), dtype=np.int64)
+        d = np.zeros(max(nd, 1), dtype=np.int64)
+        _check(lib().bcp_plan_buffer_extents(self._h, s.ctypes.data, ns, d.ctypes.data, nd))
+        return s[:ns], d[:nd]
 
     def stats(self) -> dict:
         out = np.zeros(1, dtype=STATS)
@@ -301,18 +327,18 @@ def _ptrs(bufs: Sequence) -> "ctypes.Array":
     return arr
 
 
+def _sizes(bufs: Sequence):
+    return (ctypes.c_int64 * max(len(bufs), 1))(*[b.numel() * b.element_size() for b in bufs])
+
+
 def reshard(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, stream=None, check_sizes: bool = True) -> None:
     """bcp_reshard(plan, src_blobs, dst_buffers, stream): asynchronous on `stream` (default: torch's current).
-    check_sizes: when the buffers are tensors, refuse buffers smaller than the plan's extents (the
-    extents are computed once per plan) -- an undersized buffer would otherwise be a GPU memory fault."""
-    if check_sizes:
-        se, de = p.buffer_extents()
-        for what, ext, bufs in (("src_blobs", se, src_blobs), ("dst_buffers", de, dst_buffers)):
-            for i, need in enumerate(ext):
-                if i < len(bufs) and not isinstance(bufs[i], int):
-                    have = bufs[i].numel() * bufs[i].element_size()
-                    if have < need:
-                        raise ValueError(f"{what}[{i}] holds {have} bytes, the plan touches {int(need)}")
+    check_sizes (the buffers are tensors): go through bcp_reshard_checked, which refuses buffers smaller
+    than what the plan touches -- an undersized buffer would otherwise be a GPU memory fault."""
+    if check_sizes and not any(isinstance(b, int) for b in list(src_blobs) + list(dst_buffers)):
+        _check(lib().bcp_reshard_checked(p._h, _ptrs(src_blobs), _sizes(src_blobs), len(src_blobs),
+                                         _ptrs(dst_buffers), _sizes(dst_buffers), len(dst_buffers), _stream_ptr(stream)))
+        return
     _check(lib().bcp_reshard(p._h, _ptrs(src_blobs), len(src_blobs), _ptrs(dst_buffers), len(dst_buffers),
                              _stream_ptr(stream)))
 
@@ -334,10 +360,9 @@ def reshard_arrived(p: Plan, src_blobs: Sequence, dst_buffers: Sequence, src_buf
 def reshard_from_host(p: Plan, host_blobs: Sequence, src_blobs: Sequence, dst_buffers: Sequence, chunk_bytes: int,
                       copy_stream, stream=None) -> None:
     """bcp_reshard_from_host: chunked host-to-device arrival overlapped with the reshard."""
-    sizes = (ctypes.c_int64 * max(len(host_blobs), 1))(*[b.numel() * b.element_size() for b in host_blobs])
-    for i, need in enumerate(p.buffer_extents()[0]):
-        if i >= len(host_blobs) or sizes[i] < need:
-            raise ValueError(f"host blob {i} is shorter than the {int(need)} bytes the plan reads from it")
+    sizes = _sizes(host_blobs)
+    if len(host_blobs) < len(src_blobs):
+        raise ValueError("fewer host blobs than device blobs")
     for h, d in zip(host_blobs, src_blobs):
         if d.numel() * d.element_size() < h.numel() * h.element_size():
             raise ValueError("device blob smaller than its host blob")
@@ -358,8 +383,3 @@ def release_workspace() -> int:
 
 
 DEFAULT_CONFIG = dict(tile_bytes=65536, persistent=1, wg_per_cu=1, threads=1024)
-
-
-def copy_baseline(dst, src, nbytes: Optional[int] = None, stream=None) -> None:
-    n = nbytes if nbytes is not None else src.numel() * src.element_size()
-    _check(lib().bcp_copy_baseline(dst.data_ptr(), src.data_ptr(), n, _stream_ptr(stream)))

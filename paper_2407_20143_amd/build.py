@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libbcp.so")
-SOURCES = ["bcp_api.hip", "bcp_planner.hip", "bcp_copy.hip"]
+SOURCES = ["bcp_api.hip", "bcp_planner.hip", "bcp_copy.hip", "bcp_host.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

@@ -1,4 +1,5 @@
-// C-ABI layer: argument checks, plan object, pointer-table staging, host helpers (a1, a2 mirror).
+// C-ABI layer of the GPU entry points: argument checks, plan object, pointer-table staging.
+// (The entry points that need no GPU are in bcp_host.cpp.)
 #include <algorithm>
 #include <chrono>
 #include <cstring>
@@ -12,15 +13,12 @@
 namespace bcp {
 
 namespace {
-thread_local std::string g_error;
 PlanConfig g_config;
 std::mutex g_config_mu;
 }  // namespace
 
-void set_error(const std::string& msg) { g_error = msg; }
-
 bcp_status hip_fail(hipError_t e, const char* what) {
-  g_error = std::string(what) + ": " + hipGetErrorString(e);
+  set_error(std::string(what) + ": " + hipGetErrorString(e));
   if (e == hipErrorOutOfMemory) return BCP_ERR_OOM;
   if (e == hipErrorNoDevice || e == hipErrorInvalidDevice) return BCP_ERR_NO_DEVICE;
   return BCP_ERR_HIP;
@@ -29,28 +27,6 @@ bcp_status hip_fail(hipError_t e, const char* what) {
 PlanConfig config() {
   std::lock_guard<std::mutex> g(g_config_mu);
   return g_config;
-}
-
-// No exception leaves the library: every entry point that can allocate on the host is a function
-// try block that ends here.
-static bcp_status on_exception(const char* who) noexcept {
-  try {
-    throw;
-  } catch (const std::bad_alloc&) {
-    try {
-      set_error(std::string(who) + ": out of host memory");
-    } catch (...) {
-    }
-    return BCP_ERR_OOM;
-  } catch (const std::exception& e) {
-    try {
-      set_error(std::string(who) + ": " + e.what());
-    } catch (...) {
-    }
-    return BCP_ERR_INVALID_ARG;
-  } catch (...) {
-    return BCP_ERR_INVALID_ARG;
-  }
 }
 
 }  // namespace bcp
@@ -71,6 +47,7 @@ struct bcp_plan_s {
   char* table_host = nullptr;  // pinned, kSlots slots
   size_t table_bytes = 0;
   int32_t n_src = 0, n_dst = 0;
+  std::vector<int64_t> src_extent, dst_extent;  // per buffer: one past the highest byte the plan touches
   hipEvent_t slot_done[kSlots]{};
   bool slot_used[kSlots]{};
   int next_slot = 0;
@@ -82,28 +59,6 @@ struct bcp_plan_s {
 };
 
 extern "C" {
-
-const char* bcp_last_error(void) { return g_error.c_str(); }
-
-const char* bcp_status_name(bcp_status s) {
-  switch (s) {
-    case BCP_OK: return "BCP_OK";
-    case BCP_ERR_INVALID_ARG: return "BCP_ERR_INVALID_ARG";
-    case BCP_ERR_SHAPE_MISMATCH: return "BCP_ERR_SHAPE_MISMATCH";
-    case BCP_ERR_DTYPE_MISMATCH: return "BCP_ERR_DTYPE_MISMATCH";
-    case BCP_ERR_OUT_OF_BOUNDS: return "BCP_ERR_OUT_OF_BOUNDS";
-    case BCP_ERR_SAVED_OVERLAP: return "BCP_ERR_SAVED_OVERLAP";
-    case BCP_ERR_UNCOVERED: return "BCP_ERR_UNCOVERED";
-    case BCP_ERR_TOO_MANY_DIMS: return "BCP_ERR_TOO_MANY_DIMS";
-    case BCP_ERR_OOM: return "BCP_ERR_OOM";
-    case BCP_ERR_HIP: return "BCP_ERR_HIP";
-    case BCP_ERR_NO_DEVICE: return "BCP_ERR_NO_DEVICE";
-  }
-  return "BCP_ERR_UNKNOWN";
-}
-
-int32_t bcp_abi_version(void) { return 1; }
-int64_t bcp_sizeof_shard_meta(void) { return (int64_t)sizeof(bcp_shard_meta); }
 
 bcp_status bcp_release_workspace(int64_t* freed_bytes) { return release_workspace(freed_bytes); }
 
@@ -136,194 +91,6 @@ bcp_status bcp_configure(int64_t tile_bytes, int32_t persistent, int32_t wg_per_
   return on_exception("bcp_configure");
 }
 
-// ---- a1: flat slice of a concatenation -> per-tensor records ----------------------------------
-bcp_status bcp_meta_from_flat_slice(const bcp_shard_meta* params, int64_t n_params, int64_t A, int64_t B,
-                                    int32_t buf, int64_t byte_offset, bcp_shard_meta* out, int64_t* inout_n) try {
-  if (!inout_n || n_params < 0 || (n_params > 0 && !params) || A < 0 || B < A || buf < 0 || byte_offset < 0) {
-    set_error("bcp_meta_from_flat_slice: bad argument");
-    return BCP_ERR_INVALID_ARG;
-  }
-  const int64_t room = *inout_n;
-  int64_t written = 0, pos = 0;
-  for (int64_t i = 0; i < n_params; ++i) {
-    const bcp_shard_meta& p = params[i];
-    if (p.ndim < 0 || p.ndim > BCP_MAX_DIMS) {
-      set_error("bcp_meta_from_flat_slice: bad ndim in parameter " + std::to_string(i));
-      return p.ndim < 0 ? BCP_ERR_INVALID_ARG : BCP_ERR_TOO_MANY_DIMS;
-    }
-    int64_t vol = 1;
-    bool strided = false;
-    for (int k = 0; k < p.ndim; ++k) {
-      if (p.lengths[k] < 0) {
-        set_error("bcp_meta_from_flat_slice: negative length");
-        return BCP_ERR_INVALID_ARG;
-      }
-      vol *= p.lengths[k];
-      strided |= p.strides[k] != 0;
-    }
-    if (strided || p.flat_begin != 0 || p.flat_end != vol || p.itemsize != params[0].itemsize) {
-      set_error("bcp_meta_from_flat_slice: parameter " + std::to_string(i) +
-                " must be a regular packed record of the common itemsize");
-      return BCP_ERR_INVALID_ARG;
-    }
-    // the part of [A, B) inside this tensor's span [pos, pos + vol)
-    const int64_t lo = std::max(A, pos), hi = std::min(B, pos + vol);
-    if (lo < hi) {
-      if (out && written < room) {
-        bcp_shard_meta r = p;
-        r.flat_begin = lo - pos;
-        r.flat_end = hi - pos;
-        r.buf = buf;
-        r.byte_offset = byte_offset + (int64_t)p.itemsize * (lo - A);
-        out[written] = r;
-      }
-      ++written;
-    }
-    pos += vol;
-  }
-  if (B > pos) {
-    set_error("bcp_meta_from_flat_slice: slice ends beyond the concatenation");
-    return BCP_ERR_OUT_OF_BOUNDS;
-  }
-  *inout_n = written;
-  if (written > room || (written > 0 && !out)) {
-    set_error("bcp_meta_from_flat_slice: output array too small");
-    return BCP_ERR_INVALID_ARG;
-  }
-  return BCP_OK;
-} catch (...) {
-  return on_exception("bcp_meta_from_flat_slice");
-}
-
-// ---- a2: host mirror of the device decomposer ---------------------------------------------------
-bcp_status bcp_decompose(const bcp_shard_meta* rec, bcp_shard_meta* out_boxes, int64_t* inout_n) try {
-  if (!rec || !inout_n) {
-    set_error("bcp_decompose: null argument");
-    return BCP_ERR_INVALID_ARG;
-  }
-  if (rec->ndim < 0 || rec->ndim > BCP_MAX_DIMS) {
-    set_error("bcp_decompose: bad ndim");
-    return rec->ndim < 0 ? BCP_ERR_INVALID_ARG : BCP_ERR_TOO_MANY_DIMS;
-  }
-  int64_t len[kDims];
-  int n = rec->ndim;
-  int64_t vol = 1;
-  for (int k = 0; k < n; ++k) {
-    if (rec->lengths[k] < 0) {
-      set_error("bcp_decompose: negative length");
-      return BCP_ERR_INVALID_ARG;
-    }
-    len[k] = rec->lengths[k];
-    vol *= len[k];
-    if (rec->strides[k] != 0) {
-      set_error("bcp_decompose: strided records are regular by definition");
-      return BCP_ERR_INVALID_ARG;
-    }
-  }
-  if (n == 0) {
-    len[0] = 1;
-    n = 1;
-  }
-  if (rec->flat_begin < 0 || rec->flat_end < rec->flat_begin || rec->flat_end > vol) {
-    set_error("bcp_decompose: flat range outside the box");
-    return BCP_ERR_OUT_OF_BOUNDS;
-  }
-  LocalBox lb[kMaxBoxesPerRecord];
-  const int nb = decompose_flat_range(len, n, rec->flat_begin, rec->flat_end, lb);
-  const int64_t room = *inout_n;
-  *inout_n = nb;
-  if (nb > room || (nb > 0 && !out_boxes)) {
-    set_error("bcp_decompose: output array too small");
-    return BCP_ERR_INVALID_ARG;
-  }
-  for (int j = 0; j < nb; ++j) {
-    bcp_shard_meta b = *rec;
-    int64_t v = 1;
-    for (int k = 0; k < rec->ndim; ++k) {
-      b.offsets[k] = rec->offsets[k] + lb[j].off[k];
-      b.lengths[k] = lb[j].len[k];
-      v *= lb[j].len[k];
-    }
-    b.flat_begin = 0;
-    b.flat_end = v;
-    b.byte_offset = rec->byte_offset + (int64_t)rec->itemsize * (lb[j].flat_start - rec->flat_begin);
-    out_boxes[j] = b;
-  }
-  return BCP_OK;
-} catch (...) {
-  return on_exception("bcp_decompose");
-}
-
-// ---- save-side deduplication (Worst-Fit) ----------------------------------------------------------
-namespace {
-struct ShardIdentity {
-  const bcp_shard_meta* r;
-  bool operator==(const ShardIdentity& o) const {
-    const bcp_shard_meta &a = *r, &b = *o.r;
-    if (a.fqn_id != b.fqn_id || a.ndim != b.ndim || a.itemsize != b.itemsize || a.flat_begin != b.flat_begin ||
-        a.flat_end != b.flat_end)
-      return false;
-    for (int k = 0; k < a.ndim; ++k)
-      if (a.offsets[k] != b.offsets[k] || a.lengths[k] != b.lengths[k]) return false;
-    return true;
-  }
-};
-struct ShardIdentityHash {
-  size_t operator()(const ShardIdentity& s) const {
-    const bcp_shard_meta& a = *s.r;
-    uint64_t h = 0x9e3779b97f4a7c15ull ^ (uint64_t)a.fqn_id;
-    auto mix = [&](uint64_t v) { h = (h ^ v) * 0x100000001b3ull; h ^= h >> 29; };
-    mix((uint64_t)a.flat_begin);
-    mix((uint64_t)a.flat_end);
-    for (int k = 0; k < a.ndim; ++k) {
-      mix((uint64_t)a.offsets[k]);
-      mix((uint64_t)a.lengths[k]);
-    }
-    return (size_t)h;
-  }
-};
-}  // namespace
-
-bcp_status bcp_dedup_worst_fit(const bcp_shard_meta* recs, const int32_t* rank_of, int64_t n, int32_t n_ranks,
-                               uint8_t* keep, int64_t* load) try {
-  if (n < 0 || n_ranks <= 0 || (n > 0 && (!recs || !rank_of || !keep))) {
-    set_error("bcp_dedup_worst_fit: bad argument");
-    return BCP_ERR_INVALID_ARG;
-  }
-  std::unordered_map<ShardIdentity, int64_t, ShardIdentityHash> group_of;  // identity -> group index
-  std::vector<std::vector<int64_t>> groups;                                // in order of first appearance
-  for (int64_t i = 0; i < n; ++i) {
-    if (recs[i].ndim < 0 || recs[i].ndim > BCP_MAX_DIMS || rank_of[i] < 0 || rank_of[i] >= n_ranks ||
-        recs[i].flat_end < recs[i].flat_begin || recs[i].itemsize <= 0) {
-      set_error("bcp_dedup_worst_fit: bad record " + std::to_string(i));
-      return BCP_ERR_INVALID_ARG;
-    }
-    auto it = group_of.find(ShardIdentity{&recs[i]});
-    if (it == group_of.end()) {
-      group_of.emplace(ShardIdentity{&recs[i]}, (int64_t)groups.size());
-      groups.emplace_back(1, i);
-    } else {
-      groups[(size_t)it->second].push_back(i);
-    }
-  }
-  std::vector<int64_t> assigned((size_t)n_ranks, 0);
-  for (int64_t i = 0; i < n; ++i) keep[i] = 0;
-  for (const std::vector<int64_t>& g : groups) {
-    int64_t best = g[0];
-    for (int64_t i : g) {
-      const int64_t li = assigned[(size_t)rank_of[i]], lb = assigned[(size_t)rank_of[best]];
-      if (li < lb || (li == lb && rank_of[i] < rank_of[best])) best = i;
-    }
-    keep[best] = 1;
-    assigned[(size_t)rank_of[best]] += (recs[best].flat_end - recs[best].flat_begin) * (int64_t)recs[best].itemsize;
-  }
-  if (load)
-    for (int32_t r = 0; r < n_ranks; ++r) load[r] = assigned[(size_t)r];
-  return BCP_OK;
-} catch (...) {
-  return on_exception("bcp_dedup_worst_fit");
-}
-
 // ---- plan ------------------------------------------------------------------------------------
 bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shard_meta* target, int64_t n_target,
                     uint32_t flags, void* stream, bcp_plan_t* out_plan) try {
@@ -337,7 +104,8 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     set_error("bcp_plan: null metadata array or negative count");
     return BCP_ERR_INVALID_ARG;
   }
-  if (flags & ~(BCP_ALLOW_UNCOVERED | BCP_SKIP_OVERLAP_CHECK | BCP_ORDER_BY_SOURCE | BCP_META_ON_DEVICE)) {
+  if (flags & ~(BCP_ALLOW_UNCOVERED | BCP_SKIP_OVERLAP_CHECK | BCP_ORDER_BY_SOURCE | BCP_META_ON_DEVICE |
+                BCP_CONVERT_F32_TO_BF16)) {
     set_error("bcp_plan: unknown flag");
     return BCP_ERR_INVALID_ARG;
   }
@@ -381,6 +149,9 @@ bcp_status bcp_plan(const bcp_shard_meta* saved, int64_t n_saved, const bcp_shar
     for (int k = 0; k <= BCP_MAX_DIMS; ++k) st.region_dims_hist[k] = (int64_t)res.ctl.dims_hist[k];
     st.plan_device_ms = res.device_ms;
     st.n_batches = res.dev.n_batches;
+    st.src_bytes = (int64_t)res.ctl.src_bytes;
+    plan->src_extent = std::move(res.src_extent);
+    plan->dst_extent = std::move(res.dst_extent);
     plan->n_src = (int32_t)(st.max_src_buf + 1);
     plan->n_dst = (int32_t)(st.max_dst_buf + 1);
     plan->table_bytes = sizeof(void*) * (size_t)(plan->n_src + plan->n_dst);
@@ -461,25 +232,8 @@ bcp_status bcp_plan_buffer_extents(bcp_plan_t plan, int64_t* src_extent, int32_t
     set_error("bcp_plan_buffer_extents: bad argument");
     return BCP_ERR_INVALID_ARG;
   }
-  for (int32_t i = 0; i < n_src; ++i) src_extent[i] = 0;
-  for (int32_t i = 0; i < n_dst; ++i) dst_extent[i] = 0;
-  const int64_t n = plan->dev.n_regions;
-  const int64_t chunk = 1 << 16;
-  std::vector<Region> tmp((size_t)std::min(n, chunk));
-  for (int64_t base = 0; base < n; base += chunk) {
-    const int64_t m = std::min(chunk, n - base);
-    BCP_HIP(hipMemcpy(tmp.data(), plan->dev.regions + base, sizeof(Region) * (size_t)m, hipMemcpyDeviceToHost));
-    for (int64_t i = 0; i < m; ++i) {
-      const Region& r = tmp[(size_t)i];
-      int64_t s_end = r.src_base + r.run_bytes, d_end = r.dst_base + r.run_bytes;
-      for (int k = 0; k < r.ndim; ++k) {
-        s_end += (r.len[k] - 1) * r.spitch[k];
-        d_end += (r.len[k] - 1) * r.dpitch[k];
-      }
-      src_extent[r.src_buf] = std::max(src_extent[r.src_buf], s_end);
-      dst_extent[r.dst_buf] = std::max(dst_extent[r.dst_buf], d_end);
-    }
-  }
+  for (int32_t i = 0; i < n_src; ++i) src_extent[i] = (size_t)i < plan->src_extent.size() ? plan->src_extent[(size_t)i] : 0;
+  for (int32_t i = 0; i < n_dst; ++i) dst_extent[i] = (size_t)i < plan->dst_extent.size() ? plan->dst_extent[(size_t)i] : 0;
   return BCP_OK;
 } catch (...) {
   return on_exception("bcp_plan_buffer_extents");
@@ -552,6 +306,29 @@ bcp_status bcp_reshard(bcp_plan_t plan, const void* const* src_blobs, int32_t n_
   return on_exception("bcp_reshard");
 }
 
+bcp_status bcp_reshard_checked(bcp_plan_t plan, const void* const* src_blobs, const int64_t* src_bytes, int32_t n_src,
+                               void* const* dst_buffers, const int64_t* dst_bytes, int32_t n_dst, void* stream) try {
+  if (bcp_status s = check_reshard_args(plan, src_blobs, n_src, dst_buffers, n_dst, "bcp_reshard_checked")) return s;
+  if (plan->dev.n_tiles == 0) return BCP_OK;
+  if (!src_bytes || !dst_bytes) {
+    set_error("bcp_reshard_checked: null size array");
+    return BCP_ERR_INVALID_ARG;
+  }
+  for (int side = 0; side < 2; ++side) {
+    const std::vector<int64_t>& need = side ? plan->dst_extent : plan->src_extent;
+    const int64_t* have = side ? dst_bytes : src_bytes;
+    for (size_t i = 0; i < need.size(); ++i)
+      if (have[i] < need[i]) {
+        set_error(std::string("bcp_reshard_checked: ") + (side ? "dst_buffers[" : "src_blobs[") + std::to_string(i) + "] holds " +
+                  std::to_string(have[i]) + " bytes, the plan touches " + std::to_string(need[i]));
+        return BCP_ERR_OUT_OF_BOUNDS;
+      }
+  }
+  return reshard_impl(plan, src_blobs, n_src, dst_buffers, n_dst, stream, nullptr, "bcp_reshard_checked");
+} catch (...) {
+  return on_exception("bcp_reshard_checked");
+}
+
 bcp_status bcp_reshard_noalloc(bcp_plan_t plan, const void* const* src_blobs, int32_t n_src, void* const* dst_buffers,
                                int32_t n_dst, void* stream) try {
   if (bcp_status s = check_reshard_args(plan, src_blobs, n_src, dst_buffers, n_dst, "bcp_reshard_noalloc")) return s;
@@ -591,7 +368,24 @@ bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs,
     set_error("bcp_reshard_from_host: the copy stream and the reshard stream must differ");
     return BCP_ERR_INVALID_ARG;
   }
+  if (bcp_status s = check_reshard_args(plan, src_blobs, n_src, dst_buffers, n_dst, "bcp_reshard_from_host")) return s;
   if (plan->dev.n_tiles == 0) return BCP_OK;
+  if (!plan->dev.batch_key) {
+    set_error("bcp_reshard_from_host: the plan was not built with BCP_ORDER_BY_SOURCE");
+    return BCP_ERR_INVALID_ARG;
+  }
+  // every blob is looked at before anything is queued
+  for (int32_t b = 0; b < plan->n_src; ++b) {
+    if (blob_bytes[b] < 0 || (blob_bytes[b] > 0 && !host_blobs[b])) {
+      set_error("bcp_reshard_from_host: blob " + std::to_string(b) + " has no host buffer");
+      return BCP_ERR_INVALID_ARG;
+    }
+    if (blob_bytes[b] < plan->src_extent[(size_t)b]) {  // its last regions would wait for bytes that never arrive
+      set_error("bcp_reshard_from_host: blob " + std::to_string(b) + " holds " + std::to_string(blob_bytes[b]) +
+                " bytes, the plan reads " + std::to_string(plan->src_extent[(size_t)b]));
+      return BCP_ERR_OUT_OF_BOUNDS;
+    }
+  }
   hipStream_t cs = (hipStream_t)copy_stream;
   hipStream_t st = (hipStream_t)stream;
   // the copy stream starts after whatever the reshard stream has queued (buffers may still be in use)
@@ -612,11 +406,7 @@ bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs,
   BCP_HIP(next_event(&ev));
   BCP_HIP(hipEventRecord(ev, st));
   BCP_HIP(hipStreamWaitEvent(cs, ev, 0));
-  for (int32_t b = 0; b < plan->n_src && b < n_src; ++b) {
-    if (blob_bytes[b] < 0 || (blob_bytes[b] > 0 && (!host_blobs[b] || !src_blobs || !src_blobs[b]))) {
-      set_error("bcp_reshard_from_host: blob " + std::to_string(b) + " has no host or device buffer");
-      return BCP_ERR_INVALID_ARG;
-    }
+  for (int32_t b = 0; b < plan->n_src; ++b) {
     for (int64_t off = 0; off < blob_bytes[b]; off += chunk_bytes) {
       const int64_t n = std::min(chunk_bytes, blob_bytes[b] - off);
       BCP_HIP(hipMemcpyAsync((char*)src_blobs[b] + off, (const char*)host_blobs[b] + off, (size_t)n,
@@ -631,16 +421,6 @@ bcp_status bcp_reshard_from_host(bcp_plan_t plan, const void* const* host_blobs,
   return BCP_OK;
 } catch (...) {
   return on_exception("bcp_reshard_from_host");
-}
-
-bcp_status bcp_copy_baseline(void* dst, const void* src, int64_t nbytes, void* stream) try {
-  if (!dst || !src || nbytes < 0) {
-    set_error("bcp_copy_baseline: bad argument");
-    return BCP_ERR_INVALID_ARG;
-  }
-  return launch_copy_baseline(dst, src, nbytes, (hipStream_t)stream);
-} catch (...) {
-  return on_exception("bcp_copy_baseline");
 }
 
 }  // extern "C"

@@ -10,7 +10,9 @@
 //                              unaligned 16-byte loads + aligned 16-byte stores;
 //   * granule path          -- short runs: 8/4/2/1-byte elements, flat over rows x run;
 //   * LDS-staged transpose  -- the source-contiguous and destination-contiguous dimensions
-//                              differ (strided shards): both global sides stay coalesced.
+//                              differ (strided shards): both global sides stay coalesced;
+//   * narrowing rows        -- dtype-converting loads (fp32 saved, bf16 asked for): 4 bytes read and
+//                              2 written per element, eight elements per lane and access.
 // Scheduling: a persistent grid of (CU count x wg_per_cu) workgroups pops batch indices from an
 // atomic queue; a batch is one big tile (whole workgroup) or a run of small tiles that share the
 // workgroup's threads in proportion to their size, so 100k tiny tensors do not cost one queue pop
@@ -357,6 +359,91 @@ __device__ __forceinline__ void copy_rows_unaligned(gsrc_t __restrict__ s, gdst_
   }
 }
 
+// ---- dtype-converting rows: binary32 -> bfloat16 -----------------------------------------------------
+// Round to nearest, ties to even (IEEE 754 roundTiesToEven) on the bit pattern: bfloat16 is the upper
+// half of binary32, so adding 0x7FFF plus the lowest kept bit carries into the kept half exactly when
+// the dropped half is above one half, or equal to it with an odd kept half.  The carry may run on
+// into the exponent, which is the right result there too (the next binade, or infinity).  Infinity has
+// a zero lower half and stays.  NaN stays NaN: sign and the upper seven fraction bits kept, quiet.
+__device__ __forceinline__ uint32_t narrow_bf16(uint32_t u) {
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t nan = (u >> 16) | 0x40u;
+  return (u & 0x7fffffffu) > 0x7f800000u ? nan : rounded;
+}
+__device__ __forceinline__ uint32_t narrow_pair(uint32_t lo, uint32_t hi) { return narrow_bf16(lo) | (narrow_bf16(hi) << 16); }
+__device__ __forceinline__ u32x4 narrow8(const u32x4& a, const u32x4& b) {
+  return u32x4{narrow_pair(a[0], a[1]), narrow_pair(a[2], a[3]), narrow_pair(b[0], b[1]), narrow_pair(b[2], b[3])};
+}
+// one element at any address
+__device__ __forceinline__ void narrow_one(gsrc_t s, gdst_t d) {
+  uint32_t u;
+  if (((uintptr_t)s & 3u) == 0) {
+    u = ld<4>(s);
+  } else {
+    u = (uint32_t)(uint8_t)s[0] | ((uint32_t)(uint8_t)s[1] << 8) | ((uint32_t)(uint8_t)s[2] << 16) | ((uint32_t)(uint8_t)s[3] << 24);
+  }
+  const uint32_t v = narrow_bf16(u);
+  if (((uintptr_t)d & 1u) == 0) {
+    st<2>(d, (uint16_t)v);
+  } else {
+    d[0] = (char)(v & 0xffu);
+    d[1] = (char)(v >> 8);
+  }
+}
+
+// `nrows` rows of `n` elements; source rows sp bytes apart, destination rows dp bytes apart.  Fast
+// path: groups of eight elements, two 16-byte loads (at any 4-byte aligned address) and one aligned
+// 16-byte store.  One long row is peeled to the destination's next 16-byte boundary first; rows that
+// rule the groups out (odd addresses, a destination pitch or run that breaks the alignment from row to
+// row) go element by element.  No barriers: any group of threads may run it.
+__device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows, uint32_t n,
+                                             int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
+  const bool src4 = (((uintptr_t)s | (nrows > 1 ? (uintptr_t)sp : 0)) & 3u) == 0;
+  if (nrows == 1 && src4 && ((uintptr_t)d & 1u) == 0) {
+    uint32_t head = ((uint32_t)(-(uintptr_t)d) & 15u) >> 1;  // elements before the destination's 16-byte boundary
+    if (head > n) head = n;
+    const uint32_t groups = (n - head) >> 3, done = head + (groups << 3);
+    for (uint32_t i = tid; i < head; i += nt) narrow_one(s + (size_t)i * 4, d + (size_t)i * 2);
+    gsrc_t s2 = s + (size_t)head * 4;
+    gdst_t d2 = d + (size_t)head * 2;
+    uint32_t g = tid;
+    for (; g + nt < groups; g += 2 * nt) {
+      const u32x4 a0 = ld<-16>(s2 + (size_t)g * 32), b0 = ld<-16>(s2 + (size_t)g * 32 + 16);
+      const u32x4 a1 = ld<-16>(s2 + (size_t)(g + nt) * 32), b1 = ld<-16>(s2 + (size_t)(g + nt) * 32 + 16);
+      st<16>(d2 + (size_t)g * 16, narrow8(a0, b0));
+      st<16>(d2 + (size_t)(g + nt) * 16, narrow8(a1, b1));
+    }
+    for (; g < groups; g += nt) {
+      const u32x4 a = ld<-16>(s2 + (size_t)g * 32), b = ld<-16>(s2 + (size_t)g * 32 + 16);
+      st<16>(d2 + (size_t)g * 16, narrow8(a, b));
+    }
+    for (uint32_t i = done + tid; i < n; i += nt) narrow_one(s + (size_t)i * 4, d + (size_t)i * 2);
+    return;
+  }
+  if (nrows > 1 && src4 && (((uintptr_t)d | (uintptr_t)dp) & 15u) == 0 && (n & 7u) == 0) {
+    const uint32_t gpr = n >> 3, total = nrows * gpr;  // groups per row
+    uint32_t row = tid / gpr, col = tid - row * gpr;
+    const uint32_t drow = nt / gpr, dcol = nt - drow * gpr;
+    for (uint32_t i = tid; i < total; i += nt) {
+      gsrc_t sr = s + (int64_t)row * sp + (size_t)col * 32;
+      const u32x4 a = ld<-16>(sr), b = ld<-16>(sr + 16);
+      st<16>(d + (int64_t)row * dp + (size_t)col * 16, narrow8(a, b));
+      col += dcol;
+      row += drow;
+      if (col >= gpr) {
+        col -= gpr;
+        ++row;
+      }
+    }
+    return;
+  }
+  const uint32_t total = nrows * n;
+  for (uint32_t i = tid; i < total; i += nt) {
+    const uint32_t row = nrows == 1 ? 0 : i / n, col = i - row * n;
+    narrow_one(s + (int64_t)row * sp + (size_t)col * 4, d + (int64_t)row * dp + (size_t)col * 2);
+  }
+}
+
 // ---- small tiles ---------------------------------------------------------------------------------
 // A few threads copy a tile of a few hundred bytes: what such a copy costs is memory round trips,
 // not bandwidth.  Every thread therefore issues all loads of a round of kRound items before the
@@ -488,7 +575,9 @@ __device__ __forceinline__ void small_transpose(gsrc_t __restrict__ s, gdst_t __
 // choice of granule mirrors process_tile)
 __device__ __forceinline__ uint32_t small_tile_threads(const TileDesc& T, gsrc_t s, gdst_t d) {
   uint32_t items;
-  if ((T.kind & 0xffu) == kTranspose) {
+  if ((T.kind & 0xffu) == kConvert) {
+    items = max(T.b * (T.a >> 3), 1u);  // groups of eight elements
+  } else if ((T.kind & 0xffu) == kTranspose) {
     const uint32_t e = (T.kind >> 8) & 0xffu;
     const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)T.p0 | (uintptr_t)T.p1;
     items = T.a * T.b * ((al & (e - 1)) == 0 ? 1u : e);
@@ -508,10 +597,14 @@ __device__ __forceinline__ uint32_t small_tile_threads(const TileDesc& T, gsrc_t
 // staging area and barriers) or any group of threads that need not agree on the tile (WG == false,
 // no barriers, nothing assumed uniform across a wave).
 // TR == false: the plan holds no transposed tile that needs the staging area, and the code for
-// them is left out (it would cost the other paths registers).
-template <bool WG, bool TR>
+// them is left out (it would cost the other paths registers).  CV: likewise for converting tiles.
+template <bool WG, bool TR, bool CV>
 __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t d, char* lds, uint32_t tid,
                                              uint32_t nt) {
+  if (CV && (T.kind & 0xffu) == kConvert) {
+    convert_rows(s, d, T.b, T.a, T.p0, T.p1, tid, nt);
+    return;
+  }
   if ((T.kind & 0xffu) == kTranspose) {
     const uint32_t e = (T.kind >> 8) & 0xffu, na = T.a, nb = T.b;
     const uint32_t tda = 1u << ((T.kind >> 16) & 0xffu), tdb = 1u << (T.kind >> 24);
@@ -589,7 +682,7 @@ struct PtrArgs {
 
 // queue[0]: next batch index; queue[1]: workgroups that are done.  The last workgroup to finish
 // puts both back to zero, so the next launch on this plan needs no memset.
-template <bool TR, typename PTRS>
+template <bool TR, bool CV, typename PTRS>
 __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads, uint32_t n_batches,
                                              const TileDesc* __restrict__ tiles, const PTRS& ptr_table,
                                              uint32_t n_src, uint32_t n_ptrs, unsigned long long* queue,
@@ -618,7 +711,7 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
   // thread ranges), and each thread looks up the tile it works for.
   auto run_batch = [&](const TileDesc& H) {
     if (H.count == 1) {
-      process_tile<true, TR>(H, src_of(H), dst_of(H), lds, threadIdx.x, blockDim.x);
+      process_tile<true, TR, CV>(H, src_of(H), dst_of(H), lds, threadIdx.x, blockDim.x);
       return;
     }
     const uint32_t nthr = blockDim.x, tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -657,7 +750,7 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
         }
         const TileDesc T = ldesc[lo];
         const uint32_t t0 = lstart[lo];
-        process_tile<false, TR>(T, src_of(T), dst_of(T), lds, v - t0, lstart[lo + 1] - t0);
+        process_tile<false, TR, CV>(T, src_of(T), dst_of(T), lds, v - t0, lstart[lo + 1] - t0);
       }
       __syncthreads();  // the staging area is written again by the next slice or batch
     }
@@ -706,21 +799,21 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
   }
 }
 
-template <bool TR>
+template <bool TR, bool CV>
 __global__ __launch_bounds__(kMaxThreads) void k_reshard(const TileDesc* __restrict__ heads, uint32_t n_batches,
                                                          const TileDesc* __restrict__ tiles, PtrArgs ptrs,
                                                          uint32_t n_src, uint32_t n_ptrs, unsigned long long* queue,
                                                          int persistent) {
-  reshard_body<TR>(heads, n_batches, tiles, ptrs.p, n_src, n_ptrs, queue, persistent);
+  reshard_body<TR, CV>(heads, n_batches, tiles, ptrs.p, n_src, n_ptrs, queue, persistent);
 }
 
-template <bool TR>
+template <bool TR, bool CV>
 __global__ __launch_bounds__(kMaxThreads) void k_reshard_table(const TileDesc* __restrict__ heads, uint32_t n_batches,
                                                                const TileDesc* __restrict__ tiles,
                                                                const uint64_t* __restrict__ ptr_table, uint32_t n_src,
                                                                uint32_t n_ptrs, unsigned long long* queue,
                                                                int persistent) {
-  reshard_body<TR>(heads, n_batches, tiles, ptr_table, n_src, n_ptrs, queue, persistent);
+  reshard_body<TR, CV>(heads, n_batches, tiles, ptr_table, n_src, n_ptrs, queue, persistent);
 }
 
 // Batches of a source-ordered plan whose key lies in [key_lo, key_hi): the queue starts at the
@@ -742,21 +835,6 @@ __global__ void k_range_lookup(const uint64_t* __restrict__ batch_key, uint32_t 
   queue[1] = 0;
   queue[2] = bound[0];
   queue[3] = bound[1];
-}
-
-__global__ __launch_bounds__(256) void k_copy_baseline(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
-                                                       uint64_t n_vec, uint32_t vec_per_block) {
-  const uint64_t base = (uint64_t)blockIdx.x * vec_per_block;
-  const uint64_t end = min(n_vec, base + vec_per_block);
-  uint64_t i = base + threadIdx.x;
-  for (; i + 3 * 256 < end; i += 4 * 256) {
-    const u32x4 a = src[i], b = src[i + 256], c = src[i + 2 * 256], e = src[i + 3 * 256];
-    dst[i] = a;
-    dst[i + 256] = b;
-    dst[i + 2 * 256] = c;
-    dst[i + 3 * 256] = e;
-  }
-  for (; i < end; i += 256) dst[i] = src[i];
 }
 
 }  // namespace
@@ -801,10 +879,20 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_
     set_error("the plan needs more LDS than a workgroup can have");
     return BCP_ERR_INVALID_ARG;
   }
+  typedef void (*ArgKernel)(const TileDesc*, uint32_t, const TileDesc*, PtrArgs, uint32_t, uint32_t, unsigned long long*, int);
+  typedef void (*TableKernel)(const TileDesc*, uint32_t, const TileDesc*, const uint64_t*, uint32_t, uint32_t,
+                              unsigned long long*, int);
+  // instances by [transposed tiles][converting tiles]
+  static const ArgKernel arg_kernel[2][2] = {{k_reshard<false, false>, k_reshard<false, true>},
+                                             {k_reshard<true, false>, k_reshard<true, true>}};
+  static const TableKernel table_kernel[2][2] = {{k_reshard_table<false, false>, k_reshard_table<false, true>},
+                                                 {k_reshard_table<true, false>, k_reshard_table<true, true>}};
   static const hipError_t lds_attr = [] {
-    const void* fns[] = {reinterpret_cast<const void*>(&k_reshard<false>), reinterpret_cast<const void*>(&k_reshard<true>),
-                         reinterpret_cast<const void*>(&k_reshard_table<false>),
-                         reinterpret_cast<const void*>(&k_reshard_table<true>)};
+    const void* fns[8];
+    for (int i = 0; i < 4; ++i) {
+      fns[i] = reinterpret_cast<const void*>(arg_kernel[i >> 1][i & 1]);
+      fns[4 + i] = reinterpret_cast<const void*>(table_kernel[i >> 1][i & 1]);
+    }
     for (const void* f : fns) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxDynamicLds);
       if (e != hipSuccess) return e;
@@ -812,18 +900,18 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_
     return hipSuccess;
   }();
   BCP_HIP(lds_attr);
-  const bool tr = plan.lds_transpose != 0;
+  const int tr = plan.lds_transpose != 0, cv = plan.converts;
   const dim3 g(grid), b((unsigned)cfg.threads);
   if (!table) {
     PtrArgs args;
     for (int32_t i = 0; i < n_src; ++i) args.p[i] = (uint64_t)(uintptr_t)src[i];
     for (int32_t i = 0; i < n_dst; ++i) args.p[n_src + i] = (uint64_t)(uintptr_t)dst[i];
     for (uint32_t i = n_ptrs; i < (uint32_t)kArgPtrs; ++i) args.p[i] = 0;
-    hipLaunchKernelGGL(tr ? k_reshard<true> : k_reshard<false>, g, b, lds_bytes, stream, plan.heads,
+    hipLaunchKernelGGL(arg_kernel[tr][cv], g, b, lds_bytes, stream, plan.heads,
                        (uint32_t)plan.n_batches, plan.tiles, args, (uint32_t)n_src, n_ptrs, plan.queue,
                        cfg.persistent);
   } else {
-    hipLaunchKernelGGL(tr ? k_reshard_table<true> : k_reshard_table<false>, g, b, lds_bytes, stream, plan.heads,
+    hipLaunchKernelGGL(table_kernel[tr][cv], g, b, lds_bytes, stream, plan.heads,
                        (uint32_t)plan.n_batches, plan.tiles, (const uint64_t*)table, (uint32_t)n_src, n_ptrs,
                        plan.queue, cfg.persistent);
   }
@@ -903,25 +991,6 @@ bcp_status launch_reshard_noalloc(const PlanDevice& plan, const void* const* src
   PlanDevice view = plan;  // same tiles and batches, the queue words of the static array
   view.queue = queue;
   return launch_reshard(view, nullptr, n_src, nullptr, n_dst, table, stream, nullptr);
-}
-
-bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream) {
-  if (nbytes <= 0) return BCP_OK;
-  if ((((uintptr_t)dst | (uintptr_t)src) & 15u) || (nbytes & 15)) {
-    set_error("bcp_copy_baseline needs 16-byte aligned pointers and size");
-    return BCP_ERR_INVALID_ARG;
-  }
-  const uint64_t n_vec = (uint64_t)nbytes / 16;
-  const uint32_t vpb = 65536 / 16;
-  const uint64_t grid = (n_vec + vpb - 1) / vpb;
-  if (grid >= 0x7fffffffull) {
-    set_error("copy too large for one launch");
-    return BCP_ERR_INVALID_ARG;
-  }
-  hipLaunchKernelGGL(k_copy_baseline, dim3((unsigned)grid), dim3(256), 0, stream, (u32x4*)dst, (const u32x4*)src,
-                     n_vec, vpb);
-  BCP_HIP(hipGetLastError());
-  return BCP_OK;
 }
 
 }  // namespace bcp

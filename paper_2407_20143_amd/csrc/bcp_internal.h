@@ -4,9 +4,12 @@
 #include <stdint.h>
 
 #include <string>
+#include <vector>
 
 #include "bcp.h"
 #include "bcp_decompose.h"
+#include "bcp_host.h"
+#include "bcp_validate.h"
 
 namespace bcp {
 
@@ -25,11 +28,13 @@ struct Box {
   int32_t buf;
 };
 
-enum RegionKind : int32_t { kRows = 0, kTranspose = 1 };
+enum RegionKind : int32_t { kRows = 0, kTranspose = 1, kConvert = 2 };
 
 // One copy region: `len[0..ndim)` rows (slowest first) of `run_bytes` contiguous bytes.
 // kTranspose: run_bytes == itemsize, len[ndim-2] runs along the source-contiguous dimension
 // (src pitch == itemsize) and len[ndim-1] along the destination-contiguous one.
+// kConvert: rows of 4-byte source elements that arrive as 2-byte elements (binary32 -> bfloat16);
+// run_bytes counts SOURCE bytes, the destination run is half as long; pitches are bytes of their side.
 struct Region {
   int64_t src_base, dst_base;
   int64_t run_bytes;
@@ -59,6 +64,7 @@ struct Region {
 //   kRows:      `b` rows of `a` contiguous bytes, row pitches p0 (source) / p1 (destination)
 //   kTranspose: `a` x `b` elements of `esize` bytes; the source is contiguous along a with pitch
 //               p0 along b, the destination contiguous along b with pitch p1 along a
+//   kConvert:   `b` rows of `a` ELEMENTS (4 bytes in the source, 2 in the destination), pitches in bytes
 //
 // The queue of the copy kernel hands out BATCHES: one big tile, or a run of consecutive small
 // tiles (each below kSmallTileBytes, together about one tile budget) that the threads of a
@@ -93,17 +99,8 @@ struct Ctl {
   unsigned long long dims_hist[kDims + 1];
   unsigned long long max_src_end;  // one past the highest source byte offset any region reads
   unsigned long long lds_transpose;  // LDS staging bytes the largest transposed tile needs
-};
-
-// device error codes carried in err_key's low byte (mapped to bcp_status on the host)
-enum DevErr : unsigned {
-  kErrInvalid = 1,
-  kErrTooManyDims = 2,
-  kErrBounds = 3,
-  kErrShape = 4,
-  kErrDtype = 5,
-  kErrOverlap = 6,
-  kErrUncovered = 7,
+  unsigned long long src_bytes;      // bytes the copy reads (differs from payload_bytes when regions convert)
+  unsigned long long n_convert;      // regions that convert
 };
 
 struct PlanConfig {
@@ -114,7 +111,6 @@ struct PlanConfig {
 };
 PlanConfig config();  // a snapshot of the process-wide setting
 
-void set_error(const std::string& msg);
 bcp_status hip_fail(hipError_t e, const char* what);
 
 #define BCP_HIP(expr)                                   \
@@ -134,6 +130,7 @@ struct PlanDevice {
   int64_t n_tiles = 0;
   int64_t n_batches = 0;
   uint32_t lds_transpose = 0;  // LDS staging bytes of the largest transposed tile (0: none)
+  bool converts = false;       // some tiles narrow binary32 to bfloat16
   size_t regions_bytes = 0, desc_bytes = 0;  // sizes of the two allocations (regions; heads | tiles | queue | keys)
 };
 
@@ -151,6 +148,7 @@ int64_t block_pool_release();
 struct PlannerResult {
   PlanDevice dev;
   Ctl ctl;
+  std::vector<int64_t> src_extent, dst_extent;  // per buffer: one past the highest byte the plan touches
   int64_t n_saved_boxes = 0, n_target_boxes = 0;
   float device_ms = 0.f;
 };
@@ -176,7 +174,6 @@ bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_
 // bcp_reshard_noalloc: pointer table and queue words in a static device array, no allocation
 bcp_status launch_reshard_noalloc(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
                                   int32_t n_dst, hipStream_t stream);
-bcp_status launch_copy_baseline(void* dst, const void* src, int64_t nbytes, hipStream_t stream);
 int device_cu_count();
 
 }  // namespace bcp

@@ -140,7 +140,8 @@ struct Workspace {
   std::vector<Chunk> chunks;
   std::mutex mu;
   int device = -1;
-  void* landing = nullptr;  // pinned host memory the planner's read-backs arrive in (kLandingBytes)
+  void* landing = nullptr;  // pinned host memory the planner's read-backs arrive in
+  size_t landing_bytes = 0;
   hipEvent_t ev[2] = {nullptr, nullptr};  // bracket the planner's device work (reused from plan to plan)
 
   void reset(int dev) {
@@ -196,6 +197,7 @@ bcp_status release_workspace(int64_t* freed_bytes) {
     const hipError_t e = hipHostFree(g_ws.landing);
     if (first == hipSuccess) first = e;
     g_ws.landing = nullptr;
+    g_ws.landing_bytes = 0;
   }
   for (hipEvent_t& e : g_ws.ev)
     if (e) {
@@ -235,52 +237,6 @@ bcp_status device_scan(const Tin* in, T* out, int64_t n, Workspace& ws, hipStrea
 // ---- step 1: validate, count and emit boxes --------------------------------------------------
 __device__ inline void report(Ctl* ctl, int64_t record, unsigned code) {
   atomicMin(&ctl->err_key, ((ull)record << 8) | code);
-}
-
-__device__ inline unsigned validate_record(const bcp_shard_meta& r) {
-  if (r.ndim < 0) return kErrInvalid;
-  if (r.ndim > kDims) return kErrTooManyDims;
-  const int e = r.itemsize;
-  if (!(e == 1 || e == 2 || e == 4 || e == 8 || e == 16)) return kErrInvalid;
-  if (r.fqn_id < 0 || r.buf < 0 || r.byte_offset < 0 || r.reserved != 0) return kErrInvalid;
-  int64_t vol = 1;
-  bool strided = false;
-  for (int k = 0; k < r.ndim; ++k) {
-    if (r.global_shape[k] < 0 || r.offsets[k] < 0 || r.lengths[k] < 0 || r.strides[k] < 0) return kErrInvalid;
-    if (r.offsets[k] > r.global_shape[k] || r.lengths[k] > r.global_shape[k] - r.offsets[k]) return kErrBounds;
-    if (r.lengths[k] != 0 && vol > (int64_t)(0x3fffffffffffffffLL / r.lengths[k])) return kErrInvalid;
-    vol *= r.lengths[k];
-    strided |= r.strides[k] != 0;
-  }
-  if (r.flat_begin < 0 || r.flat_end < r.flat_begin) return kErrInvalid;
-  if (r.flat_end > vol) return kErrBounds;
-  // byte addresses inside the buffer must stay far from the 64-bit limit: at most 2^56 elements of
-  // storage behind byte_offset < 2^60
-  constexpr int64_t kMaxSpan = (int64_t)1 << 56;
-  if (r.byte_offset >= ((int64_t)1 << 60)) return kErrInvalid;
-  if (strided) {
-    if (!(r.flat_begin == 0 && r.flat_end == vol)) return kErrInvalid;  // flat shards are packed
-    int64_t span = 0;  // element offset of the last element
-    for (int k = 0; k < r.ndim; ++k) {
-      if (r.lengths[k] > 1 && r.strides[k] == 0) return kErrInvalid;
-      if (r.lengths[k] > 1) {
-        if (r.strides[k] > (kMaxSpan - span) / (r.lengths[k] - 1)) return kErrInvalid;
-        span += (r.lengths[k] - 1) * r.strides[k];
-      }
-    }
-  } else if (vol > kMaxSpan) {
-    return kErrInvalid;
-  }
-  return 0;
-}
-
-__device__ inline int local_shape(const bcp_shard_meta& r, int64_t* len) {
-  if (r.ndim == 0) {
-    len[0] = 1;
-    return 1;
-  }
-  for (int k = 0; k < r.ndim; ++k) len[k] = r.lengths[k];
-  return r.ndim;
 }
 
 __global__ __launch_bounds__(kBlock) void k_validate_count(const bcp_shard_meta* recs, int64_t n_saved,
@@ -423,17 +379,9 @@ __device__ inline int64_t upper_bound_u64(const uint64_t* a, int64_t n, uint64_t
   return lo;
 }
 
-__device__ inline unsigned same_tensor(const bcp_shard_meta& a, const bcp_shard_meta& b) {
-  if (a.ndim != b.ndim) return kErrShape;
-  for (int k = 0; k < a.ndim; ++k)
-    if (a.global_shape[k] != b.global_shape[k]) return kErrShape;
-  if (a.itemsize != b.itemsize) return kErrDtype;
-  return 0;
-}
-
 __global__ __launch_bounds__(kBlock) void k_pair_count(const Box* boxes, int64_t nbs, int64_t nbt,
                                                        const uint64_t* skeys, const uint32_t* sidx,
-                                                       const bcp_shard_meta* recs, int64_t n_saved,
+                                                       const bcp_shard_meta* recs, int64_t n_saved, int convert,
                                                        uint32_t* grp_lo, uint64_t* pair_cnt, Ctl* ctl) {
   const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (t >= nbt) return;
@@ -444,7 +392,7 @@ __global__ __launch_bounds__(kBlock) void k_pair_count(const Box* boxes, int64_t
   pair_cnt[t] = (uint64_t)(hi - lo);
   if (hi > lo) {
     const Box& sb = boxes[sidx[lo]];
-    const unsigned code = same_tensor(recs[sb.rec], recs[n_saved + tb.rec]);
+    const unsigned code = same_tensor(recs[sb.rec], recs[n_saved + tb.rec], convert != 0);
     if (code) report(ctl, n_saved + tb.rec, code);
   }
 }
@@ -489,7 +437,10 @@ __global__ __launch_bounds__(kBlock) void k_saved_check(const Box* boxes, int64_
 __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_bytes, Region* R, int64_t* volume) {
   const int n = t.ndim;
   if (s.ndim != n) return false;  // reported as a shape mismatch elsewhere
-  const int64_t e = t.itemsize;
+  // element sizes of the two sides: they differ only for a converting pair (checked when the pairs
+  // were counted), which moves 4-byte source elements into 2-byte destination elements
+  const int64_t e = s.itemsize, et = t.itemsize;
+  const bool conv = e != et;
   int64_t L[kDims], ss[kDims], ds[kDims];
   int m = 0;
   int64_t soff = 0, doff = 0, vol = 1;
@@ -517,7 +468,7 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   if (!R) return true;
   *volume = vol;
   R->src_base = s.byte_base + soff * e;
-  R->dst_base = t.byte_base + doff * e;
+  R->dst_base = t.byte_base + doff * et;
   R->src_buf = s.buf;
   R->dst_buf = t.buf;
   R->srec = s.rec;
@@ -541,7 +492,7 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
       if (ds[k] == 1) b = k;
     }
   }
-  if (a >= 0 && b >= 0 && a != b && L[a] >= 4 && L[b] >= 4) {
+  if (!conv && a >= 0 && b >= 0 && a != b && L[a] >= 4 && L[b] >= 4) {
     // source-contiguous and destination-contiguous dimensions differ: LDS-staged transpose
     R->kind = kTranspose;
     R->run_bytes = e;
@@ -570,10 +521,10 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
     R->tiles_b = (uint32_t)(tb < 0xffffffffull ? tb : 0xffffffffull);
     const uint64_t tpg = ta * tb;
     R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
-    R->n_tiles = (tpg >> 32) ? ~0ull : groups * tpg;
+    R->n_tiles = (tpg >> 32 || groups >> 31) ? ~0ull : groups * tpg;
     return true;
   }
-  R->kind = kRows;
+  R->kind = conv ? kConvert : kRows;
   int nd;
   if (m > 0 && ss[m - 1] == 1 && ds[m - 1] == 1) {
     R->run_bytes = L[m - 1] * e;
@@ -585,7 +536,7 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   for (int k = 0; k < nd; ++k) {
     R->len[k] = L[k];
     R->spitch[k] = ss[k] * e;
-    R->dpitch[k] = ds[k] * e;
+    R->dpitch[k] = ds[k] * et;
   }
   R->ndim = nd;
   const uint64_t L0 = nd > 0 ? (uint64_t)L[nd - 1] : 1;
@@ -601,9 +552,10 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
     uint64_t misal = (uint64_t)R->dst_base;
     for (int k = 0; k < nd; ++k) misal |= (uint64_t)R->dpitch[k];
     R->lead_mod = (misal % kSegmentAlign) ? kSegmentAlign : 0;
-    const uint64_t segs = ((uint64_t)R->run_bytes + (R->lead_mod ? kSegmentAlign - 1 : 0) + tile_bytes - 1) / tile_bytes;
+    // (the lead-in is counted in source bytes: e / et of them per destination byte)
+    const uint64_t segs = ((uint64_t)R->run_bytes + (R->lead_mod ? kSegmentAlign * (uint64_t)(e / et) - 1 : 0) + tile_bytes - 1) / tile_bytes;
     R->segs_per_row = (uint32_t)(segs < 0xffffffffull ? segs : 0xffffffffull);
-    tpg = (segs >> 32) ? ~0ull : L0 * segs;
+    tpg = (segs >> 32 || L0 >> 31) ? ~0ull : L0 * segs;
   } else {
     uint64_t rpt = tile_bytes / (uint64_t)R->run_bytes;
     if (rpt > L0) rpt = L0;
@@ -611,14 +563,14 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
     tpg = (L0 + rpt - 1) / rpt;
   }
   R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
-  R->n_tiles = (tpg >> 32) ? ~0ull : groups * tpg;
+  R->n_tiles = (tpg >> 32 || groups >> 31) ? ~0ull : groups * tpg;
   return true;
 }
 
 // plan statistics are summed per workgroup in LDS first: one global atomic per counter and
 // workgroup instead of one per region
 struct BlockStats {
-  ull payload, transposed, dims[kDims + 1], src_end, lds_transpose;
+  ull payload, src_bytes, converted, transposed, dims[kDims + 1], src_end, lds_transpose;
   long long max_src, max_dst;
 };
 
@@ -637,7 +589,7 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
   // (a 280-byte struct stored by each thread on its own is 18 partial-line stores per region)
   __shared__ __attribute__((aligned(16))) char stage[WRITE ? kBlock * sizeof(Region) : 16];
   if (WRITE && threadIdx.x == 0) {
-    bs.payload = bs.transposed = 0;
+    bs.payload = bs.src_bytes = bs.converted = bs.transposed = 0;
     for (int k = 0; k <= kDims; ++k) bs.dims[k] = 0;
     bs.max_src = bs.max_dst = -1;
     bs.src_end = 0;
@@ -677,7 +629,9 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
     tile_cnt[pos] = R.n_tiles;
     atomicAdd(&cov[tb->rec], (ull)vol);
     atomicAdd(&bs.payload, (ull)vol * (ull)tb->itemsize);
-    atomicAdd(&bs.dims[R.ndim + (R.kind == kRows && R.run_bytes > tb->itemsize ? 1 : 0)], 1ull);
+    atomicAdd(&bs.src_bytes, (ull)vol * (ull)sb->itemsize);
+    if (R.kind == kConvert) atomicAdd(&bs.converted, 1ull);
+    atomicAdd(&bs.dims[R.ndim + (R.kind != kTranspose && R.run_bytes > sb->itemsize ? 1 : 0)], 1ull);
     if (R.kind == kTranspose) {
       atomicAdd(&bs.transposed, 1ull);
       atomicMax(&bs.lds_transpose, (ull)transpose_lds_bytes(R.tdim_a, R.tdim_b, (uint32_t)R.run_bytes));
@@ -701,6 +655,8 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
   }
   if (threadIdx.x == 0 && (wcnt[0] | wcnt[1] | wcnt[2] | wcnt[3])) {
     atomicAdd(&ctl->payload_bytes, bs.payload);
+    atomicAdd(&ctl->src_bytes, bs.src_bytes);
+    if (bs.converted) atomicAdd(&ctl->n_convert, bs.converted);
     if (bs.transposed) {
       atomicAdd(&ctl->n_transposed, bs.transposed);
       atomicMax(&ctl->lds_transpose, bs.lds_transpose);
@@ -777,25 +733,28 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
       const uint32_t row = w / R.segs_per_row, seg = w - row * R.segs_per_row;
       so += (int64_t)row * sp;
       dof += (int64_t)row * dp;
-      const int64_t lead = R.lead_mod ? dof % (int64_t)R.lead_mod : 0;
-      int64_t begin = (int64_t)seg * R.tile_bytes - lead, end = begin + (int64_t)R.tile_bytes;
+      // segments are counted in source bytes; a converting region writes half as many
+      const int64_t ratio = R.kind == kConvert ? 2 : 1;
+      int64_t lead = R.lead_mod ? dof % (int64_t)R.lead_mod : 0;
+      if (ratio > 1) lead &= ~(int64_t)1;  // whole destination elements
+      int64_t begin = (int64_t)seg * R.tile_bytes - lead * ratio, end = begin + (int64_t)R.tile_bytes;
       if (begin < 0) begin = 0;
       if (end > R.run_bytes) end = R.run_bytes;
-      if (end < begin) end = begin;  // the spare segment of a row that did not need it
+      if (begin > end) begin = end;  // the spare segment of a row that did not need it: empty, at the row's end
       so += begin;
-      dof += begin;
-      t.a = (uint32_t)(end - begin);
+      dof += begin / ratio;
+      t.a = (uint32_t)((end - begin) / (R.kind == kConvert ? 4 : 1));
       t.b = 1;
     } else {  // a few whole short rows
       const uint64_t L0 = nd >= 1 ? (uint64_t)R.len[nd - 1] : 1;
       const uint64_t row0 = (uint64_t)w * R.rows_per_tile;
       const uint64_t left = L0 - row0;
       t.b = (uint32_t)(left < R.rows_per_tile ? left : R.rows_per_tile);
-      t.a = (uint32_t)R.run_bytes;
+      t.a = (uint32_t)(R.run_bytes / (R.kind == kConvert ? 4 : 1));
       so += (int64_t)row0 * sp;
       dof += (int64_t)row0 * dp;
     }
-    bytes = (uint64_t)t.a * t.b;
+    bytes = (uint64_t)t.a * t.b * (R.kind == kConvert ? 4u : 1u);  // source bytes
   }
   t.src_off = so;
   t.dst_off = dof;
@@ -826,7 +785,10 @@ __global__ __launch_bounds__(kBlock) void k_tile_weights(const uint64_t* tile_st
       const uint64_t e = (t.kind >> 8) & 0xffu;
       last += (uint64_t)(t.a ? t.a - 1 : 0) * e + (uint64_t)(t.b ? t.b - 1 : 0) * (uint64_t)t.p0 + (e ? e - 1 : 0);
     } else if (bytes) {
-      last += (uint64_t)(t.b - 1) * (uint64_t)t.p0 + t.a - 1;
+      last += (uint64_t)(t.b - 1) * (uint64_t)t.p0 + (uint64_t)t.a * ((t.kind & 0xffu) == kConvert ? 4u : 1u) - 1;
+    } else if (last) {
+      --last;  // an empty tile (the spare segment of a long row) sits one past its row's last byte: it is keyed
+               // to that byte, so that its batch's key never points beyond the bytes the plan reads
     }
     key[i] = ((uint64_t)t.src_buf << kKeyShift) | last;
     order[i] = (uint32_t)i;
@@ -901,24 +863,28 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const Region* regions, co
   }
 }
 
+// Per buffer, one past the highest byte the plan touches: ext[0 .. n_src) for the source blobs,
+// ext[n_src ..) for the destination buffers (zeroed before).
+__global__ __launch_bounds__(kBlock) void k_extents(const Region* __restrict__ regions, int64_t n_regions, uint32_t n_src,
+                                                    ull* ext) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_regions) return;
+  const Region& R = regions[i];
+  int64_t s_end = R.src_base + R.run_bytes, d_end = R.dst_base + (R.kind == kConvert ? R.run_bytes / 2 : R.run_bytes);
+  for (int k = 0; k < R.ndim; ++k) {
+    s_end += (R.len[k] - 1) * R.spitch[k];
+    d_end += (R.len[k] - 1) * R.dpitch[k];
+  }
+  atomicMax(&ext[R.src_buf], (ull)s_end);
+  atomicMax(&ext[n_src + R.dst_buf], (ull)d_end);
+}
+
 bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
   if (ctl.err_key == ~0ull) return BCP_OK;
   const unsigned code = (unsigned)(ctl.err_key & 0xff);
   const int64_t rec = (int64_t)(ctl.err_key >> 8);
   const bool is_saved = rec < n_saved;
-  const std::string who = std::string(is_saved ? "saved" : "target") + " record " +
-                          std::to_string(is_saved ? rec : rec - n_saved);
-  switch (code) {
-    case kErrInvalid: set_error(who + ": invalid field (ndim, itemsize, fqn_id, buf, offsets, flat range or strides)"); return BCP_ERR_INVALID_ARG;
-    case kErrTooManyDims: set_error(who + ": ndim exceeds BCP_MAX_DIMS"); return BCP_ERR_TOO_MANY_DIMS;
-    case kErrBounds: set_error(who + ": box or flat range outside the tensor"); return BCP_ERR_OUT_OF_BOUNDS;
-    case kErrShape: set_error(who + ": ndim / global shape differs from other records of its FQN"); return BCP_ERR_SHAPE_MISMATCH;
-    case kErrDtype: set_error(who + ": itemsize differs from other records of its FQN"); return BCP_ERR_DTYPE_MISMATCH;
-    case kErrOverlap: set_error(who + ": saved shards overlap (an element has two savers)"); return BCP_ERR_SAVED_OVERLAP;
-    case kErrUncovered: set_error(who + ": no saved shard holds some of its elements"); return BCP_ERR_UNCOVERED;
-  }
-  set_error("unknown device error");
-  return BCP_ERR_INVALID_ARG;
+  return record_error(code, is_saved, is_saved ? rec : rec - n_saved);
 }
 
 // device memory a plan keeps; freed here on any early return
@@ -1028,8 +994,21 @@ struct Readback {
   Ctl ctl;
   uint64_t v[3];
 };
-constexpr size_t kLandingBytes = 4096;
+constexpr size_t kLandingBytes = 4096;  // at least; grows when a plan has many buffers (their extents land here)
+constexpr size_t kLandingExtents = 64;  // offset of the per-buffer extents in the final read-back
 static_assert(sizeof(Readback) <= kLandingBytes, "landing buffer");
+
+// grow-only; the caller has made sure no copy into the old block is in flight
+hipError_t ensure_landing(Workspace& ws, size_t bytes) {
+  bytes = std::max(bytes, kLandingBytes);
+  if (ws.landing && ws.landing_bytes >= bytes) return hipSuccess;
+  if (ws.landing) (void)hipHostFree(ws.landing);
+  ws.landing = nullptr;
+  ws.landing_bytes = 0;
+  const hipError_t e = hipHostMalloc(&ws.landing, bytes, hipHostMallocDefault);
+  if (e == hipSuccess) ws.landing_bytes = bytes;
+  return e;
+}
 
 __global__ void k_readback(const Ctl* ctl, const void* p0, int w0, const void* p1, int w1, const void* p2, int w2,
                            Readback* out) {
@@ -1067,10 +1046,12 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   init.max_src_buf = init.max_dst_buf = -1;
   out->ctl = init;
   if (n_target == 0) return BCP_OK;
-  if (n_total >= (int64_t)1 << 31) {
+  if (n_total > (int64_t)(0xffffffffu / kMaxBoxesPerRecord)) {  // box indices are 32-bit
     set_error("too many records");
     return BCP_ERR_INVALID_ARG;
   }
+  out->src_extent.clear();
+  out->dst_extent.clear();
   int dev = 0;
   BCP_HIP(hipGetDevice(&dev));
   std::lock_guard<std::mutex> ws_lock(g_ws.mu);
@@ -1083,7 +1064,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     if (!e) BCP_HIP(hipEventCreate(&e));
   const hipEvent_t ev0 = ws.ev[0], ev1 = ws.ev[1];
 
-  if (!ws.landing) BCP_HIP(hipHostMalloc(&ws.landing, kLandingBytes, hipHostMallocDefault));
+  BCP_HIP(ensure_landing(ws, kLandingBytes));
   bcp_shard_meta* recs = nullptr;
   Ctl* ctl = nullptr;
   Readback* rb_dev = nullptr;
@@ -1155,7 +1136,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   BCP_HIP(ws.alloc(&pair_start, (size_t)nbt + 1));
   BCP_HIP(ws.alloc(&cov, (size_t)n_target));
   BCP_HIP(hipMemsetAsync(cov, 0, sizeof(ull) * (size_t)n_target, st));
-  hipLaunchKernelGGL(k_pair_count, dim3(blocks_for(nbt)), dim3(kBlock), 0, st, boxes, nbs, nbt, keys_a, idx_a, recs, n_saved, grp_lo, pair_start, ctl);
+  hipLaunchKernelGGL(k_pair_count, dim3(blocks_for(nbt)), dim3(kBlock), 0, st, boxes, nbs, nbt, keys_a, idx_a, recs, n_saved,
+                     (flags & BCP_CONVERT_F32_TO_BF16) ? 1 : 0, grp_lo, pair_start, ctl);
   BCP_HIP(hipGetLastError());
   if (bcp_status s = device_scan<uint64_t, uint64_t>(pair_start, pair_start, nbt, ws, st)) return s;
   if (nbs > 0) {
@@ -1167,7 +1149,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   h = rb.ctl;
   const uint64_t n_pairs = rb.v[0];
   if (bcp_status s = device_error(h, n_saved)) return s;
-  if (n_pairs >= (1ull << 31) * kBlock) {
+  if (n_pairs >= 0xffffffffull) {  // region indices are 32-bit
     set_error("too many candidate pairs");
     return BCP_ERR_OOM;
   }
@@ -1254,8 +1236,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       BCP_HIP(hipGetLastError());
       if (by_source) {
         // sort the tiles by (source buffer, last source byte): the plan can then run as blobs arrive
-        if (h.max_src_end >> kKeyShift) {
-          set_error("BCP_ORDER_BY_SOURCE: source offsets beyond 2^44 bytes");
+        if ((h.max_src_end >> kKeyShift) || h.max_src_buf >= ((long long)1 << (64 - kKeyShift))) {
+          set_error("BCP_ORDER_BY_SOURCE: source offsets beyond 2^44 bytes or more than 2^20 source blobs");
           return BCP_ERR_INVALID_ARG;
         }
         uint64_t *key_b = nullptr, *w2 = nullptr;
@@ -1297,11 +1279,28 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, regions, tile_region, tile_local, weight,
                          bflags, bstart, n_tiles, tiles, heads, key, out->dev.batch_key);
       BCP_HIP(hipGetLastError());
+      // what each buffer must hold: one past the highest byte touched, per source blob and destination buffer
+      const size_t n_src = (size_t)(h.max_src_buf + 1), n_dst = (size_t)(h.max_dst_buf + 1);
+      ull* ext = nullptr;
+      BCP_HIP(ws.alloc(&ext, n_src + n_dst));
+      BCP_HIP(hipMemsetAsync(ext, 0, sizeof(ull) * (n_src + n_dst), st));
+      hipLaunchKernelGGL(k_extents, dim3(blocks_for(n_regions)), dim3(kBlock), 0, st, regions, (int64_t)n_regions,
+                         (uint32_t)n_src, ext);
+      BCP_HIP(hipGetLastError());
+      BCP_HIP(ensure_landing(ws, kLandingExtents + sizeof(ull) * (n_src + n_dst)));  // (nothing is in flight into it)
       BCP_HIP(hipMemcpyAsync(ws.landing, bflags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+      BCP_HIP(hipMemcpyAsync((char*)ws.landing + kLandingExtents, ext, sizeof(ull) * (n_src + n_dst), hipMemcpyDeviceToHost, st));
+      out->src_extent.resize(n_src);
+      out->dst_extent.resize(n_dst);
     }
     BCP_HIP(hipEventRecord(ev1, st));
     BCP_HIP(hipStreamSynchronize(st));                                                 // (final sync)
-    if (n_tiles > 0) std::memcpy(&n_batches, ws.landing, sizeof(uint32_t));
+    if (n_tiles > 0) {
+      std::memcpy(&n_batches, ws.landing, sizeof(uint32_t));
+      const char* e = (const char*)ws.landing + kLandingExtents;
+      std::memcpy(out->src_extent.data(), e, sizeof(int64_t) * out->src_extent.size());
+      std::memcpy(out->dst_extent.data(), e + sizeof(int64_t) * out->src_extent.size(), sizeof(int64_t) * out->dst_extent.size());
+    }
     BCP_HIP(hipEventElapsedTime(&out->device_ms, ev0, ev1));
     h.n_tiles = n_tiles;
     out->dev.tiles = tiles;
@@ -1309,6 +1308,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     out->dev.n_tiles = (int64_t)n_tiles;
     out->dev.n_batches = (int64_t)n_batches;
     out->dev.lds_transpose = (uint32_t)h.lds_transpose;
+    out->dev.converts = h.n_convert != 0;
   } else {
     hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
                        (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);

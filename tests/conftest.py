@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "needs_full_lib: calls an entry point outside the host-only part of the library "
+                                       "(left out when the tests run against a sanitizer build of that part)")
 
 
 def read_golden(name):

@@ -29,7 +29,7 @@ def reshard_on_gpu(case):
     src = synth.materialize(case.saved, case.tensors, case.seed, device="cuda")
     dst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
     sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
-    p = binding.plan(sm, tm)
+    p = binding.plan(sm, tm, flags=binding.BCP_CONVERT_F32_TO_BF16 if case.convert else 0)
     binding.reshard(p, src, dst)
     torch.cuda.synchronize()
     st = p.stats()
@@ -58,7 +58,7 @@ def check_oracle_sample(case, src, dst, sm, tm, fqns):
         n = int(r["flat_end"] - r["flat_begin"]) * int(r["itemsize"])
         o, b = int(r["byte_offset"]), int(r["buf"])
         src_host[b][o:o + n] = src[b][o:o + n].cpu().numpy()
-    oracle.reshard(case.saved, case.target, src_host, dst_inplace=dst_host, only_fqns=list(fq))
+    oracle.reshard(case.saved, case.target, src_host, dst_inplace=dst_host, only_fqns=list(fq), convert=case.convert)
     checked = 0
     for r in tm[np.isin(tm["fqn_id"], fq)]:
         n = int(r["flat_end"] - r["flat_begin"]) * int(r["itemsize"])
@@ -230,3 +230,55 @@ def test_cfg5_small_tensors_full_against_the_whole_oracle():
     for b, w in enumerate(want):
         assert np.array_equal(dst[b].cpu().numpy(), w), f"cfg5 small tensors: buffer {b} differs from the oracle"
     p.destroy()
+
+
+def test_cfg5_whole_as_one_plan():
+    """Configuration 5 as the ONE plan it is: the stacked expert tensors and the 100 000 small tensors together.
+    Experts against the closed form on the device, small tensors against the whole oracle, counts asserted."""
+    case = synth.cfg5()
+    experts = {f for f, s in case.tensors.items() if "experts" in s.name}
+    assert len(experts) == 48 and len(case.tensors) == 100_048
+    e_saved = synth.Layout([sh for sh in case.saved.shards if sh.parts[0].fqn in experts], case.saved.buf_bytes)
+    s_saved = synth.Layout([sh for sh in case.saved.shards if sh.parts[0].fqn not in experts], case.saved.buf_bytes)
+    e_target = synth.Layout([sh for sh in case.target.shards if sh.parts[0].fqn in experts], case.target.buf_bytes)
+    s_target = synth.Layout([sh for sh in case.target.shards if sh.parts[0].fqn not in experts], case.target.buf_bytes)
+    e_bufs = sorted({sh.buf for sh in e_saved.shards})
+    # small tensors are generated on the host (100k tiny tensors one by one on the GPU take minutes), experts on the GPU
+    small_src = synth.materialize(s_saved, case.tensors, case.seed)
+    src = synth.materialize(e_saved, case.tensors, case.seed, device="cuda", only_bufs=set(e_bufs))
+    for b in range(len(src)):
+        if src[b] is None:
+            src[b] = small_src[b].cuda()
+    assert not (set(e_bufs) & {sh.buf for sh in s_saved.shards})   # experts and small tensors live in separate blobs
+    dst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
+    p = binding.plan(sm, tm)
+    binding.reshard(p, src, dst)
+    torch.cuda.synchronize()
+    st = p.stats()
+    assert st["payload_bytes"] == case.target.payload_bytes()
+    assert st["n_saved_boxes"] + st["n_target_boxes"] > 1_000_000 and st["n_regions"] > 48 * 32
+    p.destroy()
+    et_bufs = sorted({sh.buf for sh in e_target.shards})
+    for b in et_bufs:
+        want = synth.materialize(e_target, case.tensors, case.seed, device="cuda", poison=POISON, only_bufs={b})
+        assert torch.equal(dst[b], want[b]), f"cfg5: expert buffer {b} differs from the closed form"
+        del want
+    want = oracle.reshard(s_saved, s_target, small_src, poison=POISON)
+    for b in sorted({sh.buf for sh in s_target.shards}):
+        assert np.array_equal(dst[b].cpu().numpy(), want[b]), f"cfg5: small-tensor buffer {b} differs from the oracle"
+    check_oracle_sample(case, src, dst, sm, tm, fqns_by_name(case, {"layers.3.experts.up"}))
+
+
+@pytest.mark.parametrize("zero_saved", [False, True])
+def test_eval_load_full_fp32_master_as_bf16(zero_saved):
+    """The dtype-converting load at full size: the 7B fp32 master weights (27 GB), saved TP4 PP2 or as ZeRO flat
+    slices, loaded as bf16 under TP2 PP4."""
+    case = synth.eval_load_case(zero_saved=zero_saved)
+    src, dst, sm, tm, st = reshard_on_gpu(case)
+    assert st["src_bytes"] == 2 * st["payload_bytes"] == 4 * 6_738_415_616 + 4 * 65 * 4096   # (norms go to both TP ranks)
+    check_closed_form(case, dst, [[b] for b in range(len(dst))])
+    sample = fqns_by_name(case, {"embed.weight.master", "layers.0.ln1.weight.master", "layers.11.attn.o.weight.master",
+                                 "layers.31.mlp.down.weight.master"})
+    assert len(sample) == 4
+    check_oracle_sample(case, src, dst, sm, tm, sample)

@@ -22,6 +22,8 @@ def _default_config():
 
 
 def gpu_reshard(case: Case, src_cpu, flags=0, dst_init=None):
+    if case.convert:
+        flags |= binding.BCP_CONVERT_F32_TO_BF16
     sm, tm = binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target)
     p = binding.plan(sm, tm, flags=flags)
     dsrc = [b.cuda() for b in src_cpu]
@@ -44,7 +46,7 @@ def assert_same(got, want, what):
 
 def check_case(case: Case, also_closed_form=True):
     src = synth.materialize(case.saved, case.tensors, case.seed)
-    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON, convert=case.convert)
     got, p = gpu_reshard(case, src)
     assert_same(got, want, case.name + " vs oracle")
     if also_closed_form:
@@ -52,8 +54,105 @@ def check_case(case: Case, also_closed_form=True):
         assert_same(got, exp, case.name + " vs library slicing")
     st = p.stats()
     assert st["payload_bytes"] == case.target.payload_bytes()
+    # bytes read: every target element at its SAVED element size
+    assert st["src_bytes"] == sum(sh.numel * case.tensors[sh.parts[0].fqn].dtype.itemsize for sh in case.target.shards if sh.parts)
     p.destroy()
     return st
+
+
+# ---- dtype-converting load: fp32 saved, bf16 asked for (Sec. 2.2, evaluation jobs) -------------------
+@pytest.mark.parametrize("modes", [("grid", "grid"), ("grid", "flat"), ("flat", "grid"), ("flat", "flat")])
+@pytest.mark.parametrize("seed", range(6))
+def test_convert_random_layouts(seed, modes):
+    """Arbitrary fp32 bit patterns (NaN payloads, infinities, subnormals, ties), every alignment class,
+    strided shards on either side: bit-exact against the oracle's IEEE narrowing."""
+    case = synth.random_case(300 + seed, n_tensors=6, max_elems=40000, saved_mode=modes[0], target_mode=modes[1],
+                             dtype=torch.float32, p_strided=0.3 if "grid" in modes else 0.0, narrow_target=True)
+    check_case(case, also_closed_form=False)   # (the library cast differs on NaN payloads; the oracle is the reference)
+
+
+def test_convert_every_upper_half_and_the_rounding_edges():
+    """One tensor holding every upper half with the lower halves around the rounding decision."""
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    bits = ((np.arange(1 << 16, dtype=np.uint32) << 16)[None, :] | lows[:, None]).reshape(-1)
+    n = bits.size
+    part = Part(0, (n,), (0,), (n,))
+    saved, target = Layout([regular(part, 4, 0, 0)], [4 * n]), Layout([regular(part, 2, 0, 6)], [2 * n + 6])
+    src = [torch.from_numpy(bits.view(np.uint8).copy())]
+    want = oracle.reshard(saved, target, src, poison=POISON, convert=1)
+    case = Case("edges", 0, {0: TensorSpec(0, "t", (n,), torch.float32, ("bits",))}, saved, target, convert=1)
+    got, p = gpu_reshard(case, src)
+    assert_same(got, want, "rounding edges")
+    p.destroy()
+
+
+def test_convert_model_shaped_scaled():
+    for case in (synth.eval_load_case(layers=2, hidden=256, ffn=688, vocab=1000),
+                 synth.eval_load_case(layers=2, hidden=264, ffn=696, vocab=1000, zero_saved=True)):
+        st = check_case(case)
+        assert st["n_transposed"] == 0
+    # mixed: a plan with the flag where only some tensors differ in element size
+    c = synth.eval_load_case(layers=1, hidden=128, ffn=344, vocab=500)
+    keep = {f for f in c.tensors if f % 2 == 0}   # these stay fp32 on the target side
+    wide = synth.megatron_layout(synth.llama_tensors(1, 128, 344, 500), [synth.STATE_FP32_MASTER], 1, 2, 4, replicate_norms=True)
+    shards = [w if w.parts[0].fqn in keep else n for w, n in zip(wide.shards, c.target.shards)]
+    # re-pack: the two layouts' offsets do not fit together
+    target = synth.packed_layout(shards, [sh.buf for sh in shards], len(wide.buf_bytes))
+    check_case(Case("eval_load_mixed", c.seed, c.tensors, c.saved, target, convert=1))
+
+
+def test_convert_needs_the_flag():
+    c = synth.eval_load_case(layers=1, hidden=64, ffn=96, vocab=128)
+    with pytest.raises(binding.BcpError) as e:
+        binding.plan(binding.layout_to_meta(c.saved), binding.layout_to_meta(c.target))
+    assert e.value.name == "BCP_ERR_DTYPE_MISMATCH"
+
+
+def test_device_and_host_verdicts_agree():
+    """bcp_plan and bcp_validate_meta give the same status for the same metadata and flags."""
+    from tests import meta_cases
+    for name, sm, tm, flags, want in meta_cases.cases():
+        dev, dtext = meta_cases.device_verdict(sm, tm, flags)
+        host, htext = meta_cases.host_verdict(sm, tm, flags)
+        assert dev == host == want, f"{name}: device {dev} ({dtext}), host {host} ({htext}), expected {want}"
+        if dev != "BCP_OK" and "record" in htext:
+            assert dtext.split(":")[1] == htext.split(":")[1], f"{name}: device names '{dtext}', host '{htext}'"
+
+
+def test_checked_reshard_refuses_short_buffers():
+    case = synth.cfg1(128, 96)
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    p = binding.plan(binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target))
+    se, de = p.buffer_extents()
+    assert list(se) == case.saved.buf_bytes and list(de) == case.target.buf_bytes
+    dsrc = [b.cuda() for b in src]
+    ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    for side, i in (("src", 1), ("dst", 2)):
+        bufs = {"src": list(dsrc), "dst": list(ddst)}
+        bufs[side][i] = bufs[side][i][:-1]
+        with pytest.raises(binding.BcpError) as e:
+            binding.reshard(p, bufs["src"], bufs["dst"])
+        assert e.value.name == "BCP_ERR_OUT_OF_BOUNDS" and f"[{i}]" in str(e.value)
+    torch.cuda.synchronize()
+    assert all(bool((d == POISON).all()) for d in ddst)   # nothing was launched
+    binding.reshard(p, dsrc, ddst)
+    torch.cuda.synchronize()
+    assert_same([d.cpu().numpy() for d in ddst], oracle.reshard(case.saved, case.target, src, poison=POISON), "checked")
+    p.destroy()
+
+
+def test_skip_overlap_check_flag():
+    """BCP_SKIP_OVERLAP_CHECK: same plan and bytes on a valid layout; an overlap is then the caller's error
+    and shows up, if at all, as a target covered more than once."""
+    case = synth.cfg5(layers=1, hidden=128, experts=8, ffn=44, n_small=500)
+    src = synth.materialize(case.saved, case.tensors, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    got, p = gpu_reshard(case, src, flags=binding.BCP_SKIP_OVERLAP_CHECK)
+    assert_same(got, want, "skip overlap check")
+    got2, p2 = gpu_reshard(case, src)
+    assert np.array_equal(p.regions(), p2.regions())
+    p.destroy()
+    p2.destroy()
 
 
 @pytest.mark.parametrize("modes", [("grid", "grid"), ("grid", "flat"), ("flat", "grid"), ("flat", "flat")])
@@ -271,6 +370,36 @@ def test_source_ordered_plan_runs_as_chunks_arrive(idx):
             off = end
     torch.cuda.synchronize()
     assert_same([t.cpu().numpy() for t in ddst], want, case.name + " chunked arrival")
+    p.destroy()
+
+
+def test_source_ordered_plan_with_a_spare_segment_at_the_end_of_a_blob():
+    """A long run with a misaligned destination is cut where the DESTINATION offset is a multiple of 256, which
+    reserves a possibly empty last segment per row; here that empty segment sits at the very end of a blob,
+    followed only by a tiny tensor.  Its key must still lie inside the blob, or the batch it shares with the
+    tiny tensor would never run under chunked arrival."""
+    n_a, n_b = 2 * 65536 - 100, 50
+    specs = {0: TensorSpec(0, "a", (n_a,), torch.uint8, ("bits",)), 1: TensorSpec(1, "b", (n_b,), torch.uint8, ("bits",))}
+    pa, pb = Part(0, (n_a,), (0,), (n_a,)), Part(1, (n_b,), (0,), (n_b,))
+    saved = Layout([regular(pa, 1, 0, 0), regular(pb, 1, 0, n_a)], [n_a + n_b])
+    target = Layout([regular(pa, 1, 0, 7), regular(pb, 1, 0, n_a + 300)], [n_a + 400])
+    case = Case("spare", 5, specs, saved, target)
+    src = synth.materialize(saved, specs, 5)
+    want = oracle.reshard(saved, target, src, poison=POISON)
+    p = binding.plan(binding.layout_to_meta(saved), binding.layout_to_meta(target), flags=binding.BCP_ORDER_BY_SOURCE)
+    assert p.stats()["n_tiles"] == 4   # three segments of the long run (the last one empty) and the tiny tensor
+    host = [b.pin_memory() for b in src]
+    for chunk in (40000, 1 << 20):
+        dsrc = [torch.full((b.numel(),), 0x3C, dtype=torch.uint8, device="cuda") for b in src]
+        ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in target.buf_bytes]
+        binding.reshard_from_host(p, host, dsrc, ddst, chunk, torch.cuda.Stream())
+        torch.cuda.synchronize()
+        assert_same([d.cpu().numpy() for d in ddst], want, f"spare segment, chunks of {chunk}")
+    # a host blob shorter than what the plan reads is refused (its last regions would never run)
+    with pytest.raises(binding.BcpError) as e:
+        binding.reshard_from_host(p, [host[0][:-1]], dsrc, ddst, 40000, torch.cuda.Stream())
+    assert e.value.name == "BCP_ERR_OUT_OF_BOUNDS"
+    torch.cuda.synchronize()
     p.destroy()
 
 

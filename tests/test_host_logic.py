@@ -24,6 +24,7 @@ def declared_functions():
     return sorted(set(re.findall(r"\b(bcp_[a-z_0-9]+)\s*\(", text)))
 
 
+@pytest.mark.needs_full_lib
 def test_releasing_an_unused_workspace_is_a_no_op():
     assert binding.release_workspace() == 0
 
@@ -167,6 +168,7 @@ def test_layout_to_meta_flat_case_counts():
                 off += int(r["flat_end"] - r["flat_begin"]) * int(r["itemsize"])
 
 
+@pytest.mark.needs_full_lib
 @pytest.mark.skipif(torch.cuda.is_available(), reason="checks the no-GPU failure mode")
 def test_compute_calls_fail_loudly_without_a_gpu():
     m = np.zeros(1, dtype=SHARD_META)
@@ -175,6 +177,7 @@ def test_compute_calls_fail_loudly_without_a_gpu():
     assert e.value.name == "BCP_ERR_NO_DEVICE"
 
 
+@pytest.mark.needs_full_lib
 def test_configure_rejects_bad_values():
     with pytest.raises(binding.BcpError):
         binding.configure(tile_bytes=5000)
