@@ -195,6 +195,18 @@ def cpu_baseline(workload: str):
             "host": host_description()}
 
 
+def count_mismatches(a, b) -> int:
+    """Differing bytes of two equally long byte tensors on one device (in pieces: a whole-buffer mask would
+    take as much memory again as the buffers)."""
+    import torch
+    if torch.equal(a, b):
+        return 0
+    step, bad = 256 << 20, 0
+    for i in range(0, a.numel(), step):
+        bad += int(torch.count_nonzero(a[i:i + step] != b[i:i + step]))
+    return bad
+
+
 def verify_result(case, src, dst, stream, reshard_once, generated: bool):
     """After the timed loop, outside it: the destination buffers are poisoned, one more reshard runs, and its
     result is compared on the device with the library-slicing closed form (synth.materialize of the TARGET
@@ -218,7 +230,7 @@ def verify_result(case, src, dst, stream, reshard_once, generated: bool):
         dev = "cuda" if any(sh.numel > (1 << 20) for sh in shards) else "cpu"
         want = synth.materialize(synth.Layout(shards, case.target.buf_bytes), case.tensors, case.seed, device=dev,
                                  poison=POISON, only_bufs={b})[b]
-        bad += int((dst[b] != want.to(dst[b].device)).sum())
+        bad += count_mismatches(dst[b], want.to(dst[b].device))
         compared += dst[b].numel()
         del want
     for gid, shards in groups.items():
@@ -227,7 +239,7 @@ def verify_result(case, src, dst, stream, reshard_once, generated: bool):
                                  poison=POISON, only_bufs=bufs)
         for sh in shards:
             n = sh.numel * sh.itemsize
-            bad += int((dst[sh.buf][sh.byte_offset:sh.byte_offset + n] != want[sh.buf][sh.byte_offset:sh.byte_offset + n]).sum())
+            bad += count_mismatches(dst[sh.buf][sh.byte_offset:sh.byte_offset + n], want[sh.buf][sh.byte_offset:sh.byte_offset + n])
             compared += n
         del want
     return {"mismatched_bytes": bad, "compared_bytes": compared,
@@ -305,6 +317,10 @@ def main():
     ap.add_argument("--from-host", type=int, default=0, metavar="CHUNK_MIB",
                     help="also time the chunked host-to-HBM arrival overlapped with the reshard (pinned host copies "
                          "of the saved blobs, chunks of this many MiB) against copy-then-reshard")
+    ap.add_argument("--pmc-reference", action="store_true",
+                    help="for counter runs under rocprofv3 --pmc: instead of the ceiling copies (which would add other "
+                         "k_reshard launches to the per-kernel averages) run one plain elementwise copy kernel of known "
+                         "size, whose FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
     ap.add_argument("--reshard-only", action="store_true",
                     help="extra timing loop of bcp_reshard alone on a prebuilt plan (reported beside the step numbers)")
     args = ap.parse_args()
@@ -334,6 +350,8 @@ def main():
         host = synth.materialize(small_layout, case.tensors, case.seed, only_bufs=set(range(len(src))) - big)
         src = [s if s is not None else h.cuda() for s, h in zip(src, host)]
         del host
+    else:
+        src = synth.materialize(case.saved, case.tensors, case.seed, device="cuda")
     dst = [torch.empty(n, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
     torch.cuda.synchronize()
     torch.cuda.empty_cache()  # hand the generator's temporaries back: the library allocates with hipMalloc
@@ -426,7 +444,15 @@ def main():
     big_s = max(src, key=lambda b: b.numel())
     big_d = max(dst, key=lambda b: b.numel())
     ceil, naive = {}, {}
-    if n_copy >= 1 << 20:
+    if args.pmc_reference:
+        # torch's elementwise kernel for bitwise_xor on int32: reads n_ref bytes, writes n_ref bytes, nothing else
+        n_ref = min(n_copy, 1 << 30) // 4 * 4
+        a, b = big_s[:n_ref].view(torch.int32), big_d[:n_ref].view(torch.int32)
+        for _ in range(3):
+            torch.bitwise_xor(a, 0, out=b)
+        torch.cuda.synchronize()
+        ceil = {"reference_kernel": "elementwise bitwise_xor(int32, 0)", "reference_bytes_each_way": n_ref}
+    elif n_copy >= 1 << 20:
         cc = synth.copy_case(n_copy)
         cp = binding.plan(binding.layout_to_meta(cc.saved), binding.layout_to_meta(cc.target), stream=stream)
         for name, fn, out in (("copy_through_k_reshard", lambda: binding.reshard(cp, [big_s], [big_d], stream=stream), ceil),

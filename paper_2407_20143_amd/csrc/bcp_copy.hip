@@ -65,6 +65,16 @@ template <int G>
 __device__ __forceinline__ void st(gdst_t p, typename Granule<G>::type v) {
   __builtin_nontemporal_store(v, (typename Granule<G>::type BCP_GLOBAL*)p);
 }
+// small tiles: neighbouring tiles share cache lines at their edges, and the L2 that has a line from one
+// tile serves, or merges with, the next one's part of it -- ordinary (temporal) accesses
+template <int G>
+__device__ __forceinline__ typename Granule<G>::type ldc(gsrc_t p) {
+  return *(const typename Granule<G>::type BCP_GLOBAL*)p;
+}
+template <int G>
+__device__ __forceinline__ void stc(gdst_t p, typename Granule<G>::type v) {
+  *(typename Granule<G>::type BCP_GLOBAL*)p = v;
+}
 template <int G>
 __device__ __forceinline__ typename Granule<G>::type lds_ld(const char* p) {
   return *reinterpret_cast<const typename Granule<G>::type*>(p);
@@ -84,6 +94,14 @@ __device__ __forceinline__ u32x4 ld<-16>(gsrc_t p) {
 template <>
 __device__ __forceinline__ void st<-16>(gdst_t p, u32x4 v) {
   __builtin_nontemporal_store(v, (u32x4_unaligned BCP_GLOBAL*)p);
+}
+template <>
+__device__ __forceinline__ u32x4 ldc<-16>(gsrc_t p) {
+  return *(const u32x4_unaligned BCP_GLOBAL*)p;
+}
+template <>
+__device__ __forceinline__ void stc<-16>(gdst_t p, u32x4 v) {
+  *(u32x4_unaligned BCP_GLOBAL*)p = v;
 }
 
 // rows x run_g granules of |GG| bytes (GG == -16: 16-byte granules at unaligned addresses); rows at
@@ -445,160 +463,196 @@ __device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __res
 }
 
 // ---- small tiles ---------------------------------------------------------------------------------
-// A few threads copy a tile of a few hundred bytes: what such a copy costs is memory round trips,
-// not bandwidth.  Every thread therefore issues all loads of a round of kRound items before the
-// first store of the round, so a tile takes one round trip per round instead of one per item, and
-// a tile is given one thread per round of items it consists of (small_tile_threads).
-constexpr int kRound = 4;
+// The lanes of one wave work on different tiles of a few hundred bytes with different alignments.
+// What such a copy costs is instructions and memory round trips, not bandwidth.  Both are kept down by
+// cutting a tile into ITEMS -- one access of 16, 8, 4, 2 or 1 bytes on both sides -- by rules worked
+// out ONCE per tile, by the thread that fetched its descriptor (one thread per tile: full waves), and
+// left in LDS as a SmallTile record.  A tile then gets one lane per kRound items; a lane finds its tile
+// by binary search in the scanned lane counts, reads the record, decodes its items with a few
+// instructions each, and all loads of the wave are issued -- whatever their sizes and tiles -- before
+// the first store: one round trip per round for lanes that work on different tiles and alignments.
+constexpr int kRound = 2;  // items of a lane in flight (measured: 2 beats 1 and 4)
 
-// rows x run_g granules of |GG| bytes, as copy_rows
-template <int GG>
-__device__ __forceinline__ void small_rows(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
-                                           uint32_t run_g, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
-  constexpr int G = GG < 0 ? -GG : GG;
-  constexpr int R = kRound;
-  typedef typename Granule<GG>::type V;
-  const uint32_t total = nrows * run_g;
-  for (uint32_t base = tid; base < total; base += R * nt) {
-    V v[R];
-    int64_t dof[R];
-#pragma unroll
-    for (int u = 0; u < R; ++u) {
-      const uint32_t i = base + u * nt;
-      if (i < total) {
-        const uint32_t row = nrows == 1 ? 0 : i / run_g, col = i - row * run_g;
-        v[u] = ld<GG>(s + (int64_t)row * sp + (int64_t)col * G);
-        dof[u] = (int64_t)row * dp + (int64_t)col * G;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < R; ++u)
-      if (base + u * nt < total) st<GG>(d + dof[u], v[u]);
-  }
+struct SmallTile {  // 64 bytes, takes the descriptor's place in LDS
+  enum Mode : uint32_t {
+    kUniform,  // rows of items of one size g
+    kRun,      // one contiguous run whose two sides disagree modulo 16: items of e bytes up to the destination's
+               // next 16-byte boundary, 16-byte items (aligned stores, unaligned loads), items of e bytes again
+    kMixed,    // rows of runs of 16 bytes or more whose accesses may be unaligned: per row 16-byte items, then
+               // items of e bytes
+    kElems,    // transposed tile: items of g bytes inside elements, source contiguous along a, destination along b
+  };
+  uint64_t s, d;        // addresses of the tile's first byte on the two sides
+  int64_t p0, p1;       // pitches of the descriptor
+  uint32_t n_items;
+  uint32_t ipr;         // items per row (kUniform, kMixed); items per element (kElems)
+  float inv_ipr;        // 1 / ipr, a little high: (i * inv_ipr) truncates to i / ipr or one more
+  uint32_t body;        // 16-byte items per row (kMixed) or in the run (kRun); kElems: element size
+  uint32_t head;        // kRun: bytes before the first 16-byte item; kElems: elements along a, and 1 / that
+  float inv_na;
+  uint32_t mode_glog;   // mode | log2 of g (kUniform, kElems) or of e (kRun, kMixed) << 8
+  uint32_t pad_;
+};
+static_assert(sizeof(SmallTile) == sizeof(TileDesc), "takes the descriptor's slot");
+
+__device__ __forceinline__ float inv_high(uint32_t n) {  // for n, i < 2^22: floor(i * inv_high(n)) is i / n or i / n + 1
+  return __uint_as_float(__float_as_uint(1.0f / (float)(n ? n : 1u)) + 2u);
+}
+__device__ __forceinline__ uint32_t div_small(uint32_t i, uint32_t n, float inv) {
+  uint32_t q = (uint32_t)((float)i * inv);
+  if (q * n > i) --q;
+  return q;
 }
 
-// One contiguous run whose two sides disagree modulo 16, as copy_run_misaligned; the bytes before
-// the destination's first and after its last 16-byte boundary move as items of E bytes (4 when
-// both addresses and the length allow it) together with the first round of 16-byte items.
-template <int E>
-__device__ __forceinline__ void small_run_misaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t run,
-                                                     uint32_t tid, uint32_t nt) {
-  typedef typename Granule<E>::type EV;
-  constexpr int RE = E == 4 ? 2 : kRound, RB = kRound;
-  uint32_t head = (uint32_t)(-(uintptr_t)d) & 15u;
-  if (head > run) head = run;
-  const uint32_t body = (run - head) >> 4, done = head + (body << 4);
-  const uint32_t nh = head / E, ne = nh + (run - done) / E;  // edge items: at most 30 / E
-  auto edge_off = [&](uint32_t e) -> uint32_t { return e < nh ? e * E : done + (e - nh) * E; };
-  gsrc_t s2 = s + head;
-  gdst_t d2 = d + head;
-  EV ev[RE];
-  u32x4 bv[RB];
-#pragma unroll
-  for (int u = 0; u < RE; ++u) {
-    const uint32_t e = tid + u * nt;
-    if (e < ne) ev[u] = ld<E>(s + edge_off(e));
-  }
-#pragma unroll
-  for (int u = 0; u < RB; ++u) {
-    const uint32_t i = tid + u * nt;
-    if (i < body) bv[u] = ld<-16>(s2 + i * 16u);
-  }
-#pragma unroll
-  for (int u = 0; u < RE; ++u) {
-    const uint32_t e = tid + u * nt;
-    if (e < ne) st<E>(d + edge_off(e), ev[u]);
-  }
-#pragma unroll
-  for (int u = 0; u < RB; ++u) {
-    const uint32_t i = tid + u * nt;
-    if (i < body) st<16>(d2 + i * 16u, bv[u]);
-  }
-  // what the first round did not reach (few threads on a long or byte-aligned run)
-  for (uint32_t e = tid + RE * nt; e < ne; e += nt) st<E>(d + edge_off(e), ld<E>(s + edge_off(e)));
-  for (uint32_t base = tid + RB * nt; base < body; base += RB * nt) {
-#pragma unroll
-    for (int u = 0; u < RB; ++u) {
-      const uint32_t i = base + u * nt;
-      if (i < body) bv[u] = ld<-16>(s2 + i * 16u);
-    }
-#pragma unroll
-    for (int u = 0; u < RB; ++u) {
-      const uint32_t i = base + u * nt;
-      if (i < body) st<16>(d2 + i * 16u, bv[u]);
-    }
-  }
-}
-
-// rows of `run` >= 16 bytes where 16-byte alignment does not hold everywhere, as copy_rows_unaligned
-__device__ __forceinline__ void small_rows_unaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
-                                                     uint32_t run, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
-  const uint32_t body = run >> 4, tail = run & 15u;
-  small_rows<-16>(s, d, nrows, body, sp, dp, tid, nt);
-  if (tail) {
-    const size_t off = (size_t)body << 4;
-    const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run | (uintptr_t)sp | (uintptr_t)dp;
-    if ((al & 3u) == 0) small_rows<4>(s + off, d + off, nrows, tail >> 2, sp, dp, tid, nt);
-    else small_rows<1>(s + off, d + off, nrows, tail, sp, dp, tid, nt);
-  }
-}
-
-// na x nb elements of `e` bytes moved as granules of E bytes (E == e, or E == 1 when the addresses
-// are not aligned to the element size); source contiguous along a, destination along b
-template <int E>
-__device__ __forceinline__ void small_transpose(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na,
-                                                uint32_t nb, uint32_t e, int64_t spb, int64_t dpa, uint32_t tid,
-                                                uint32_t nt) {
-  constexpr int R = kRound;
-  typedef typename Granule<E>::type V;
-  const uint32_t per = e / E, total = na * nb * per;
-  for (uint32_t base = tid; base < total; base += R * nt) {
-    V v[R];
-    int64_t dof[R];
-#pragma unroll
-    for (int u = 0; u < R; ++u) {
-      const uint32_t i = base + u * nt;
-      if (i < total) {
-        const uint32_t el = i / per, by = (i - el * per) * E;
-        const uint32_t b = el / na, a = el - b * na;
-        v[u] = ld<E>(s + (int64_t)a * e + (int64_t)b * spb + by);
-        dof[u] = (int64_t)a * dpa + (int64_t)b * e + by;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < R; ++u)
-      if (base + u * nt < total) st<E>(d + dof[u], v[u]);
-  }
-}
-
-// threads a small tile wants: one per kRound items of the granule its alignment allows (the
-// choice of granule mirrors process_tile)
-__device__ __forceinline__ uint32_t small_tile_threads(const TileDesc& T, gsrc_t s, gdst_t d) {
-  uint32_t items;
-  if ((T.kind & 0xffu) == kConvert) {
-    items = max(T.b * (T.a >> 3), 1u);  // groups of eight elements
-  } else if ((T.kind & 0xffu) == kTranspose) {
+__device__ __forceinline__ SmallTile small_tile(const TileDesc& T, gsrc_t s, gdst_t d) {
+  SmallTile c;
+  c.s = (uint64_t)(uintptr_t)s;
+  c.d = (uint64_t)(uintptr_t)d;
+  c.p0 = T.p0;
+  c.p1 = T.p1;
+  c.ipr = 1;
+  c.body = c.head = c.pad_ = 0;
+  c.inv_na = 0.f;
+  uint32_t mode, glog;
+  if ((T.kind & 0xffu) == kTranspose) {
     const uint32_t e = (T.kind >> 8) & 0xffu;
     const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)T.p0 | (uintptr_t)T.p1;
-    items = T.a * T.b * ((al & (e - 1)) == 0 ? 1u : e);
+    const uint32_t g = (al & (e - 1)) == 0 ? e : 1u;  // elements not aligned to their own size move as bytes
+    mode = SmallTile::kElems;
+    glog = 31u - (uint32_t)__clz((int)g);
+    c.ipr = e / g;
+    c.head = T.a;
+    c.inv_na = inv_high(T.a);
+    c.body = e;
+    c.n_items = T.a * T.b * c.ipr;
   } else {
     const uint32_t run = T.a, nrows = T.b;
     uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
     if (nrows > 1) al |= (uintptr_t)T.p0 | (uintptr_t)T.p1;
-    if ((al & 15u) == 0) items = nrows * (run >> 4);
-    else if (run >= 64) items = max(nrows * (run >> 4), nrows == 1 ? 3u * kRound : 0u);  // 3 threads cover the
-                                                                // pieces at the two ends of a single run
-    else items = nrows * (run >> ((al & 7u) == 0 ? 3 : (al & 3u) == 0 ? 2 : (al & 1u) == 0 ? 1 : 0));
+    if ((al & 15u) == 0) {
+      mode = SmallTile::kUniform;
+      glog = 4;
+      c.ipr = run >> 4;
+      c.n_items = nrows * c.ipr;
+    } else if (nrows == 1 && run >= 64) {
+      mode = SmallTile::kRun;
+      glog = (al & 3u) == 0 ? 2u : 0u;
+      c.head = (uint32_t)(-(uintptr_t)d) & 15u;
+      c.body = (run - c.head) >> 4;
+      c.n_items = (c.head >> glog) + c.body + ((run - c.head - (c.body << 4)) >> glog);
+    } else if (run >= 16 && (al & 3u) == 0) {
+      // 16-byte accesses at 4-byte aligned addresses cost the memory system nothing extra, and four times
+      // fewer items than 4-byte ones
+      mode = SmallTile::kMixed;
+      glog = 2;
+      c.body = run >> 4;
+      c.ipr = c.body + ((run & 15u) >> 2);
+      c.n_items = nrows * c.ipr;
+    } else if (run >= 64) {
+      mode = SmallTile::kMixed;
+      glog = 0;
+      c.body = run >> 4;
+      c.ipr = c.body + (run & 15u);
+      c.n_items = nrows * c.ipr;
+    } else {
+      mode = SmallTile::kUniform;
+      glog = (al & 7u) == 0 ? 3u : (al & 3u) == 0 ? 2u : (al & 1u) == 0 ? 1u : 0u;
+      c.ipr = run >> glog;
+      c.n_items = nrows * c.ipr;
+    }
   }
-  return (items + kRound - 1) / kRound;
+  c.inv_ipr = inv_high(c.ipr);
+  c.mode_glog = mode | (glog << 8);
+  return c;
 }
 
-// `nt` threads (tid in [0, nt)) copy one tile: the whole workgroup (WG == true, may use the LDS
-// staging area and barriers) or any group of threads that need not agree on the tile (WG == false,
-// no barriers, nothing assumed uniform across a wave).
+// item i of the tile: byte offsets on the two sides and log2 of its size
+__device__ __forceinline__ void small_item(const SmallTile& c, uint32_t i, int64_t* so, int64_t* dof, uint32_t* gl) {
+  const uint32_t mode = c.mode_glog & 0xffu, glog = c.mode_glog >> 8;
+  if (mode == SmallTile::kRun) {
+    const uint32_t nh = c.head >> glog;
+    uint32_t off;
+    *gl = glog;
+    if (i < nh) {
+      off = i << glog;
+    } else if (i < nh + c.body) {
+      off = c.head + ((i - nh) << 4);
+      *gl = 4;
+    } else {
+      off = c.head + (c.body << 4) + ((i - nh - c.body) << glog);
+    }
+    *so = *dof = off;
+    return;
+  }
+  const uint32_t row = div_small(i, c.ipr, c.inv_ipr), col = i - row * c.ipr;
+  if (mode == SmallTile::kElems) {  // row: element index, col: item inside the element
+    const uint32_t b = div_small(row, c.head, c.inv_na), a = row - b * c.head, by = col << glog;
+    *so = (int64_t)a * c.body + (int64_t)b * c.p0 + by;
+    *dof = (int64_t)a * c.p1 + (int64_t)b * c.body + by;
+    *gl = glog;
+    return;
+  }
+  uint32_t off = col << glog;
+  *gl = glog;
+  if (mode == SmallTile::kMixed) {
+    if (col < c.body) {
+      off = col << 4;
+      *gl = 4;
+    } else {
+      off = (c.body << 4) + ((col - c.body) << glog);
+    }
+  }
+  *so = (int64_t)row * c.p0 + off;
+  *dof = (int64_t)row * c.p1 + off;
+}
+
+// One item: the load, and later the store.  Ordinary (temporal) accesses: neighbouring tiles share cache
+// lines at their edges, and the L2 that holds a line for one tile serves, or merges with, the next one's
+// part of it.  16-byte items may sit at any address on either side.
+__device__ __forceinline__ u32x4 item_load(gsrc_t p, uint32_t gl) {
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (gl == 4) v = *(const u32x4_unaligned BCP_GLOBAL*)p;
+  else if (gl == 3) { const u32x2 t = *(const u32x2 BCP_GLOBAL*)p; v[0] = t[0]; v[1] = t[1]; }
+  else if (gl == 2) v[0] = *(const uint32_t BCP_GLOBAL*)p;
+  else if (gl == 1) v[0] = *(const uint16_t BCP_GLOBAL*)p;
+  else if (gl == 0) v[0] = *(const uint8_t BCP_GLOBAL*)p;
+  return v;
+}
+__device__ __forceinline__ void item_store(gdst_t p, uint32_t gl, const u32x4& v) {
+  if (gl == 4) *(u32x4_unaligned BCP_GLOBAL*)p = v;
+  else if (gl == 3) *(u32x2 BCP_GLOBAL*)p = u32x2{v[0], v[1]};
+  else if (gl == 2) *(uint32_t BCP_GLOBAL*)p = v[0];
+  else if (gl == 1) *(uint16_t BCP_GLOBAL*)p = (uint16_t)v[0];
+  else if (gl == 0) *(uint8_t BCP_GLOBAL*)p = (uint8_t)v[0];
+}
+
+// a whole tile by `nt` lanes (tid in [0, nt)), kRound items of a lane in flight at a time
+__device__ __forceinline__ void small_tile_copy(const SmallTile& c, uint32_t tid, uint32_t nt) {
+  constexpr int R = kRound;
+  gsrc_t s = (gsrc_t)c.s;
+  gdst_t d = (gdst_t)c.d;
+  for (uint32_t base = tid; base < c.n_items; base += R * nt) {
+    int64_t dof[R];
+    uint32_t gl[R];
+    u32x4 v[R];
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      const uint32_t i = base + u * nt;
+      gl[u] = ~0u;
+      int64_t so = 0;
+      if (i < c.n_items) small_item(c, i, &so, &dof[u], &gl[u]);
+      v[u] = item_load(s + so, gl[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u) item_store(d + dof[u], gl[u], v[u]);
+  }
+}
+
+// The whole workgroup (`nt` threads, tid in [0, nt)) copies one tile; may use the LDS staging area and
+// barriers.
 // TR == false: the plan holds no transposed tile that needs the staging area, and the code for
 // them is left out (it would cost the other paths registers).  CV: likewise for converting tiles.
-template <bool WG, bool TR, bool CV>
+template <bool TR, bool CV>
 __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t d, char* lds, uint32_t tid,
                                              uint32_t nt) {
   if (CV && (T.kind & 0xffu) == kConvert) {
@@ -610,7 +664,7 @@ __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t
     const uint32_t tda = 1u << ((T.kind >> 16) & 0xffu), tdb = 1u << (T.kind >> 24);
     const int64_t spb = T.p0, dpa = T.p1;
     const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
-    if (WG && TR && (al & (e - 1)) == 0) {
+    if (TR && (al & (e - 1)) == 0) {
       switch (e) {
         case 1: transpose_any<1>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
         case 2: transpose_any<2>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
@@ -618,38 +672,8 @@ __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t
         case 8: transpose_any<8>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
         default: transpose_any<16>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
       }
-    } else if (!WG && (al & (e - 1)) == 0) {  // a small tile: no staging, element by element
-      switch (e) {
-        case 1: small_transpose<1>(s, d, na, nb, e, spb, dpa, tid, nt); break;
-        case 2: small_transpose<2>(s, d, na, nb, e, spb, dpa, tid, nt); break;
-        case 4: small_transpose<4>(s, d, na, nb, e, spb, dpa, tid, nt); break;
-        case 8: small_transpose<8>(s, d, na, nb, e, spb, dpa, tid, nt); break;
-        default: small_transpose<16>(s, d, na, nb, e, spb, dpa, tid, nt); break;
-      }
-    } else {  // elements not aligned to their own size: byte moves
-      small_transpose<1>(s, d, na, nb, e, spb, dpa, tid, nt);
-    }
-    return;
-  }
-  if (!WG) {
-    const uint32_t run = T.a, nrows = T.b;
-    const int64_t sp = T.p0, dp = T.p1;
-    uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
-    if (nrows > 1) al |= (uintptr_t)sp | (uintptr_t)dp;
-    if ((al & 15u) == 0) {
-      small_rows<16>(s, d, nrows, run >> 4, sp, dp, tid, nt);
-    } else if (run >= 64) {
-      if (nrows > 1) small_rows_unaligned(s, d, nrows, run, sp, dp, tid, nt);
-      else if ((al & 3u) == 0) small_run_misaligned<4>(s, d, run, tid, nt);
-      else small_run_misaligned<1>(s, d, run, tid, nt);
-    } else if ((al & 7u) == 0) {
-      small_rows<8>(s, d, nrows, run >> 3, sp, dp, tid, nt);
-    } else if ((al & 3u) == 0) {
-      small_rows<4>(s, d, nrows, run >> 2, sp, dp, tid, nt);
-    } else if ((al & 1u) == 0) {
-      small_rows<2>(s, d, nrows, run >> 1, sp, dp, tid, nt);
-    } else {
-      small_rows<1>(s, d, nrows, run, sp, dp, tid, nt);
+    } else {  // elements not aligned to their own size (or a plan without staged tiles): item by item
+      small_tile_copy(small_tile(T, s, d), tid, nt);
     }
     return;
   }
@@ -704,30 +728,43 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
     const uint64_t p = ptrs_in_lds ? lds_ptrs[n_src + T.dst_buf] : ptr_table[n_src + T.dst_buf];
     return (gdst_t)p + T.dst_off;
   };
-  // One batch: a single tile for the whole workgroup, or several small tiles.  Small tiles are
-  // latency bound (descriptor load, then data load, then store, a few hundred bytes each), so the
-  // whole batch is kept in flight at once: the threads fetch one descriptor each into LDS, every
-  // tile is given one thread per round of items (a scan over the workgroup turns the counts into
-  // thread ranges), and each thread looks up the tile it works for.
+  // One batch: a single tile for the whole workgroup, or up to a few hundred small tiles (a few tile
+  // budgets of payload).  The threads fetch and classify one tile each, a scan over the workgroup turns
+  // the lane counts into lane ranges, and every lane works for the tile whose range it falls in.
   auto run_batch = [&](const TileDesc& H) {
     if (H.count == 1) {
-      process_tile<true, TR, CV>(H, src_of(H), dst_of(H), lds, threadIdx.x, blockDim.x);
+      process_tile<TR, CV>(H, src_of(H), dst_of(H), lds, threadIdx.x, blockDim.x);
       return;
     }
     const uint32_t nthr = blockDim.x, tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    TileDesc* ldesc = reinterpret_cast<TileDesc*>(lds);                              // [nthr]
-    uint32_t* lstart = reinterpret_cast<uint32_t*>(lds + sizeof(TileDesc) * nthr);   // [nthr + 1]
-    uint32_t* lwave = lstart + nthr + 1;                                             // [waves]
+    SmallTile* ltile = reinterpret_cast<SmallTile*>(lds);                                // [nthr]
+    uint32_t* lstart = reinterpret_cast<uint32_t*>(lds + sizeof(SmallTile) * nthr);      // [nthr + 1]
+    uint32_t* lwave = lstart + nthr + 1;                                                 // [waves]
     for (uint32_t base = 0; base < H.count; base += nthr) {
       const uint32_t n = min(nthr, H.count - base);
       uint32_t c = 0;
       if (tid < n) {
         const TileDesc T = tiles[H.first + base + tid];
-        ldesc[tid] = T;
-        c = small_tile_threads(T, src_of(T), dst_of(T));
+        if (CV && (T.kind & 0xffu) == kConvert) {  // converting tiles: what convert_rows needs, marked by the mode
+          SmallTile raw;
+          raw.s = (uint64_t)(uintptr_t)src_of(T);
+          raw.d = (uint64_t)(uintptr_t)dst_of(T);
+          raw.p0 = T.p0;
+          raw.p1 = T.p1;
+          raw.n_items = max(T.b * ((T.a + 7u) >> 3), 1u);  // groups of eight elements
+          raw.ipr = T.b;       // rows
+          raw.body = T.a;      // elements per row
+          raw.mode_glog = 0xffu;
+          ltile[tid] = raw;
+          c = raw.n_items;
+        } else {
+          const SmallTile st = small_tile(T, src_of(T), dst_of(T));
+          ltile[tid] = st;
+          c = (st.n_items + kRound - 1) / kRound;
+        }
         c = c < 1 ? 1u : (c > nthr ? nthr : c);
       }
-      uint32_t x = c;  // inclusive scan of c: within the wave, then over the waves' totals
+      uint32_t x = c;  // inclusive scan of the lane counts: within the wave, then over the waves' totals
 #pragma unroll
       for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
         const uint32_t y = __shfl_up(x, dlt);
@@ -748,12 +785,14 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
           if (lstart[mid] <= v) lo = mid;
           else hi = mid;
         }
-        const TileDesc T = ldesc[lo];
-        const uint32_t t0 = lstart[lo];
-        process_tile<false, TR, CV>(T, src_of(T), dst_of(T), lds, v - t0, lstart[lo + 1] - t0);
+        const SmallTile st = ltile[lo];
+        const uint32_t t0 = lstart[lo], cnt = lstart[lo + 1] - t0;
+        if (CV && st.mode_glog == 0xffu) convert_rows((gsrc_t)st.s, (gdst_t)st.d, st.ipr, st.body, st.p0, st.p1, v - t0, cnt);
+        else small_tile_copy(st, v - t0, cnt);
       }
       __syncthreads();  // the staging area is written again by the next slice or batch
     }
+    // (the next batch, which may want the whole staging area, starts behind the caller's barrier)
   };
   if (!persistent) {
     __syncthreads();

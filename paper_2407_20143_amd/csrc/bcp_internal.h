@@ -85,6 +85,8 @@ static_assert(sizeof(TileDesc) == 64, "one tile descriptor per 64-byte line");
 constexpr int kKeyShift = 44;                    // source-order key: buffer index above, byte offset below
 constexpr uint32_t kSmallTileBytes = 16 * 1024;  // tiles below this may share a batch
 constexpr uint32_t kMinBatchWeight = 256;        // a tile counts at least this much: <= budget/256 tiles per batch
+constexpr uint32_t kSmallBatchTiles = 4;         // budget of a batch of small tiles, in tile budgets: up to 1024 tiles,
+                                                 // one per thread of the copy kernel's workgroup (measured: 4 beats 1 and 8)
 
 // Device control block: written by kernels, read back by the host between phases.
 struct Ctl {

@@ -1272,7 +1272,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
         weight = w2;
       }
       if (bcp_status s = device_scan<uint64_t, uint64_t>(weight, wprefix, (int64_t)n_tiles, ws, st)) return s;
-      hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes, key, bflags);
+      hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes * kSmallBatchTiles, key, bflags);
       BCP_HIP(hipGetLastError());
       if (bcp_status s = device_scan<uint32_t, uint32_t>(bflags, bflags, (int64_t)n_tiles, ws, st)) return s;
       hipLaunchKernelGGL(k_batch_starts, dim3(nblk), dim3(kBlock), 0, st, bflags, n_tiles, bstart);
