@@ -425,11 +425,15 @@ __device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __res
     gsrc_t s2 = s + (size_t)head * 4;
     gdst_t d2 = d + (size_t)head * 2;
     uint32_t g = tid;
-    for (; g + nt < groups; g += 2 * nt) {
-      const u32x4 a0 = ld<-16>(s2 + (size_t)g * 32), b0 = ld<-16>(s2 + (size_t)g * 32 + 16);
-      const u32x4 a1 = ld<-16>(s2 + (size_t)(g + nt) * 32), b1 = ld<-16>(s2 + (size_t)(g + nt) * 32 + 16);
-      st<16>(d2 + (size_t)g * 16, narrow8(a0, b0));
-      st<16>(d2 + (size_t)(g + nt) * 16, narrow8(a1, b1));
+    for (; g + 3 * nt < groups; g += 4 * nt) {  // four groups of a lane in flight: 128 bytes of loads
+      u32x4 a[4], b[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        a[u] = ld<-16>(s2 + (size_t)(g + u * nt) * 32);
+        b[u] = ld<-16>(s2 + (size_t)(g + u * nt) * 32 + 16);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) st<16>(d2 + (size_t)(g + u * nt) * 16, narrow8(a[u], b[u]));
     }
     for (; g < groups; g += nt) {
       const u32x4 a = ld<-16>(s2 + (size_t)g * 32), b = ld<-16>(s2 + (size_t)g * 32 + 16);
@@ -442,16 +446,34 @@ __device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __res
     const uint32_t gpr = n >> 3, total = nrows * gpr;  // groups per row
     uint32_t row = tid / gpr, col = tid - row * gpr;
     const uint32_t drow = nt / gpr, dcol = nt - drow * gpr;
-    for (uint32_t i = tid; i < total; i += nt) {
-      gsrc_t sr = s + (int64_t)row * sp + (size_t)col * 32;
-      const u32x4 a = ld<-16>(sr), b = ld<-16>(sr + 16);
-      st<16>(d + (int64_t)row * dp + (size_t)col * 16, narrow8(a, b));
+    auto advance = [&]() {
       col += dcol;
       row += drow;
       if (col >= gpr) {
         col -= gpr;
         ++row;
       }
+    };
+    uint32_t i = tid;
+    for (; i + 3 * nt < total; i += 4 * nt) {  // four groups of a lane in flight
+      u32x4 a[4], b[4];
+      int64_t dof[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        gsrc_t sr = s + (int64_t)row * sp + (size_t)col * 32;
+        dof[u] = (int64_t)row * dp + (int64_t)col * 16;
+        a[u] = ld<-16>(sr);
+        b[u] = ld<-16>(sr + 16);
+        advance();
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) st<16>(d + dof[u], narrow8(a[u], b[u]));
+    }
+    for (; i < total; i += nt) {
+      gsrc_t sr = s + (int64_t)row * sp + (size_t)col * 32;
+      const u32x4 a = ld<-16>(sr), b = ld<-16>(sr + 16);
+      st<16>(d + (int64_t)row * dp + (size_t)col * 16, narrow8(a, b));
+      advance();
     }
     return;
   }

@@ -103,6 +103,7 @@ struct Ctl {
   unsigned long long lds_transpose;  // LDS staging bytes the largest transposed tile needs
   unsigned long long src_bytes;      // bytes the copy reads (differs from payload_bytes when regions convert)
   unsigned long long n_convert;      // regions that convert
+  long long max_saved_rec_buf, max_target_rec_buf;  // largest buffer index any saved / target RECORD names (-1: none)
 };
 
 struct PlanConfig {

@@ -241,20 +241,37 @@ __device__ inline void report(Ctl* ctl, int64_t record, unsigned code) {
 
 __global__ __launch_bounds__(kBlock) void k_validate_count(const bcp_shard_meta* recs, int64_t n_saved,
                                                            int64_t n_total, uint32_t* nboxes, Ctl* ctl) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= n_total) return;
-  const bcp_shard_meta& r = recs[i];
-  const unsigned code = validate_record(r);
-  if (code) {
-    report(ctl, i, code);
-    nboxes[i] = 0;
-    return;
+  // largest saved FQN id and largest buffer indices of the block: one global atomic per block, not per record
+  __shared__ ull block_max;
+  __shared__ int block_sbuf, block_tbuf;
+  if (threadIdx.x == 0) {
+    block_max = 0;
+    block_sbuf = block_tbuf = -1;
   }
-  int64_t len[kDims];
-  const int n = local_shape(r, len);
-  const int nb = decompose_flat_range(len, n, r.flat_begin, r.flat_end, nullptr);
-  nboxes[i] = (uint32_t)nb;
-  if (i < n_saved && nb) atomicMax(&ctl->max_saved_fqn, (ull)r.fqn_id);
+  __syncthreads();
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n_total) {
+    const bcp_shard_meta& r = recs[i];
+    const unsigned code = validate_record(r);
+    if (code) {
+      report(ctl, i, code);
+      nboxes[i] = 0;
+    } else {
+      int64_t len[kDims];
+      const int n = local_shape(r, len);
+      const int nb = decompose_flat_range(len, n, r.flat_begin, r.flat_end, nullptr);
+      nboxes[i] = (uint32_t)nb;
+      if (i < n_saved && nb && block_max < (ull)r.fqn_id) atomicMax(&block_max, (ull)r.fqn_id);
+      int* bb = i < n_saved ? &block_sbuf : &block_tbuf;
+      if (*bb < r.buf) atomicMax(bb, r.buf);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (block_max) atomicMax(&ctl->max_saved_fqn, block_max);
+    if (block_sbuf >= 0) atomicMax(&ctl->max_saved_rec_buf, (long long)block_sbuf);
+    if (block_tbuf >= 0) atomicMax(&ctl->max_target_rec_buf, (long long)block_tbuf);
+  }
 }
 
 // The boxes of a block's records are consecutive in the output (box_start is a scan), so they are
@@ -441,6 +458,9 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   // were counted), which moves 4-byte source elements into 2-byte destination elements
   const int64_t e = s.itemsize, et = t.itemsize;
   const bool conv = e != et;
+  // a converting tile writes half of what it reads: twice the source bytes per tile keep the traffic per
+  // tile (and per queue pop, descriptor and barrier) near that of a plain copy
+  if (conv) tile_bytes *= 2;
   int64_t L[kDims], ss[kDims], ds[kDims];
   int m = 0;
   int64_t soff = 0, doff = 0, vol = 1;
@@ -517,7 +537,8 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
     R->tdim_b = tdb;
     uint64_t groups = 1;
     for (int k = 0; k < nd - 2; ++k) groups *= (uint64_t)R->len[k];
-    const uint64_t ta = ((uint64_t)L[a] + tda - 1) / tda, tb = ((uint64_t)L[b] + tdb - 1) / tdb;
+    // (the edges are powers of two)
+    const uint64_t ta = ((uint64_t)L[a] + tda - 1) >> (31 - __clz((int)tda)), tb = ((uint64_t)L[b] + tdb - 1) >> (31 - __clz((int)tdb));
     R->tiles_b = (uint32_t)(tb < 0xffffffffull ? tb : 0xffffffffull);
     const uint64_t tpg = ta * tb;
     R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
@@ -553,14 +574,15 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
     for (int k = 0; k < nd; ++k) misal |= (uint64_t)R->dpitch[k];
     R->lead_mod = (misal % kSegmentAlign) ? kSegmentAlign : 0;
     // (the lead-in is counted in source bytes: e / et of them per destination byte)
-    const uint64_t segs = ((uint64_t)R->run_bytes + (R->lead_mod ? kSegmentAlign * (uint64_t)(e / et) - 1 : 0) + tile_bytes - 1) / tile_bytes;
+    const uint64_t segs = ((uint64_t)R->run_bytes + (R->lead_mod ? kSegmentAlign * (uint64_t)(e / et) - 1 : 0) + tile_bytes - 1) >>
+                          (31 - __clz((int)tile_bytes));  // (the tile budget is a power of two)
     R->segs_per_row = (uint32_t)(segs < 0xffffffffull ? segs : 0xffffffffull);
     tpg = (segs >> 32 || L0 >> 31) ? ~0ull : L0 * segs;
   } else {
-    uint64_t rpt = tile_bytes / (uint64_t)R->run_bytes;
+    uint64_t rpt = tile_bytes / (uint32_t)R->run_bytes;  // (32-bit: the run is shorter than the budget here)
     if (rpt > L0) rpt = L0;
     R->rows_per_tile = (uint32_t)rpt;
-    tpg = (L0 + rpt - 1) / rpt;
+    tpg = (L0 >> 32) ? (L0 + rpt - 1) / rpt : (uint64_t)(((uint32_t)L0 + (uint32_t)rpt - 1) / (uint32_t)rpt);
   }
   R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
   R->n_tiles = (tpg >> 32 || groups >> 31) ? ~0ull : groups * tpg;
@@ -582,7 +604,8 @@ template <bool WRITE>
 __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs, int64_t nbt, const uint32_t* sidx,
                                                   const uint32_t* grp_lo, const uint64_t* pair_start, uint64_t n_pairs,
                                                   uint32_t* blk_cnt, const uint32_t* blk_off, uint32_t tile_bytes,
-                                                  Region* regions, uint64_t* tile_cnt, ull* cov, Ctl* ctl) {
+                                                  Region* regions, uint64_t* tile_cnt, ull* cov, Ctl* ctl, ull* ext,
+                                                  uint32_t ext_src_bufs, uint32_t ext_bufs, uint32_t ext_stripes) {
   __shared__ uint32_t wcnt[kBlock / 64];
   __shared__ BlockStats bs;
   // WRITE: the block's regions are put together in LDS and leave as one contiguous, coalesced copy
@@ -636,9 +659,19 @@ __global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs,
       atomicAdd(&bs.transposed, 1ull);
       atomicMax(&bs.lds_transpose, (ull)transpose_lds_bytes(R.tdim_a, R.tdim_b, (uint32_t)R.run_bytes));
     }
-    ull send = (ull)(R.src_base + R.run_bytes);
-    for (int k = 0; k < R.ndim; ++k) send += (ull)((R.len[k] - 1) * R.spitch[k]);
+    ull send = (ull)(R.src_base + R.run_bytes), dend = (ull)(R.dst_base + (R.kind == kConvert ? R.run_bytes / 2 : R.run_bytes));
+    for (int k = 0; k < R.ndim; ++k) {
+      send += (ull)((R.len[k] - 1) * R.spitch[k]);
+      dend += (ull)((R.len[k] - 1) * R.dpitch[k]);
+    }
     atomicMax(&bs.src_end, send);
+    // Per buffer, one past the highest byte the plan touches.  Millions of regions share a few hundred
+    // buffers: the table is kept in several copies (one per group of workgroups, folded afterwards), and
+    // most regions lie below what an earlier one has recorded (the values only grow, so a stale read
+    // costs an atomic, never a wrong maximum).
+    ull* e = ext + (size_t)(blockIdx.x % ext_stripes) * ext_bufs;
+    if (e[R.src_buf] < send) atomicMax(&e[R.src_buf], send);
+    if (e[ext_src_bufs + R.dst_buf] < dend) atomicMax(&e[ext_src_bufs + R.dst_buf], dend);
     atomicMax(&bs.max_src, (long long)R.src_buf);
     atomicMax(&bs.max_dst, (long long)R.dst_buf);
     if (R.n_tiles == ~0ull) report(ctl, 0, kErrInvalid);
@@ -700,8 +733,15 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
   if (R.kind == kTranspose) {
     for (int k = nd - 3; k >= 0; --k) {
       const uint64_t L = (uint64_t)R.len[k];
-      const uint64_t c = group % L;
-      group /= L;
+      uint64_t c;
+      if ((group | L) >> 32) {
+        c = group % L;
+        group /= L;
+      } else {  // 32-bit division is several times cheaper, and this is the common case
+        const uint32_t q = (uint32_t)group / (uint32_t)L;
+        c = (uint32_t)group - q * (uint32_t)L;
+        group = q;
+      }
       so += (int64_t)c * R.spitch[k];
       dof += (int64_t)c * R.dpitch[k];
     }
@@ -721,8 +761,15 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
   } else {
     for (int k = nd - 2; k >= 0; --k) {
       const uint64_t L = (uint64_t)R.len[k];
-      const uint64_t c = group % L;
-      group /= L;
+      uint64_t c;
+      if ((group | L) >> 32) {
+        c = group % L;
+        group /= L;
+      } else {
+        const uint32_t q = (uint32_t)group / (uint32_t)L;
+        c = (uint32_t)group - q * (uint32_t)L;
+        group = q;
+      }
       so += (int64_t)c * R.spitch[k];
       dof += (int64_t)c * R.dpitch[k];
     }
@@ -735,7 +782,7 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
       dof += (int64_t)row * dp;
       // segments are counted in source bytes; a converting region writes half as many
       const int64_t ratio = R.kind == kConvert ? 2 : 1;
-      int64_t lead = R.lead_mod ? dof % (int64_t)R.lead_mod : 0;
+      int64_t lead = R.lead_mod ? dof & (int64_t)(R.lead_mod - 1) : 0;  // (a power of two)
       if (ratio > 1) lead &= ~(int64_t)1;  // whole destination elements
       int64_t begin = (int64_t)seg * R.tile_bytes - lead * ratio, end = begin + (int64_t)R.tile_bytes;
       if (begin < 0) begin = 0;
@@ -863,20 +910,16 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const Region* regions, co
   }
 }
 
-// Per buffer, one past the highest byte the plan touches: ext[0 .. n_src) for the source blobs,
-// ext[n_src ..) for the destination buffers (zeroed before).
-__global__ __launch_bounds__(kBlock) void k_extents(const Region* __restrict__ regions, int64_t n_regions, uint32_t n_src,
-                                                    ull* ext) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= n_regions) return;
-  const Region& R = regions[i];
-  int64_t s_end = R.src_base + R.run_bytes, d_end = R.dst_base + (R.kind == kConvert ? R.run_bytes / 2 : R.run_bytes);
-  for (int k = 0; k < R.ndim; ++k) {
-    s_end += (R.len[k] - 1) * R.spitch[k];
-    d_end += (R.len[k] - 1) * R.dpitch[k];
+// fold the copies of the per-buffer extent table: ext[b] = max over the stripes
+__global__ __launch_bounds__(kBlock) void k_extents_fold(ull* ext, uint32_t n_bufs, uint32_t stripes) {
+  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
+  if (b >= n_bufs) return;
+  ull m = ext[b];
+  for (uint32_t s = 1; s < stripes; ++s) {
+    const ull v = ext[(size_t)s * n_bufs + b];
+    m = v > m ? v : m;
   }
-  atomicMax(&ext[R.src_buf], (ull)s_end);
-  atomicMax(&ext[n_src + R.dst_buf], (ull)d_end);
+  ext[b] = m;
 }
 
 bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
@@ -1044,6 +1087,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   Ctl init{};
   init.err_key = ~0ull;
   init.max_src_buf = init.max_dst_buf = -1;
+  init.max_saved_rec_buf = init.max_target_rec_buf = -1;
   out->ctl = init;
   if (n_target == 0) return BCP_OK;
   if (n_total > (int64_t)(0xffffffffu / kMaxBoxesPerRecord)) {  // box indices are 32-bit
@@ -1160,12 +1204,13 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   Region* regions = nullptr;
   uint64_t* tile_start = nullptr;
   uint32_t* blk = nullptr;
+  ull* ext = nullptr;  // per-buffer extents: [source blobs | destination buffers] by record buffer index
   unsigned nblk_pairs = 0;
   if (n_pairs > 0) {
     nblk_pairs = blocks_for((int64_t)n_pairs);
     BCP_HIP(ws.alloc(&blk, (size_t)nblk_pairs + 1));
     hipLaunchKernelGGL((k_pairs<false>), dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
-                       n_pairs, blk, blk, tile_bytes, (Region*)nullptr, (uint64_t*)nullptr, cov, ctl);
+                       n_pairs, blk, blk, tile_bytes, (Region*)nullptr, (uint64_t*)nullptr, cov, ctl, (ull*)nullptr, 0u, 0u, 1u);
     BCP_HIP(hipGetLastError());
     if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk_pairs, ws, st)) return s;
     size_t cap = (size_t)n_pairs;
@@ -1179,8 +1224,15 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     BCP_HIP(ws.alloc(&tile_start, cap + 1));
     // slots beyond the region count stay zero so that the scan below may run over `cap` entries
     BCP_HIP(hipMemsetAsync(tile_start, 0, sizeof(uint64_t) * (cap + 1), st));
+    // what each buffer must hold: a table over every buffer index the records name, in up to 64 copies
+    const uint32_t ext_src_bufs = (uint32_t)(h.max_saved_rec_buf + 1), ext_bufs = ext_src_bufs + (uint32_t)(h.max_target_rec_buf + 1);
+    const uint32_t ext_stripes = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(1, ((uint64_t)1 << 20) / std::max(ext_bufs, 1u)));
+    BCP_HIP(ws.alloc(&ext, (size_t)ext_bufs * ext_stripes));
+    BCP_HIP(hipMemsetAsync(ext, 0, sizeof(ull) * (size_t)ext_bufs * ext_stripes, st));
     hipLaunchKernelGGL((k_pairs<true>), dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
-                       n_pairs, blk, blk, tile_bytes, regions, tile_start, cov, ctl);
+                       n_pairs, blk, blk, tile_bytes, regions, tile_start, cov, ctl, ext, ext_src_bufs, ext_bufs, ext_stripes);
+    BCP_HIP(hipGetLastError());
+    hipLaunchKernelGGL(k_extents_fold, dim3(blocks_for(ext_bufs)), dim3(kBlock), 0, st, ext, ext_bufs, ext_stripes);
     BCP_HIP(hipGetLastError());
     hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
                        (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);
@@ -1279,17 +1331,13 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, regions, tile_region, tile_local, weight,
                          bflags, bstart, n_tiles, tiles, heads, key, out->dev.batch_key);
       BCP_HIP(hipGetLastError());
-      // what each buffer must hold: one past the highest byte touched, per source blob and destination buffer
+      // the extents of the buffers the plan uses come back with the batch count
       const size_t n_src = (size_t)(h.max_src_buf + 1), n_dst = (size_t)(h.max_dst_buf + 1);
-      ull* ext = nullptr;
-      BCP_HIP(ws.alloc(&ext, n_src + n_dst));
-      BCP_HIP(hipMemsetAsync(ext, 0, sizeof(ull) * (n_src + n_dst), st));
-      hipLaunchKernelGGL(k_extents, dim3(blocks_for(n_regions)), dim3(kBlock), 0, st, regions, (int64_t)n_regions,
-                         (uint32_t)n_src, ext);
-      BCP_HIP(hipGetLastError());
       BCP_HIP(ensure_landing(ws, kLandingExtents + sizeof(ull) * (n_src + n_dst)));  // (nothing is in flight into it)
       BCP_HIP(hipMemcpyAsync(ws.landing, bflags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-      BCP_HIP(hipMemcpyAsync((char*)ws.landing + kLandingExtents, ext, sizeof(ull) * (n_src + n_dst), hipMemcpyDeviceToHost, st));
+      BCP_HIP(hipMemcpyAsync((char*)ws.landing + kLandingExtents, ext, sizeof(ull) * n_src, hipMemcpyDeviceToHost, st));
+      BCP_HIP(hipMemcpyAsync((char*)ws.landing + kLandingExtents + sizeof(ull) * n_src, ext + ext_src_bufs, sizeof(ull) * n_dst,
+                             hipMemcpyDeviceToHost, st));
       out->src_extent.resize(n_src);
       out->dst_extent.resize(n_dst);
     }
