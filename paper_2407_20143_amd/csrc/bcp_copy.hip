@@ -343,17 +343,69 @@ __device__ __forceinline__ void transpose_full_tile(gsrc_t __restrict__ s, gdst_
   wave_lds_sync();  // the block's part of the staging area is free again
 }
 
+// A full 256 x 256 tile of 2-byte elements through the LDS transpose read of gfx950.  Every wave owns a
+// 64 x 64 block (8 KiB): it loads the block's 64 source rows as 16-byte vectors (eight rows of 128 bytes
+// per instruction), writes them to its part of the staging area as they are -- row b of the block at
+// b * kTr16Pitch, 128 bytes along a -- and reads them back with ds_read_b64_tr_b16, which hands lane l of
+// a group of sixteen lanes the elements M[l/4 + 4k][l%4], k = 0..3, of the 16 x 4 matrix whose row L is
+// the four elements at the address lane L gives.  Lane L of group g points at row
+// 32 (g & 1) + 8 (L & 3) + (L >> 2), columns a0 .. a0 + 3; lane l then holds column a0 + (l & 3), rows
+// 32 (g & 1) + 8 (l >> 2) + k: four elements consecutive along b.  A second read four rows further
+// completes a 16-byte vector, and a store instruction covers eight destination rows of 128 bytes.
+// Three LDS instructions per vector instead of sixteen, and no workgroup barrier.
+constexpr uint32_t kTr16Pitch = 144;  // 128 bytes of a row and 16 more: rows stay 16-byte aligned for the
+                                      // 16-byte writes; rows 16 apart share banks, which the reads can afford
+typedef short tr_v4i16 __attribute__((ext_vector_type(4)));
+typedef tr_v4i16 __attribute__((address_space(3))) * tr_lds_ptr;
+
+__device__ __forceinline__ void transpose_full_tile_b16(gsrc_t __restrict__ s, gdst_t __restrict__ d, int64_t spb,
+                                                        int64_t dpa, char* lds) {
+  constexpr uint32_t P = kTr16Pitch;
+  static_assert(transpose_edge_a(2) == 256 && transpose_edge_b(2) == 256 && kMaxThreads / 64 == 16, "4 x 4 blocks of 64 x 64");
+  uint32_t tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));  // opaque, see transpose_full_tile
+  const uint32_t lane = tid & 63u, w = tid >> 6;
+  const uint32_t a_w = (w & 3u) * 64u, b_w = (w >> 2) * 64u;
+  char* wl = lds + (size_t)w * (64u * P);
+  const uint32_t lo = lane & 7u, hi = lane >> 3;  // in: vector lo of rows hi + 8 j
+  gsrc_t sp = s + (size_t)(a_w + lo * 8u) * 2u + (int64_t)(b_w + hi) * spb;
+  const int64_t s_step = 8 * spb;
+  u32x4 v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = ld<16>(sp + j * s_step);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) lds_st<16>(wl + (size_t)(hi + 8u * j) * P + lo * 16u, v[j]);
+  wave_lds_sync();
+  const uint32_t g = lane >> 4, L = lane & 15u;
+  const char* rd = wl + (size_t)(32u * (g & 1u) + 8u * (L & 3u) + (L >> 2)) * P + 8u * (g >> 1);
+  gdst_t dp = d + (int64_t)(a_w + 4u * (g >> 1) + (L & 3u)) * dpa + (size_t)(b_w + (4u * (g & 1u) + (L >> 2)) * 8u) * 2u;
+  const int64_t d_step = 8 * dpa;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {  // destination rows a_w + 8 j .. + 7
+    const tr_v4i16 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_lds_ptr)(rd + 16u * j));
+    const tr_v4i16 y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_lds_ptr)(rd + 16u * j + 4u * P));
+    u32x4 out;
+    out[0] = (uint32_t)(uint16_t)x[0] | ((uint32_t)(uint16_t)x[1] << 16);
+    out[1] = (uint32_t)(uint16_t)x[2] | ((uint32_t)(uint16_t)x[3] << 16);
+    out[2] = (uint32_t)(uint16_t)y[0] | ((uint32_t)(uint16_t)y[1] << 16);
+    out[3] = (uint32_t)(uint16_t)y[2] | ((uint32_t)(uint16_t)y[3] << 16);
+    st<16>(dp + j * d_step, out);
+  }
+  wave_lds_sync();  // the block's part of the staging area is free again
+}
+
 template <int E>
 __device__ __forceinline__ void transpose_any(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t na, uint32_t nb,
                                               int64_t spb, int64_t dpa, uint32_t tda, uint32_t tdb, char* lds) {
   constexpr uint32_t VE = 16 / E;
   const uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)spb | (uintptr_t)dpa;
-  // Per-wave blocks pay off from 4-byte elements on; a 4 KiB block of smaller ones is only 64 or 32
-  // bytes long on its short side, and the workgroup-wide path moves those faster.
-  if constexpr (E >= 4) {
+  // Full tiles go block by block, a wave each; 1-byte elements (a 4 KiB block of them is only 64 bytes long
+  // on either side) and ragged tiles take the workgroup-wide paths.
+  if constexpr (E >= 2) {
     if ((al & 15u) == 0 && blockDim.x == kMaxThreads && tda == transpose_edge_a(E) && tdb == transpose_edge_b(E) &&
         na == tda && nb == tdb) {
-      transpose_full_tile<E>(s, d, spb, dpa, lds);
+      if constexpr (E == 2) transpose_full_tile_b16(s, d, spb, dpa, lds);
+      else transpose_full_tile<E>(s, d, spb, dpa, lds);
       return;
     }
   }

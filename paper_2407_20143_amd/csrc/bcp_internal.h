@@ -169,8 +169,10 @@ constexpr uint32_t transpose_edge_b(uint32_t esize) { return esize <= 2 ? 256u :
 // LDS staging of one tile: tdim_a rows (one per index along a) of tdim_b elements plus one
 // element of padding, which spreads a column over the banks
 constexpr uint32_t transpose_lds_bytes(uint32_t tdim_a, uint32_t tdim_b, uint32_t esize) {
-  return tdim_a * (tdim_b + 1) * esize;
+  // 2-byte elements: full tiles go through per-wave blocks, 16 x 64 rows of 144 bytes
+  return esize == 2 ? 16u * 64u * 144u : tdim_a * (tdim_b + 1) * esize;
 }
+static_assert(transpose_lds_bytes(256, 256, 2) >= 256 * 257 * 2, "also holds the workgroup-wide staging of a ragged 2-byte tile");
 bcp_status launch_reshard(const PlanDevice& plan, const void* const* src, int32_t n_src, void* const* dst,
                           int32_t n_dst, const void* table, hipStream_t stream,
                           const uint64_t* key_range = nullptr);
