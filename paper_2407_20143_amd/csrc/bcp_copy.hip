@@ -430,17 +430,27 @@ __device__ __forceinline__ void copy_rows_unaligned(gsrc_t __restrict__ s, gdst_
 }
 
 // ---- dtype-converting rows: binary32 -> bfloat16 -----------------------------------------------------
-// Round to nearest, ties to even (IEEE 754 roundTiesToEven) on the bit pattern: bfloat16 is the upper
-// half of binary32, so adding 0x7FFF plus the lowest kept bit carries into the kept half exactly when
-// the dropped half is above one half, or equal to it with an odd kept half.  The carry may run on
-// into the exponent, which is the right result there too (the next binade, or infinity).  Infinity has
-// a zero lower half and stays.  NaN stays NaN: sign and the upper seven fraction bits kept, quiet.
+// Round to nearest, ties to even (IEEE 754 roundTiesToEven); infinities stay; NaN stays NaN with its
+// sign and upper seven fraction bits, quiet; subnormal results are kept.  Pairs go through the packed
+// conversion instruction of gfx950 (v_cvt_pk_bf16_f32), which does exactly that; single elements at the
+// ends of a run use the same rounding on the bit pattern: bfloat16 is the upper half of binary32, so
+// adding 0x7FFF plus the lowest kept bit carries into the kept half exactly when the dropped half is
+// above one half, or equal to it with an odd kept half (and the carry may run on into the exponent,
+// which is the right result there too: the next binade, or infinity).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t narrow_bf16(uint32_t u) {
   const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
   const uint32_t nan = (u >> 16) | 0x40u;
-  return (u & 0x7fffffffu) > 0x7f800000u ? nan : rounded;
+  return ((u & 0x7fffffffu) > 0x7f800000u ? nan : rounded) & 0xffffu;
 }
-__device__ __forceinline__ uint32_t narrow_pair(uint32_t lo, uint32_t hi) { return narrow_bf16(lo) | (narrow_bf16(hi) << 16); }
+__device__ __forceinline__ uint32_t narrow_pair(uint32_t lo, uint32_t hi) {
+  const f32x2 x = {__uint_as_float(lo), __uint_as_float(hi)};
+  const bf16x2 y = __builtin_convertvector(x, bf16x2);
+  uint32_t packed;
+  __builtin_memcpy(&packed, &y, 4);
+  return packed;
+}
 __device__ __forceinline__ u32x4 narrow8(const u32x4& a, const u32x4& b) {
   return u32x4{narrow_pair(a[0], a[1]), narrow_pair(a[2], a[3]), narrow_pair(b[0], b[1]), narrow_pair(b[2], b[3])};
 }
