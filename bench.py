@@ -27,8 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188957815080,
-             "csrc_sha256": "de827ba0a641db173fe77517a7b1f40fc091464baf0292aad476d436ca8d2df2"},
+    "cfg3": {"bytes_per_launch": 188956848557,
+             "csrc_sha256": "a69336922f9ccbd31a75c0b7afa80f4fbd18ebe44992c1b0a91c1a690fc31fbd"},
+    "eval_load": {"bytes_per_launch": 41235714452,
+             "csrc_sha256": "a69336922f9ccbd31a75c0b7afa80f4fbd18ebe44992c1b0a91c1a690fc31fbd"},
+    "cfg5_small": {"bytes_per_launch": 1878083811,
+             "csrc_sha256": "a69336922f9ccbd31a75c0b7afa80f4fbd18ebe44992c1b0a91c1a690fc31fbd"},
 }
 
 
@@ -207,7 +211,17 @@ def count_mismatches(a, b) -> int:
     return bad
 
 
-def verify_result(case, src, dst, stream, reshard_once, generated: bool):
+def host_generated_fqns(workload: str, case):
+    """Tensors whose values are generated on the host (torch's CPU and GPU generators give different streams, so
+    the check below has to build every tensor where its input was built): the 100k small tensors of configuration
+    5 -- one by one on the GPU they would take minutes; everything else is generated on the GPU."""
+    import math
+    if workload not in ("cfg5", "cfg5_small"):
+        return set()
+    return {f for f, spec in case.tensors.items() if math.prod(spec.shape) <= (1 << 20)}
+
+
+def verify_result(case, src, dst, stream, reshard_once, generated: bool, on_host=frozenset()):
     """After the timed loop, outside it: the destination buffers are poisoned, one more reshard runs, and its
     result is compared on the device with the library-slicing closed form (synth.materialize of the TARGET
     layout), unit by unit: a flat buffer's slices together, otherwise one destination buffer at a time.
@@ -226,8 +240,9 @@ def verify_result(case, src, dst, stream, reshard_once, generated: bool):
     for sh in case.target.shards:
         (groups.setdefault(sh.group, []) if sh.group >= 0 else plain.setdefault(sh.buf, [])).append(sh)
     for b, shards in plain.items():
-        # (buffers of tiny tensors are built on the host: 100k tensors one by one on the GPU take minutes)
-        dev = "cuda" if any(sh.numel > (1 << 20) for sh in shards) else "cpu"
+        where = {sh.parts[0].fqn in on_host for sh in shards}
+        assert len(where) == 1, "a destination buffer mixes host-generated and GPU-generated tensors"
+        dev = "cpu" if where.pop() else "cuda"
         want = synth.materialize(synth.Layout(shards, case.target.buf_bytes), case.tensors, case.seed, device=dev,
                                  poison=POISON, only_bufs={b})[b]
         bad += count_mismatches(dst[b], want.to(dst[b].device))
@@ -291,6 +306,33 @@ def from_host_leg(binding, saved_meta, target_meta, src, dst, chunk_bytes, paylo
     return out
 
 
+def dedup_timing():
+    """Save side (Sec. 4.1 'Balancing saving workload'): bcp_dedup_worst_fit on the live layout of the 7B model with
+    four states under TP4 PP2 and 16 data-parallel replicas -- a host routine, no GPU involved."""
+    import numpy as np
+    from paper_2407_20143_amd import binding, synth
+    model = synth.llama_tensors(32, 4096, 11008, 32000)
+    live, rank_of = synth.replicated_live_layout(model, synth.CFG3_STATES, 32, 4, 2, 16)
+    meta = binding.layout_to_meta(live, pinned=False)
+    ts = []
+    for _ in range(5):
+        t0 = time.perf_counter()
+        keep, load = binding.dedup_worst_fit(meta, rank_of, 4 * 2 * 16)
+        ts.append((time.perf_counter() - t0) * 1e3)
+    return {"metric": "bcp_dedup_worst_fit wall time", "value": round(min(ts), 3), "unit": "ms", "records": len(meta),
+            "distinct_shards": int(keep.sum()), "ranks": 128, "max_over_mean_load": round(float(load.max() / load.mean()), 4),
+            "host": host_description()}
+
+
+def memfloor():
+    """Run the stand-alone memory-floor measurement (bench_memfloor.hip, built by __graft_entry__.build)."""
+    import subprocess
+    exe = os.path.join(ROOT, "bench_memfloor")
+    if not os.path.exists(exe):
+        raise SystemExit("bench_memfloor is not built: run python -c 'import __graft_entry__ as g; g.build()' first")
+    return subprocess.call([exe])
+
+
 def note(msg: str):
     """Progress line on stderr (stdout carries only the JSON result)."""
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
@@ -323,7 +365,16 @@ def main():
                          "size, whose FETCH_SIZE / WRITE_SIZE readings give the scale of those counters")
     ap.add_argument("--reshard-only", action="store_true",
                     help="extra timing loop of bcp_reshard alone on a prebuilt plan (reported beside the step numbers)")
+    ap.add_argument("--dedup-only", action="store_true",
+                    help="time the save-side Worst-Fit deduplication (host routine) on the 7B live layout and exit")
+    ap.add_argument("--memfloor", action="store_true",
+                    help="run the stand-alone small-tile memory-floor measurement (bench_memfloor.hip) and exit")
     args = ap.parse_args()
+    if args.dedup_only:
+        print(json.dumps(dedup_timing()), flush=True)
+        return
+    if args.memfloor:
+        raise SystemExit(memfloor())
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the reshard path has no multi-GPU part (run with --gpus 1)")
 
@@ -339,15 +390,16 @@ def main():
     case, desc = build_case(args.workload)
     note(f"workload {args.workload}: generating inputs on the GPU")
     t0 = time.perf_counter()
+    on_host = host_generated_fqns(args.workload, case)
     if args.raw_inputs:
         src = [torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda") for n in case.saved.buf_bytes]
-    elif args.workload in ("cfg5", "cfg5_small"):
-        # (100k tiny tensors one by one on the GPU take minutes: they are generated on the host, the experts on the GPU)
-        big = {sh.buf for sh in case.saved.shards if sh.numel > (1 << 20)}
-        small_layout = synth.Layout([sh for sh in case.saved.shards if sh.buf not in big], case.saved.buf_bytes)
-        big_layout = synth.Layout([sh for sh in case.saved.shards if sh.buf in big], case.saved.buf_bytes)
-        src = synth.materialize(big_layout, case.tensors, case.seed, device="cuda", only_bufs=big)
-        host = synth.materialize(small_layout, case.tensors, case.seed, only_bufs=set(range(len(src))) - big)
+    elif on_host:
+        small_layout = synth.Layout([sh for sh in case.saved.shards if sh.parts[0].fqn in on_host], case.saved.buf_bytes)
+        big_layout = synth.Layout([sh for sh in case.saved.shards if sh.parts[0].fqn not in on_host], case.saved.buf_bytes)
+        small_bufs = {sh.buf for sh in small_layout.shards}
+        assert not small_bufs & {sh.buf for sh in big_layout.shards}, "a blob mixes host-generated and GPU-generated tensors"
+        src = synth.materialize(big_layout, case.tensors, case.seed, device="cuda", only_bufs=set(range(len(case.saved.buf_bytes))) - small_bufs)
+        host = synth.materialize(small_layout, case.tensors, case.seed, only_bufs=small_bufs)
         src = [s if s is not None else h.cuda() for s, h in zip(src, host)]
         del host
     else:
@@ -423,7 +475,7 @@ def main():
 
     note(f"timed: {ms_per_step:.3f} ms per step; verification and ceiling copies")
     verified = verify_result(case, src, dst, stream,
-                             lambda: binding.reshard(p, src, dst, stream=stream), not args.raw_inputs)
+                             lambda: binding.reshard(p, src, dst, stream=stream), not args.raw_inputs, on_host)
     extra = {}
     if args.reshard_only:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -438,8 +490,11 @@ def main():
         extra["from_host"] = from_host_leg(binding, saved_meta, target_meta, src, dst, args.from_host << 20, payload)
 
     # Beside the result: (1) the practical ceiling -- one plain contiguous copy, as large as the buffers at hand
-    # allow (at most 8 GiB), through the same plan / k_reshard path: what the kernel reaches when there is nothing
-    # to reshard; (2) the runtime's own device-to-device copy of the same bytes, for scale.
+    # allow (at most 8 GiB), through the same plan and copy-kernel body: what the kernel reaches when there is
+    # nothing to reshard.  It is launched through bcp_reshard_noalloc, whose kernel instance takes the buffer
+    # pointers from a table (k_reshard_table): same body, another name, so that a kernel trace of this run keeps
+    # the workload's launches (k_reshard) apart from these; (2) the runtime's own device-to-device copy of the
+    # same bytes, for scale.
     n_copy = min(max(b.numel() for b in src), max(b.numel() for b in dst), 8 << 30) // 256 * 256
     big_s = max(src, key=lambda b: b.numel())
     big_d = max(dst, key=lambda b: b.numel())
@@ -455,7 +510,7 @@ def main():
     elif n_copy >= 1 << 20:
         cc = synth.copy_case(n_copy)
         cp = binding.plan(binding.layout_to_meta(cc.saved), binding.layout_to_meta(cc.target), stream=stream)
-        for name, fn, out in (("copy_through_k_reshard", lambda: binding.reshard(cp, [big_s], [big_d], stream=stream), ceil),
+        for name, fn, out in (("copy_through_k_reshard", lambda: binding.reshard_noalloc(cp, [big_s], [big_d], stream=stream), ceil),
                               ("runtime_memcpy_DtoD", lambda: big_d[:n_copy].copy_(big_s[:n_copy]), naive)):
             fn()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
