@@ -239,19 +239,62 @@ __device__ inline void report(Ctl* ctl, int64_t record, unsigned code) {
   atomicMin(&ctl->err_key, ((ull)record << 8) | code);
 }
 
-__global__ __launch_bounds__(kBlock) void k_validate_count(const bcp_shard_meta* recs, int64_t n_saved,
-                                                           int64_t n_total, uint32_t* nboxes, Ctl* ctl) {
+// The plan's counters and maxima are one small struct, and an atomic on one cache line takes the L2 some
+// nanoseconds whoever asks: tens of thousands of workgroups that each add their sums to the same line
+// wait for each other longer than they compute.  So the struct exists kCtlStripes + 1 times, 256 bytes
+// apart: workgroups add to the copy their index selects, and k_readback folds the copies into the first
+// one (and clears them) before the host looks at it.  Errors are rare and go to the first copy directly.
+constexpr uint32_t kCtlStripes = 256;
+struct alignas(256) CtlStripe {
+  Ctl c;
+};
+__device__ inline Ctl* ctl_stripe(Ctl* ctl) {
+  return &(reinterpret_cast<CtlStripe*>(ctl) + 1 + blockIdx.x % kCtlStripes)->c;
+}
+
+__global__ __launch_bounds__(kBlock) void k_ctl_init(Ctl* ctl, Ctl init) {
+  for (uint32_t i = threadIdx.x; i <= kCtlStripes; i += kBlock) reinterpret_cast<CtlStripe*>(ctl)[i].c = init;
+}
+
+// A record is 304 bytes, and a wave whose lanes each read their own record asks for 64 cache lines with
+// every load instruction, most of them several times over.  So the records of a workgroup (they are
+// consecutive) come into LDS as one coalesced copy, 16 bytes per lane and instruction, and are looked at there.
+constexpr int kRecChunks = (int)(sizeof(bcp_shard_meta) / 16);
+static_assert(sizeof(bcp_shard_meta) % 16 == 0, "records are staged in 16-byte pieces");
+constexpr int kRecBlock = 128;  // records (threads) per workgroup of the kernels that stage records
+
+__device__ inline void stage_records(const bcp_shard_meta* recs, int64_t rec0, int count, uint4* lds) {
+  const uint4* from = reinterpret_cast<const uint4*>(recs + rec0);
+  const int chunks = count * kRecChunks;
+  uint4 v[kRecChunks];
+#pragma unroll
+  for (int j = 0; j < kRecChunks; ++j) {
+    const int i = j * kRecBlock + (int)threadIdx.x;
+    v[j] = from[i < chunks ? i : chunks - 1];  // (count >= 1; the copies of the last piece are not stored)
+  }
+#pragma unroll
+  for (int j = 0; j < kRecChunks; ++j) {
+    const int i = j * kRecBlock + (int)threadIdx.x;
+    if (i < chunks) lds[i] = v[j];
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kRecBlock) void k_validate_count(const bcp_shard_meta* recs, int64_t n_saved,
+                                                              int64_t n_total, uint32_t* nboxes, Ctl* ctl) {
   // largest saved FQN id and largest buffer indices of the block: one global atomic per block, not per record
   __shared__ ull block_max;
   __shared__ int block_sbuf, block_tbuf;
+  __shared__ uint4 staged[kRecBlock * kRecChunks];
   if (threadIdx.x == 0) {
     block_max = 0;
     block_sbuf = block_tbuf = -1;
   }
-  __syncthreads();
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t rec0 = (int64_t)blockIdx.x * kRecBlock;
+  stage_records(recs, rec0, (int)(n_total - rec0 < kRecBlock ? n_total - rec0 : kRecBlock), staged);
+  const int64_t i = rec0 + threadIdx.x;
   if (i < n_total) {
-    const bcp_shard_meta& r = recs[i];
+    const bcp_shard_meta& r = reinterpret_cast<const bcp_shard_meta*>(staged)[threadIdx.x];
     const unsigned code = validate_record(r);
     if (code) {
       report(ctl, i, code);
@@ -268,9 +311,10 @@ __global__ __launch_bounds__(kBlock) void k_validate_count(const bcp_shard_meta*
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    if (block_max) atomicMax(&ctl->max_saved_fqn, block_max);
-    if (block_sbuf >= 0) atomicMax(&ctl->max_saved_rec_buf, (long long)block_sbuf);
-    if (block_tbuf >= 0) atomicMax(&ctl->max_target_rec_buf, (long long)block_tbuf);
+    Ctl* part = ctl_stripe(ctl);
+    if (block_max) atomicMax(&part->max_saved_fqn, block_max);
+    if (block_sbuf >= 0) atomicMax(&part->max_saved_rec_buf, (long long)block_sbuf);
+    if (block_tbuf >= 0) atomicMax(&part->max_target_rec_buf, (long long)block_tbuf);
   }
 }
 
@@ -451,6 +495,10 @@ __global__ __launch_bounds__(kBlock) void k_saved_check(const Box* boxes, int64_
 }
 
 // ---- step 4: intersect, compact, normalise, tile ------------------------------------------------
+// The dimensions of the intersection are merged where both sides are contiguous across them.  The list of
+// merged dimensions is written straight into R (lengths, and strides in elements for the moment) while the
+// one being merged into stays in registers: the index of the next free slot depends on the data, and an
+// array in registers indexed that way costs a chain of selects per access, which R, in LDS or memory, does not.
 __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_bytes, Region* R, int64_t* volume) {
   const int n = t.ndim;
   if (s.ndim != n) return false;  // reported as a shape mismatch elsewhere
@@ -461,28 +509,47 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   // a converting tile writes half of what it reads: twice the source bytes per tile keep the traffic per
   // tile (and per queue pop, descriptor and barrier) near that of a plain copy
   if (conv) tile_bytes *= 2;
-  int64_t L[kDims], ss[kDims], ds[kDims];
-  int m = 0;
+  if (R) {
+    for (int k = 0; k < kDims; ++k) {
+      R->len[k] = 1;
+      R->spitch[k] = 0;
+      R->dpitch[k] = 0;
+    }
+  }
+  int m = 0;                        // merged dimensions already in R
+  int64_t oL = 1, oS = 0, oD = 0;  // the merged dimension still open (length, element strides), if any
+  bool open = false;
   int64_t soff = 0, doff = 0, vol = 1;
-  for (int k = 0; k < n; ++k) {
+#pragma unroll
+  for (int k = 0; k < kDims; ++k) {
+    if (k >= n) break;
     const int64_t lo = s.off[k] > t.off[k] ? s.off[k] : t.off[k];
     const int64_t hs = s.off[k] + s.len[k], ht = t.off[k] + t.len[k];
     const int64_t hi = hs < ht ? hs : ht;
     if (lo >= hi) return false;
-    soff += (lo - s.off[k]) * s.stride[k];
-    doff += (lo - t.off[k]) * t.stride[k];
+    const int64_t sk = s.stride[k], tk = t.stride[k];
+    soff += (lo - s.off[k]) * sk;
+    doff += (lo - t.off[k]) * tk;
     const int64_t len = hi - lo;
     vol *= len;
     if (len == 1) continue;  // unit dimensions carry no stride
-    if (m > 0 && ss[m - 1] == len * s.stride[k] && ds[m - 1] == len * t.stride[k]) {
-      L[m - 1] *= len;  // contiguous with the previous dimension on both sides: merge
-      ss[m - 1] = s.stride[k];
-      ds[m - 1] = t.stride[k];
+    if (open && oS == len * sk && oD == len * tk) {
+      oL *= len;  // contiguous with the previous dimension on both sides: merge
+      oS = sk;
+      oD = tk;
     } else {
-      L[m] = len;
-      ss[m] = s.stride[k];
-      ds[m] = t.stride[k];
-      ++m;
+      if (open) {
+        if (R) {
+          R->len[m] = oL;
+          R->spitch[m] = oS;
+          R->dpitch[m] = oD;
+        }
+        ++m;
+      }
+      oL = len;
+      oS = sk;
+      oD = tk;
+      open = true;
     }
   }
   if (!R) return true;
@@ -500,86 +567,86 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   R->tdim_b = 0;
   R->tiles_b = 0;
   R->lead_mod = 0;
-  for (int k = 0; k < kDims; ++k) {
-    R->len[k] = 1;
-    R->spitch[k] = 0;
-    R->dpitch[k] = 0;
-  }
-  int a = -1, b = -1;
-  if (m > 0 && !(ss[m - 1] == 1 && ds[m - 1] == 1)) {
+  int nd = m;  // row dimensions
+  int64_t run_bytes = e;
+  if (open && oS == 1 && oD == 1) {
+    run_bytes = oL * e;  // the innermost dimension is contiguous on both sides: it is the run
+  } else if (open) {
+    R->len[m] = oL;
+    R->spitch[m] = oS;
+    R->dpitch[m] = oD;
+    nd = ++m;
+    int a = -1, b = -1;
     for (int k = 0; k < m; ++k) {
-      if (ss[k] == 1) a = k;
-      if (ds[k] == 1) b = k;
+      if (R->spitch[k] == 1) a = k;
+      if (R->dpitch[k] == 1) b = k;
     }
-  }
-  if (!conv && a >= 0 && b >= 0 && a != b && L[a] >= 4 && L[b] >= 4) {
-    // source-contiguous and destination-contiguous dimensions differ: LDS-staged transpose
-    R->kind = kTranspose;
-    R->run_bytes = e;
-    int nd = 0;
-    for (int k = 0; k < m; ++k) {
-      if (k == a || k == b) continue;
-      R->len[nd] = L[k];
-      R->spitch[nd] = ss[k] * e;
-      R->dpitch[nd] = ds[k] * e;
-      ++nd;
+    if (!conv && a >= 0 && b >= 0 && a != b && R->len[a] >= 4 && R->len[b] >= 4) {
+      // source-contiguous and destination-contiguous dimensions differ: LDS-staged transpose; the other
+      // dimensions keep their order, then come the source-contiguous and the destination-contiguous one
+      R->kind = kTranspose;
+      R->run_bytes = e;
+      const int64_t La = R->len[a], Sa = R->spitch[a], Da = R->dpitch[a];
+      const int64_t Lb = R->len[b], Sb = R->spitch[b], Db = R->dpitch[b];
+      int rest = 0;
+      uint64_t groups = 1;
+      for (int k = 0; k < m; ++k) {
+        if (k == a || k == b) continue;
+        const int64_t L = R->len[k];
+        groups *= (uint64_t)L;
+        R->len[rest] = L;
+        R->spitch[rest] = R->spitch[k] * e;
+        R->dpitch[rest] = R->dpitch[k] * e;
+        ++rest;
+      }
+      R->len[rest] = La;
+      R->spitch[rest] = Sa * e;
+      R->dpitch[rest] = Da * e;
+      R->len[rest + 1] = Lb;
+      R->spitch[rest + 1] = Sb * e;
+      R->dpitch[rest + 1] = Db * e;
+      R->ndim = m;
+      const uint32_t tda = transpose_edge_a((uint32_t)e), tdb = transpose_edge_b((uint32_t)e);
+      R->tdim_a = tda;
+      R->tdim_b = tdb;
+      // (the edges are powers of two)
+      const uint64_t ta = ((uint64_t)La + tda - 1) >> (31 - __clz((int)tda)), tb = ((uint64_t)Lb + tdb - 1) >> (31 - __clz((int)tdb));
+      R->tiles_b = (uint32_t)(tb < 0xffffffffull ? tb : 0xffffffffull);
+      const uint64_t tpg = ta * tb;
+      R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
+      R->n_tiles = (tpg >> 32 || groups >> 31) ? ~0ull : groups * tpg;
+      return true;
     }
-    const int order[2] = {a, b};
-    for (int q = 0; q < 2; ++q) {
-      R->len[nd] = L[order[q]];
-      R->spitch[nd] = ss[order[q]] * e;
-      R->dpitch[nd] = ds[order[q]] * e;
-      ++nd;
-    }
-    R->ndim = nd;
-    const uint32_t tda = transpose_edge_a((uint32_t)e), tdb = transpose_edge_b((uint32_t)e);
-    R->tdim_a = tda;
-    R->tdim_b = tdb;
-    uint64_t groups = 1;
-    for (int k = 0; k < nd - 2; ++k) groups *= (uint64_t)R->len[k];
-    // (the edges are powers of two)
-    const uint64_t ta = ((uint64_t)L[a] + tda - 1) >> (31 - __clz((int)tda)), tb = ((uint64_t)L[b] + tdb - 1) >> (31 - __clz((int)tdb));
-    R->tiles_b = (uint32_t)(tb < 0xffffffffull ? tb : 0xffffffffull);
-    const uint64_t tpg = ta * tb;
-    R->tiles_per_group = (uint32_t)(tpg < 0xffffffffull ? tpg : 0xffffffffull);
-    R->n_tiles = (tpg >> 32 || groups >> 31) ? ~0ull : groups * tpg;
-    return true;
   }
   R->kind = conv ? kConvert : kRows;
-  int nd;
-  if (m > 0 && ss[m - 1] == 1 && ds[m - 1] == 1) {
-    R->run_bytes = L[m - 1] * e;
-    nd = m - 1;
-  } else {
-    R->run_bytes = e;
-    nd = m;
-  }
-  for (int k = 0; k < nd; ++k) {
-    R->len[k] = L[k];
-    R->spitch[k] = ss[k] * e;
-    R->dpitch[k] = ds[k] * et;
-  }
+  R->run_bytes = run_bytes;
   R->ndim = nd;
-  const uint64_t L0 = nd > 0 ? (uint64_t)L[nd - 1] : 1;
-  uint64_t groups = 1;
-  for (int k = 0; k < nd - 1; ++k) groups *= (uint64_t)L[k];
+  uint64_t misal = (uint64_t)(t.byte_base + doff * et);
+  uint64_t groups = 1, L0 = 1;
+  for (int k = 0; k < nd; ++k) {
+    groups *= L0;  // (all but the last row dimension)
+    L0 = (uint64_t)R->len[k];
+    R->spitch[k] *= e;
+    const int64_t dp = R->dpitch[k] * et;
+    R->dpitch[k] = dp;
+    misal |= (uint64_t)dp;
+  }
   uint64_t tpg;
-  if ((uint64_t)R->run_bytes >= tile_bytes) {
+  if ((uint64_t)run_bytes >= tile_bytes) {
     // Two workgroups writing parts of one cache line cost bandwidth, so segments of a long row are
     // cut where the destination offset is a multiple of kSegmentAlign (buffers themselves are
     // assumed at least that aligned).  Rows whose destination starts are aligned anyway need no
     // lead-in; otherwise the first segment of a row is shorter and one more segment (possibly
     // empty) is reserved per row.
-    uint64_t misal = (uint64_t)R->dst_base;
-    for (int k = 0; k < nd; ++k) misal |= (uint64_t)R->dpitch[k];
-    R->lead_mod = (misal % kSegmentAlign) ? kSegmentAlign : 0;
+    const uint32_t lead_mod = (misal % kSegmentAlign) ? kSegmentAlign : 0;
+    R->lead_mod = lead_mod;
     // (the lead-in is counted in source bytes: e / et of them per destination byte)
-    const uint64_t segs = ((uint64_t)R->run_bytes + (R->lead_mod ? kSegmentAlign * (uint64_t)(e / et) - 1 : 0) + tile_bytes - 1) >>
+    const uint64_t segs = ((uint64_t)run_bytes + (lead_mod ? kSegmentAlign * (uint64_t)(e / et) - 1 : 0) + tile_bytes - 1) >>
                           (31 - __clz((int)tile_bytes));  // (the tile budget is a power of two)
     R->segs_per_row = (uint32_t)(segs < 0xffffffffull ? segs : 0xffffffffull);
     tpg = (segs >> 32 || L0 >> 31) ? ~0ull : L0 * segs;
   } else {
-    uint64_t rpt = tile_bytes / (uint32_t)R->run_bytes;  // (32-bit: the run is shorter than the budget here)
+    uint64_t rpt = tile_bytes / (uint32_t)run_bytes;  // (32-bit: the run is shorter than the budget here)
     if (rpt > L0) rpt = L0;
     R->rows_per_tile = (uint32_t)rpt;
     tpg = (L0 >> 32) ? (L0 + rpt - 1) / rpt : (uint64_t)(((uint32_t)L0 + (uint32_t)rpt - 1) / (uint32_t)rpt);
@@ -589,116 +656,251 @@ __device__ inline bool build_region(const Box& s, const Box& t, uint32_t tile_by
   return true;
 }
 
+// Index of the first element of the ascending array a[0..n) that is greater than v, found by a whole wave:
+// every step probes 64 evenly spaced elements at once, so an array of a million entries takes four
+// dependent loads where a binary search takes twenty.  All 64 lanes call it with the same arguments.
+__device__ inline int64_t wave_upper_bound_u64(const uint64_t* a, int64_t n, uint64_t v) {
+  int64_t lo = 0, hi = n;  // the answer lies in [lo, hi]
+  while (hi - lo > 64) {
+    const int64_t step = (hi - lo + 63) >> 6;
+    const int64_t i = lo + (int64_t)(lane_id() + 1) * step - 1;  // last element of the lane's slice
+    const bool le = i < hi && a[i] <= v;
+    const int c = __popcll(__ballot(le));  // (ascending: the lanes that say yes are the first c)
+    lo += (int64_t)c * step;
+    const int64_t end = lo + step - 1;  // the slice's last element is known to be greater
+    if (end < hi) hi = end;
+  }
+  const int64_t i = lo + (int64_t)lane_id();
+  const bool le = i < hi && a[i] <= v;
+  return lo + __popcll(__ballot(le));
+}
+
+// Items numbered through consecutive segments (start[0..n] is the running count of items, ascending, with
+// start[0] == 0 and start[n] == n_items), one workgroup of kBlock threads per kBlock consecutive items:
+// the segment that holds this thread's item p0 + threadIdx.x, and the number of the segment's first item.
+// A search per thread through the whole of start[] is a chain of some twenty dependent loads and nothing
+// else, so: the block's first and last item are looked up by one wave each (wave_upper_bound_u64); the
+// items in between belong to the segments in between, whose starts come into LDS in one load and are searched
+// there.  Every thread of the block must call it (it synchronises); threads without an item (p >= n_items)
+// get segment -1.
+struct BlockSegments {
+  uint64_t start[kBlock + 1];
+  int64_t range[2];
+};
+__device__ inline int64_t locate_in_block(const uint64_t* start, int64_t n, uint64_t n_items, BlockSegments& lds,
+                                          uint64_t* seg_first) {
+  const uint64_t p0 = (uint64_t)blockIdx.x * kBlock;
+  const uint64_t p = p0 + threadIdx.x;
+  if (p0 >= n_items) return -1;  // (a block past the last item: the same for all its threads)
+  const unsigned w = threadIdx.x >> 6;
+  if (w == 0 || w == kBlock / 64 - 1) {
+    const uint64_t q = w == 0 ? p0 : (p0 + kBlock - 1 < n_items ? p0 + kBlock - 1 : n_items - 1);
+    // segment whose range contains q: last t with start[t] <= q
+    const int64_t t = wave_upper_bound_u64(start, n + 1, q) - 1;
+    if (lane_id() == 0) lds.range[w ? 1 : 0] = t;
+  }
+  __syncthreads();
+  const int64_t t0 = lds.range[0];
+  const int64_t span = lds.range[1] - t0 + 1;  // segments of this block (empty ones included)
+  const bool staged = span <= kBlock;
+  if (staged) {
+    for (int64_t i = threadIdx.x; i <= span; i += kBlock) lds.start[i] = start[t0 + i];
+    __syncthreads();
+  }
+  if (p >= n_items) return -1;
+  if (staged) {
+    int lo = 0, hi = (int)span + 1;  // first index with lds.start[i] > p
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (lds.start[mid] <= p) lo = mid + 1; else hi = mid;
+    }
+    *seg_first = lds.start[lo - 1];
+    return t0 + lo - 1;
+  }
+  const int64_t t = t0 + upper_bound_u64(start + t0, span, p) - 1;
+  *seg_first = start[t];
+  return t;
+}
+
+// Candidate pairs are numbered target box by target box (pair_start is the running count), the pairs of one
+// target in the FQN-sorted order of the saved boxes.  Pass 1, one thread per candidate: find the pair's two
+// boxes, test whether they intersect, and write the block's hits -- (saved box, target box) -- densely
+// at the start of the block's own 256 slots of `hits`, with their number in blk_cnt.  The order inside a
+// block (rank from wave ballots and a prefix over the block's waves) is the order of the pairs, so the
+// region list that pass 2 writes from these lists is ordered by (target box, saved box) and reproducible.
+__global__ __launch_bounds__(kBlock) void k_pairs_find(const Box* boxes, int64_t nbs, int64_t nbt, const uint32_t* sidx,
+                                                       const uint32_t* grp_lo, const uint64_t* pair_start,
+                                                       uint64_t n_pairs, uint32_t* blk_cnt, uint2* hits) {
+  __shared__ uint32_t wcnt[kBlock / 64];
+  __shared__ BlockSegments seg;
+  const uint64_t p0 = (uint64_t)blockIdx.x * kBlock;
+  const unsigned w = threadIdx.x >> 6;
+  uint64_t first = 0;
+  const int64_t t = locate_in_block(pair_start, nbt, n_pairs, seg, &first);
+  bool hit = false;
+  uint32_t s_box = 0;
+  if (t >= 0) {
+    s_box = sidx[grp_lo[t] + (p0 + threadIdx.x - first)];
+    hit = build_region(boxes[s_box], boxes[nbs + t], 0, nullptr, nullptr);
+  }
+  const ull m = __ballot(hit);
+  if (lane_id() == 0) wcnt[w] = (uint32_t)__popcll(m);
+  __syncthreads();
+  uint32_t rank = (uint32_t)__popcll(m & ((1ull << lane_id()) - 1ull));
+  for (unsigned i = 0; i < w; ++i) rank += wcnt[i];
+  if (hit) hits[p0 + rank] = make_uint2(s_box, (uint32_t)t);
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+    for (unsigned i = 0; i < kBlock / 64; ++i) s += wcnt[i];
+    blk_cnt[blockIdx.x] = s;
+  }
+}
+
 // plan statistics are summed per workgroup in LDS first: one global atomic per counter and
 // workgroup instead of one per region
-struct BlockStats {
+struct WaveStats {
   ull payload, src_bytes, converted, transposed, dims[kDims + 1], src_end, lds_transpose;
   long long max_src, max_dst;
 };
 
-// One thread per candidate pair.  WRITE == false: count the non-empty intersections per block.
-// WRITE == true: write them densely at blk_off[block] + rank inside the block (rank from wave
-// ballots and a popcount below the lane, then a prefix over the block's waves), so the region
-// list is ordered by (target box, saved box in FQN-sorted order) and reproducible.
-template <bool WRITE>
-__global__ __launch_bounds__(kBlock) void k_pairs(const Box* boxes, int64_t nbs, int64_t nbt, const uint32_t* sidx,
-                                                  const uint32_t* grp_lo, const uint64_t* pair_start, uint64_t n_pairs,
-                                                  uint32_t* blk_cnt, const uint32_t* blk_off, uint32_t tile_bytes,
-                                                  Region* regions, uint64_t* tile_cnt, ull* cov, Ctl* ctl, ull* ext,
-                                                  uint32_t ext_src_bufs, uint32_t ext_bufs, uint32_t ext_stripes) {
-  __shared__ uint32_t wcnt[kBlock / 64];
-  __shared__ BlockStats bs;
-  // WRITE: the block's regions are put together in LDS and leave as one contiguous, coalesced copy
-  // (a 280-byte struct stored by each thread on its own is 18 partial-line stores per region)
-  __shared__ __attribute__((aligned(16))) char stage[WRITE ? kBlock * sizeof(Region) : 16];
-  if (WRITE && threadIdx.x == 0) {
-    bs.payload = bs.src_bytes = bs.converted = bs.transposed = 0;
-    for (int k = 0; k <= kDims; ++k) bs.dims[k] = 0;
-    bs.max_src = bs.max_dst = -1;
-    bs.src_end = 0;
-    bs.lds_transpose = 0;
+// Pass 2, one wave per 64 hits of a pass-1 block (workgroup (b, q) takes hits q*64.. of block b; most
+// blocks find fewer than 128, so the later waves of a block leave at once): build the copy regions and
+// write them at blk_off[b] + rank.  The regions of a wave are put together in LDS and leave as one
+// contiguous, coalesced copy (a 280-byte struct stored by each thread on its own is 18 partial-line
+// stores per region).  Waves share nothing, so no wave waits for another one's loads.
+constexpr uint32_t kBuildWave = 64;
+
+__global__ __launch_bounds__(kBuildWave) void k_pairs_build(const Box* boxes, int64_t nbs, const uint2* hits,
+                                                            const uint32_t* blk_off, uint32_t tile_bytes, Region* regions,
+                                                            uint64_t* tile_cnt, ull* cov, Ctl* ctl, ull* ext,
+                                                            uint32_t ext_src_bufs, uint32_t ext_bufs, uint32_t ext_stripes) {
+  __shared__ WaveStats ws;
+  __shared__ __attribute__((aligned(16))) char stage[kBuildWave * sizeof(Region)];
+  // (first every block's first 64 hits, then every block's second 64, ...: workgroups go to the chip's
+  // eight dies in turn, and with the four waves of a block next to each other some dies would only ever see
+  // the later waves, which mostly have nothing to do)
+  const uint32_t n_find_blocks = gridDim.x / (kBlock / kBuildWave);
+  const uint32_t b = blockIdx.x % n_find_blocks, q = blockIdx.x / n_find_blocks;
+  const uint32_t first = blk_off[b], cnt = blk_off[b + 1] - first;
+  if (q * kBuildWave >= cnt) return;
+  const uint32_t mine = min(kBuildWave, cnt - q * kBuildWave);
+  if (threadIdx.x == 0) {
+    ws.payload = ws.src_bytes = ws.converted = ws.transposed = 0;
+    for (int k = 0; k <= kDims; ++k) ws.dims[k] = 0;
+    ws.max_src = ws.max_dst = -1;
+    ws.src_end = 0;
+    ws.lds_transpose = 0;
   }
-  const uint64_t p = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  bool hit = false;
-  const Box* sb = nullptr;
-  const Box* tb = nullptr;
-  if (p < n_pairs) {
-    // target box whose pair range contains p: last t with pair_start[t] <= p
-    const int64_t t = upper_bound_u64(pair_start, nbt + 1, p) - 1;
-    const uint64_t k = p - pair_start[t];
-    tb = &boxes[nbs + t];
-    sb = &boxes[sidx[grp_lo[t] + k]];
-    hit = build_region(*sb, *tb, tile_bytes, nullptr, nullptr);
-  }
-  const ull m = __ballot(hit);
-  const unsigned w = threadIdx.x >> 6;
-  if (lane_id() == 0) wcnt[w] = (uint32_t)__popcll(m);
   __syncthreads();
-  if (!WRITE) {
-    if (threadIdx.x == 0) {
-      uint32_t s = 0;
-      for (unsigned i = 0; i < kBlock / 64; ++i) s += wcnt[i];
-      blk_cnt[blockIdx.x] = s;
-    }
-    return;
-  }
-  if (hit) {
-    uint32_t rank = (uint32_t)__popcll(m & ((1ull << lane_id()) - 1ull));  // among the block's regions
-    for (unsigned i = 0; i < w; ++i) rank += wcnt[i];
-    const uint32_t pos = blk_off[blockIdx.x] + rank;
-    Region& R = reinterpret_cast<Region*>(stage)[rank];
+  const bool active = threadIdx.x < mine;
+  ull send = 0, dend = 0, vol_u = 0;
+  int src_buf = -1, dst_buf = -1;
+  int64_t trec = -1;
+  if (active) {
+    const uint2 h = hits[(uint64_t)b * kBlock + q * kBuildWave + threadIdx.x];
+    // (both boxes whole, in registers, before anything looks at them: their loads are in flight together
+    // instead of one dimension's after the other's)
+    const Box sbox = boxes[h.x], tbox = boxes[nbs + h.y];
+    const Box *sb = &sbox, *tb = &tbox;
+    const uint32_t pos = first + q * kBuildWave + threadIdx.x;
+    Region& R = reinterpret_cast<Region*>(stage)[threadIdx.x];
     int64_t vol = 0;
-    build_region(*sb, *tb, tile_bytes, &R, &vol);
+    build_region(sbox, tbox, tile_bytes, &R, &vol);
     tile_cnt[pos] = R.n_tiles;
-    atomicAdd(&cov[tb->rec], (ull)vol);
-    atomicAdd(&bs.payload, (ull)vol * (ull)tb->itemsize);
-    atomicAdd(&bs.src_bytes, (ull)vol * (ull)sb->itemsize);
-    if (R.kind == kConvert) atomicAdd(&bs.converted, 1ull);
-    atomicAdd(&bs.dims[R.ndim + (R.kind != kTranspose && R.run_bytes > sb->itemsize ? 1 : 0)], 1ull);
+    vol_u = (ull)vol;
+    trec = tb->rec;
+    atomicAdd(&ws.payload, (ull)vol * (ull)tb->itemsize);
+    atomicAdd(&ws.src_bytes, (ull)vol * (ull)sb->itemsize);
+    if (R.kind == kConvert) atomicAdd(&ws.converted, 1ull);
+    atomicAdd(&ws.dims[R.ndim + (R.kind != kTranspose && R.run_bytes > sb->itemsize ? 1 : 0)], 1ull);
     if (R.kind == kTranspose) {
-      atomicAdd(&bs.transposed, 1ull);
-      atomicMax(&bs.lds_transpose, (ull)transpose_lds_bytes(R.tdim_a, R.tdim_b, (uint32_t)R.run_bytes));
+      atomicAdd(&ws.transposed, 1ull);
+      atomicMax(&ws.lds_transpose, (ull)transpose_lds_bytes(R.tdim_a, R.tdim_b, (uint32_t)R.run_bytes));
     }
-    ull send = (ull)(R.src_base + R.run_bytes), dend = (ull)(R.dst_base + (R.kind == kConvert ? R.run_bytes / 2 : R.run_bytes));
+    send = (ull)(R.src_base + R.run_bytes);
+    dend = (ull)(R.dst_base + (R.kind == kConvert ? R.run_bytes / 2 : R.run_bytes));
     for (int k = 0; k < R.ndim; ++k) {
       send += (ull)((R.len[k] - 1) * R.spitch[k]);
       dend += (ull)((R.len[k] - 1) * R.dpitch[k]);
     }
-    atomicMax(&bs.src_end, send);
-    // Per buffer, one past the highest byte the plan touches.  Millions of regions share a few hundred
-    // buffers: the table is kept in several copies (one per group of workgroups, folded afterwards), and
-    // most regions lie below what an earlier one has recorded (the values only grow, so a stale read
-    // costs an atomic, never a wrong maximum).
-    ull* e = ext + (size_t)(blockIdx.x % ext_stripes) * ext_bufs;
-    if (e[R.src_buf] < send) atomicMax(&e[R.src_buf], send);
-    if (e[ext_src_bufs + R.dst_buf] < dend) atomicMax(&e[ext_src_bufs + R.dst_buf], dend);
-    atomicMax(&bs.max_src, (long long)R.src_buf);
-    atomicMax(&bs.max_dst, (long long)R.dst_buf);
+    src_buf = R.src_buf;
+    dst_buf = R.dst_buf;
+    atomicMax(&ws.src_end, send);
+    atomicMax(&ws.max_src, (long long)R.src_buf);
+    atomicMax(&ws.max_dst, (long long)R.dst_buf);
     if (R.n_tiles == ~0ull) report(ctl, 0, kErrInvalid);
   }
-  __syncthreads();
+  // What the wave adds to memory other waves add to as well leaves it once per distinct address, not once per
+  // lane: an atomic costs the L2 the same few nanoseconds whether or not a neighbour lane's could have been
+  // folded into it, and millions of regions share a few hundred buffers and half as many target records.
+  //
+  // Elements of each target record covered by saved data (Sec. 3.3 Step 2: every requested element must
+  // be found).  The hits of a wave are in target-box order, so those of one record are neighbours:
+  // runs of equal records are summed by a segmented scan and their last lane adds the sum.
   {
-    uint32_t total = 0;
-    for (unsigned i = 0; i < kBlock / 64; ++i) total += wcnt[i];
-    static_assert(sizeof(Region) % 8 == 0, "copied in 8-byte words");
-    const uint32_t words = total * (uint32_t)(sizeof(Region) / 8);
-    const uint64_t* from = reinterpret_cast<const uint64_t*>(stage);
-    uint64_t* to = reinterpret_cast<uint64_t*>(regions + blk_off[blockIdx.x]);
-    for (uint32_t i = threadIdx.x; i < words; i += kBlock) to[i] = from[i];
+    const int64_t prev = __shfl_up(trec, 1);
+    const bool head = lane_id() == 0 || prev != trec;
+    const ull heads = __ballot(head);
+    const int run = __popcll(heads & (~0ull >> (63 - lane_id())));  // runs that start at or below this lane
+    ull v = vol_u;
+    for (int o = 1; o < 64; o <<= 1) {
+      const ull u = __shfl_up(v, o);
+      const int r = __shfl_up(run, o);
+      if (lane_id() >= o && r == run) v += u;
+    }
+    const bool tail = lane_id() == 63 || ((heads >> (lane_id() + 1)) & 1ull);
+    if (active && tail) atomicAdd(&cov[trec], v);
   }
-  if (threadIdx.x == 0 && (wcnt[0] | wcnt[1] | wcnt[2] | wcnt[3])) {
-    atomicAdd(&ctl->payload_bytes, bs.payload);
-    atomicAdd(&ctl->src_bytes, bs.src_bytes);
-    if (bs.converted) atomicAdd(&ctl->n_convert, bs.converted);
-    if (bs.transposed) {
-      atomicAdd(&ctl->n_transposed, bs.transposed);
-      atomicMax(&ctl->lds_transpose, bs.lds_transpose);
+  // Per buffer, one past the highest byte the plan touches.  The table is kept in several copies (one per
+  // group of workgroups, folded afterwards), and most regions lie below what an earlier one has recorded (the
+  // values only grow, so a stale read costs an atomic, never a wrong maximum).  Of the lanes that still
+  // have something to record, those that name the same buffer as the first of them reduce their maxima
+  // among themselves and one of them updates the table (the regions of one target rank's buffer, or read
+  // from one blob, are neighbours); after two such rounds whoever is left updates it on its own.
+  {
+    ull* e = ext + (size_t)(b % ext_stripes) * ext_bufs;
+    for (int side = 0; side < 2; ++side) {
+      const int buf = side ? dst_buf : src_buf;
+      const ull end = side ? dend : send;
+      ull* slot = &e[(side ? ext_src_bufs : 0u) + (uint32_t)(active ? buf : 0)];
+      bool todo = active && *slot < end;
+      for (int round = 0; round < 2; ++round) {
+        const ull waiting = __ballot(todo);
+        if (!waiting) break;
+        const int leader = __ffsll((long long)waiting) - 1;
+        const int which = __shfl(buf, leader);
+        const bool same = todo && buf == which;
+        ull m = same ? end : 0;
+        for (int o = 32; o >= 1; o >>= 1) {
+          const ull other = __shfl_xor(m, o);
+          m = other > m ? other : m;
+        }
+        if (lane_id() == leader) atomicMax(slot, m);
+        todo = todo && !same;
+      }
+      if (todo) atomicMax(slot, end);
+    }
+  }
+  __syncthreads();
+  static_assert(sizeof(Region) % 8 == 0, "copied in 8-byte words");
+  const uint32_t words = mine * (uint32_t)(sizeof(Region) / 8);
+  const uint64_t* from = reinterpret_cast<const uint64_t*>(stage);
+  uint64_t* to = reinterpret_cast<uint64_t*>(regions + first + q * kBuildWave);
+  for (uint32_t i = threadIdx.x; i < words; i += kBuildWave) to[i] = from[i];
+  if (threadIdx.x == 0) {
+    Ctl* part = &(reinterpret_cast<CtlStripe*>(ctl) + 1 + b % kCtlStripes)->c;
+    atomicAdd(&part->payload_bytes, ws.payload);
+    atomicAdd(&part->src_bytes, ws.src_bytes);
+    if (ws.converted) atomicAdd(&part->n_convert, ws.converted);
+    if (ws.transposed) {
+      atomicAdd(&part->n_transposed, ws.transposed);
+      atomicMax(&part->lds_transpose, ws.lds_transpose);
     }
     for (int k = 0; k <= kDims; ++k)
-      if (bs.dims[k]) atomicAdd(&ctl->dims_hist[k], bs.dims[k]);
-    atomicMax(&ctl->max_src_end, bs.src_end);
-    atomicMax(&ctl->max_src_buf, bs.max_src);
-    atomicMax(&ctl->max_dst_buf, bs.max_dst);
+      if (ws.dims[k]) atomicAdd(&part->dims_hist[k], ws.dims[k]);
+    atomicMax(&part->max_src_end, ws.src_end);
+    atomicMax(&part->max_src_buf, ws.max_src);
+    atomicMax(&part->max_dst_buf, ws.max_dst);
   }
 }
 
@@ -809,20 +1011,22 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
   return bytes;
 }
 
-// Pass A, one thread per tile: its region (binary search in the scanned tile counts) and what it
+// Pass A, one thread per tile: its region (located in the scanned tile counts) and what it
 // counts towards a batch budget: 0 for big tiles, which are batches of their own.
 // key (optional): source-order sort key, (source buffer, last source byte the tile reads).
 __global__ __launch_bounds__(kBlock) void k_tile_weights(const uint64_t* tile_start, const Region* regions,
                                                          int64_t n_regions, uint64_t n_tiles, uint32_t* tile_region,
                                                          uint32_t* tile_local, uint64_t* weight, uint64_t* key,
                                                          uint32_t* order) {
+  __shared__ BlockSegments seg;
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= n_tiles) return;
-  const int64_t r = upper_bound_u64(tile_start, n_regions + 1, i) - 1;
+  uint64_t first = 0;
+  const int64_t r = locate_in_block(tile_start, n_regions, n_tiles, seg, &first);
+  if (r < 0) return;
   tile_region[i] = (uint32_t)r;
-  tile_local[i] = (uint32_t)(i - tile_start[r]);
+  tile_local[i] = (uint32_t)(i - first);
   TileDesc t;
-  const uint64_t bytes = decode_tile(regions[r], (uint32_t)(i - tile_start[r]), &t);
+  const uint64_t bytes = decode_tile(regions[r], (uint32_t)(i - first), &t);
   weight[i] = bytes >= kSmallTileBytes ? 0 : (bytes > kMinBatchWeight ? bytes : (uint64_t)kMinBatchWeight);
   // a transpose tile of any useful size wants the whole workgroup and its LDS staging
   if ((t.kind & 0xffu) == kTranspose && bytes >= 1024) weight[i] = 0;
@@ -910,16 +1114,17 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const Region* regions, co
   }
 }
 
-// fold the copies of the per-buffer extent table: ext[b] = max over the stripes
+// fold the copies of the per-buffer extent table: ext[b] = max over the stripes (at most 64 of them: one wave per
+// buffer, one lane per stripe, so the copies are read side by side and not one after the other)
 __global__ __launch_bounds__(kBlock) void k_extents_fold(ull* ext, uint32_t n_bufs, uint32_t stripes) {
-  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
-  if (b >= n_bufs) return;
-  ull m = ext[b];
-  for (uint32_t s = 1; s < stripes; ++s) {
-    const ull v = ext[(size_t)s * n_bufs + b];
-    m = v > m ? v : m;
+  const uint32_t b = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+  if (b >= n_bufs) return;  // (the same for all lanes of a wave)
+  ull m = lane_id() < stripes ? ext[(size_t)lane_id() * n_bufs + b] : 0;
+  for (int o = 32; o >= 1; o >>= 1) {
+    const ull other = __shfl_xor(m, o);
+    m = other > m ? other : m;
   }
-  ext[b] = m;
+  if (lane_id() == 0) ext[b] = m;
 }
 
 bcp_status device_error(const Ctl& ctl, int64_t n_saved) {
@@ -1053,10 +1258,51 @@ hipError_t ensure_landing(Workspace& ws, size_t bytes) {
   return e;
 }
 
-__global__ void k_readback(const Ctl* ctl, const void* p0, int w0, const void* p1, int w1, const void* p2, int w2,
-                           Readback* out) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  out->ctl = *ctl;
+// how the words of a Ctl combine
+enum CtlOp : int { kOpAdd, kOpMaxU, kOpMaxS, kOpMinU };
+__device__ inline int ctl_word_op(size_t word) {
+  const size_t off = word * 8;
+  if (off == offsetof(Ctl, err_key)) return kOpMinU;
+  if (off == offsetof(Ctl, max_saved_fqn) || off == offsetof(Ctl, max_src_end) || off == offsetof(Ctl, lds_transpose)) return kOpMaxU;
+  if (off == offsetof(Ctl, max_src_buf) || off == offsetof(Ctl, max_dst_buf) || off == offsetof(Ctl, max_saved_rec_buf) ||
+      off == offsetof(Ctl, max_target_rec_buf))
+    return kOpMaxS;
+  return kOpAdd;
+}
+static_assert(sizeof(Ctl) % 8 == 0, "a Ctl is folded as 8-byte words");
+constexpr int kCtlWords = (int)(sizeof(Ctl) / 8);
+
+// One workgroup of kCtlStripes threads: folds the striped copies of the control block into the first one,
+// leaves them as they were initialised (`neutral`), and copies the result and up to three values for the host.
+__global__ __launch_bounds__(kCtlStripes) void k_readback(Ctl* ctl, Ctl neutral, const void* p0, int w0, const void* p1,
+                                                          int w1, const void* p2, int w2, Readback* out) {
+  __shared__ ull acc[kCtlWords];
+  ull* main_words = reinterpret_cast<ull*>(ctl);
+  if (threadIdx.x < kCtlWords) acc[threadIdx.x] = main_words[threadIdx.x];
+  __syncthreads();
+  ull* mine = reinterpret_cast<ull*>(&(reinterpret_cast<CtlStripe*>(ctl) + 1 + threadIdx.x)->c);
+  const ull* none = reinterpret_cast<const ull*>(&neutral);
+  ull words[kCtlWords];  // (all loads first: they are in flight together)
+#pragma unroll
+  for (int k = 0; k < kCtlWords; ++k) words[k] = mine[k];
+#pragma unroll
+  for (int k = 0; k < kCtlWords; ++k) {
+    const ull v = words[k];
+    if (v == none[k]) continue;
+    mine[k] = none[k];
+    switch (ctl_word_op(k)) {
+      case kOpAdd: atomicAdd(&acc[k], v); break;
+      case kOpMaxU: atomicMax(&acc[k], v); break;
+      case kOpMaxS: atomicMax(reinterpret_cast<long long*>(&acc[k]), (long long)v); break;
+      default: atomicMin(&acc[k], v); break;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kCtlWords) {
+    main_words[threadIdx.x] = acc[threadIdx.x];
+    reinterpret_cast<ull*>(&out->ctl)[threadIdx.x] = acc[threadIdx.x];
+  }
+  if (threadIdx.x != 0) return;
   const void* p[3] = {p0, p1, p2};
   const int w[3] = {w0, w1, w2};
   for (int i = 0; i < 3; ++i)
@@ -1064,9 +1310,17 @@ __global__ void k_readback(const Ctl* ctl, const void* p0, int w0, const void* p
 }
 
 // Synchronises the stream.  pK: device address of a 4-byte (wK == 4) or 8-byte value, or null.
-bcp_status read_back(Workspace& ws, hipStream_t st, const Ctl* ctl, Readback* dev, Readback* host, const void* p0 = nullptr,
+Ctl initial_ctl() {
+  Ctl init{};
+  init.err_key = ~0ull;
+  init.max_src_buf = init.max_dst_buf = -1;
+  init.max_saved_rec_buf = init.max_target_rec_buf = -1;
+  return init;
+}
+
+bcp_status read_back(Workspace& ws, hipStream_t st, Ctl* ctl, Readback* dev, Readback* host, const void* p0 = nullptr,
                      int w0 = 4, const void* p1 = nullptr, int w1 = 4, const void* p2 = nullptr, int w2 = 4) {
-  hipLaunchKernelGGL(k_readback, dim3(1), dim3(1), 0, st, ctl, p0, w0, p1, w1, p2, w2, dev);
+  hipLaunchKernelGGL(k_readback, dim3(1), dim3(kCtlStripes), 0, st, ctl, initial_ctl(), p0, w0, p1, w1, p2, w2, dev);
   BCP_HIP(hipGetLastError());
   BCP_HIP(hipMemcpyAsync(ws.landing, dev, sizeof(Readback), hipMemcpyDeviceToHost, st));
   BCP_HIP(hipStreamSynchronize(st));
@@ -1084,10 +1338,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   out->n_saved_boxes = out->n_target_boxes = 0;
   out->device_ms = 0.f;
 
-  Ctl init{};
-  init.err_key = ~0ull;
-  init.max_src_buf = init.max_dst_buf = -1;
-  init.max_saved_rec_buf = init.max_target_rec_buf = -1;
+  const Ctl init = initial_ctl();
   out->ctl = init;
   if (n_target == 0) return BCP_OK;
   if (n_total > (int64_t)(0xffffffffu / kMaxBoxesPerRecord)) {  // box indices are 32-bit
@@ -1115,17 +1366,22 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   Readback rb;
   uint32_t* box_start = nullptr;
   BCP_HIP(ws.alloc(&recs, (size_t)n_total));
-  BCP_HIP(ws.alloc(&ctl, 1));
+  {
+    CtlStripe* copies = nullptr;  // the control block and its striped copies
+    BCP_HIP(ws.alloc(&copies, (size_t)kCtlStripes + 1));
+    ctl = &copies->c;
+  }
   BCP_HIP(ws.alloc(&rb_dev, 1));
   BCP_HIP(ws.alloc(&box_start, (size_t)n_total + 1));
   const hipMemcpyKind up = (flags & BCP_META_ON_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
   if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, up, st));
   BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, up, st));
-  BCP_HIP(hipMemcpyAsync(ctl, &init, sizeof(Ctl), hipMemcpyHostToDevice, st));
+  hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(kBlock), 0, st, ctl, init);
+  BCP_HIP(hipGetLastError());
   BCP_HIP(hipEventRecord(ev0, st));
 
   // 1. validate + count boxes, scan                                                    (sync 1)
-  hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total)), dim3(kBlock), 0, st, recs, n_saved, n_total, box_start, ctl);
+  hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total, kRecBlock)), dim3(kRecBlock), 0, st, recs, n_saved, n_total, box_start, ctl);
   BCP_HIP(hipGetLastError());
   if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, ws, st)) return s;
   if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, box_start + n_saved, 4, box_start + n_total, 4)) return s;
@@ -1204,13 +1460,15 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   Region* regions = nullptr;
   uint64_t* tile_start = nullptr;
   uint32_t* blk = nullptr;
+  uint2* hits = nullptr;  // per block of 256 candidate pairs: the pairs that intersect
   ull* ext = nullptr;  // per-buffer extents: [source blobs | destination buffers] by record buffer index
   unsigned nblk_pairs = 0;
   if (n_pairs > 0) {
     nblk_pairs = blocks_for((int64_t)n_pairs);
     BCP_HIP(ws.alloc(&blk, (size_t)nblk_pairs + 1));
-    hipLaunchKernelGGL((k_pairs<false>), dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
-                       n_pairs, blk, blk, tile_bytes, (Region*)nullptr, (uint64_t*)nullptr, cov, ctl, (ull*)nullptr, 0u, 0u, 1u);
+    BCP_HIP(ws.alloc(&hits, (size_t)nblk_pairs * kBlock));
+    hipLaunchKernelGGL(k_pairs_find, dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
+                       n_pairs, blk, hits);
     BCP_HIP(hipGetLastError());
     if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk_pairs, ws, st)) return s;
     size_t cap = (size_t)n_pairs;
@@ -1229,10 +1487,10 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     const uint32_t ext_stripes = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(1, ((uint64_t)1 << 20) / std::max(ext_bufs, 1u)));
     BCP_HIP(ws.alloc(&ext, (size_t)ext_bufs * ext_stripes));
     BCP_HIP(hipMemsetAsync(ext, 0, sizeof(ull) * (size_t)ext_bufs * ext_stripes, st));
-    hipLaunchKernelGGL((k_pairs<true>), dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
-                       n_pairs, blk, blk, tile_bytes, regions, tile_start, cov, ctl, ext, ext_src_bufs, ext_bufs, ext_stripes);
+    hipLaunchKernelGGL(k_pairs_build, dim3(nblk_pairs * (kBlock / kBuildWave)), dim3(kBuildWave), 0, st, boxes, nbs, hits, blk,
+                       tile_bytes, regions, tile_start, cov, ctl, ext, ext_src_bufs, ext_bufs, ext_stripes);
     BCP_HIP(hipGetLastError());
-    hipLaunchKernelGGL(k_extents_fold, dim3(blocks_for(ext_bufs)), dim3(kBlock), 0, st, ext, ext_bufs, ext_stripes);
+    hipLaunchKernelGGL(k_extents_fold, dim3(blocks_for(ext_bufs, kBlock / 64)), dim3(kBlock), 0, st, ext, ext_bufs, ext_stripes);
     BCP_HIP(hipGetLastError());
     hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
                        (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);

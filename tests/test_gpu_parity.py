@@ -631,6 +631,30 @@ def test_unused_saved_tensor_is_ignored_and_uncovered_flag():
     p.destroy()
 
 
+def test_long_stretch_of_targets_without_saved_data():
+    """Hundreds of target tensors in a row that no saved shard covers (allowed by flag): the candidate pairs of
+    one workgroup then span far more target boxes than it has threads, on both sides of the stretch."""
+    n_gap = 700
+    spec, sv, tg = {}, [], []
+    so = to = 0
+    for f in range(n_gap + 40):
+        spec[f] = TensorSpec(f, f"t{f}", (6, 4), torch.float32, ("bits",))
+        covered = f < 20 or f >= 20 + n_gap
+        if covered:  # saved as two row halves, asked for whole
+            sv.append(regular(Part(f, (6, 4), (0, 0), (3, 4)), 4, 0, so))
+            sv.append(regular(Part(f, (6, 4), (3, 0), (3, 4)), 4, 0, so + 48))
+            so += 96
+        tg.append(regular(Part(f, (6, 4), (0, 0), (6, 4)), 4, 0, to))
+        to += 96
+    case = Case("gap", 11, spec, Layout(sv, [so]), Layout(tg, [to]))
+    src = synth.materialize(case.saved, spec, 11)
+    got, p = gpu_reshard(case, src, flags=binding.BCP_ALLOW_UNCOVERED)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON, allow_uncovered=True)
+    assert_same(got, want, "gap")
+    assert p.stats()["n_regions"] == 80
+    p.destroy()
+
+
 def _plan_error(saved: Layout, target: Layout, mutate=None):
     sm, tm = binding.layout_to_meta(saved), binding.layout_to_meta(target)
     if mutate:
