@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188956848557,
-             "csrc_sha256": "a69336922f9ccbd31a75c0b7afa80f4fbd18ebe44992c1b0a91c1a690fc31fbd"},
-    "eval_load": {"bytes_per_launch": 41235714452,
-             "csrc_sha256": "a69336922f9ccbd31a75c0b7afa80f4fbd18ebe44992c1b0a91c1a690fc31fbd"},
-    "cfg5_small": {"bytes_per_launch": 1878083811,
-             "csrc_sha256": "a69336922f9ccbd31a75c0b7afa80f4fbd18ebe44992c1b0a91c1a690fc31fbd"},
+    "cfg3": {"bytes_per_launch": 188953883801,
+             "csrc_sha256": "c5072ad351efecbc0ff9208524703121f4d801c499e218f091305008c0649ffe"},
+    "eval_load": {"bytes_per_launch": 41230790267,
+             "csrc_sha256": "c5072ad351efecbc0ff9208524703121f4d801c499e218f091305008c0649ffe"},
+    "cfg5_small": {"bytes_per_launch": 1878263426,
+             "csrc_sha256": "c5072ad351efecbc0ff9208524703121f4d801c499e218f091305008c0649ffe"},
 }
 
 
