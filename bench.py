@@ -458,11 +458,11 @@ def main():
         tp = time.perf_counter()
         pl = make_plan()
         plan_ms.append((time.perf_counter() - tp) * 1e3)
-        if prev is not None:
-            prev.destroy()  # its copy has finished: building the next plan waited for the stream
         ev[i][0].record(stream)
         binding.reshard(pl, src, dst, stream=stream)
         ev[i][1].record(stream)
+        if prev is not None:
+            prev.destroy()  # its copy has finished: building this step's plan waited for the stream
         prev = pl
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0

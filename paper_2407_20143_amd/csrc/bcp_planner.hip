@@ -6,9 +6,10 @@
 //      "Decomposing irregular tensors"), exclusive scan, emit the boxes;
 //   2. sort the saved boxes by FQN (LSD radix sort, 4-bit digits, stable);
 //   3. per target box, find its FQN's run of saved boxes; scan the candidate-pair counts;
-//   4. one thread per candidate pair: intersect the two boxes; wave ballot + prefix to compact
-//      the non-empty intersections into a dense, deterministic region list; each region is
-//      normalised on the spot (unit dims dropped, dims contiguous on both sides merged) and tiled;
+//   4. one thread per candidate pair: intersect the two boxes; wave ballot + prefix to list the
+//      non-empty intersections of every block of pairs; then one thread per listed pair: the region,
+//      normalised on the spot (unit dims dropped, dims contiguous on both sides merged) and tiled,
+//      written into a dense, deterministic region list;
 //   5. scan the tile counts; weigh the tiles, group runs of small tiles into batches, and write one
 //      fully decoded descriptor per batch head (and per small tile);
 //   plus the checks: coverage of every target record, saved shards pairwise disjoint, records of
@@ -116,12 +117,22 @@ template <typename Tin, typename T>
 __global__ __launch_bounds__(kSmallScanThreads) void k_scan_small(const Tin* in, int64_t n, T* out) {
   __shared__ T lds[16];
   T carry = 0;
-  for (int64_t base = 0; base < n; base += blockDim.x) {
-    const int64_t i = base + threadIdx.x;
-    const T v = i < n ? (T)in[i] : (T)0;
+  for (int64_t base = 0; base < n; base += (int64_t)blockDim.x * kScanItems) {
+    const int64_t i0 = base + (int64_t)threadIdx.x * kScanItems;  // this thread's consecutive items
+    T v[kScanItems];
+    T s = 0;
+#pragma unroll
+    for (int u = 0; u < kScanItems; ++u) {
+      v[u] = i0 + u < n ? (T)in[i0 + u] : (T)0;
+      s += v[u];
+    }
     T tot;
-    const T ex = block_exclusive_scan(v, &tot, lds);
-    if (i < n) out[i] = carry + ex;
+    T run = carry + block_exclusive_scan(s, &tot, lds);
+#pragma unroll
+    for (int u = 0; u < kScanItems; ++u) {
+      if (i0 + u < n) out[i0 + u] = run;
+      run += v[u];
+    }
     carry += tot;
   }
   if (threadIdx.x == 0) out[n] = carry;
@@ -140,7 +151,8 @@ struct Workspace {
   std::vector<Chunk> chunks;
   std::mutex mu;
   int device = -1;
-  void* landing = nullptr;  // pinned host memory the planner's read-backs arrive in
+  void* landing = nullptr;  // pinned host memory the planner's read-backs arrive in: kernels write into it
+  void* landing_dev = nullptr;  // its address on the device
   size_t landing_bytes = 0;
   hipEvent_t ev[2] = {nullptr, nullptr};  // bracket the planner's device work (reused from plan to plan)
 
@@ -197,6 +209,7 @@ bcp_status release_workspace(int64_t* freed_bytes) {
     const hipError_t e = hipHostFree(g_ws.landing);
     if (first == hipSuccess) first = e;
     g_ws.landing = nullptr;
+    g_ws.landing_dev = nullptr;
     g_ws.landing_bytes = 0;
   }
   for (hipEvent_t& e : g_ws.ev)
@@ -252,8 +265,12 @@ __device__ inline Ctl* ctl_stripe(Ctl* ctl) {
   return &(reinterpret_cast<CtlStripe*>(ctl) + 1 + blockIdx.x % kCtlStripes)->c;
 }
 
-__global__ __launch_bounds__(kBlock) void k_ctl_init(Ctl* ctl, Ctl init) {
-  for (uint32_t i = threadIdx.x; i <= kCtlStripes; i += kBlock) reinterpret_cast<CtlStripe*>(ctl)[i].c = init;
+// (also clears the coverage counters: a fill of its own is one more launch, and a plan for a few thousand
+// records is made of launches)
+__global__ __launch_bounds__(kBlock) void k_ctl_init(Ctl* ctl, Ctl init, ull* cov, int64_t n_cov) {
+  if (blockIdx.x == 0)
+    for (uint32_t i = threadIdx.x; i <= kCtlStripes; i += kBlock) reinterpret_cast<CtlStripe*>(ctl)[i].c = init;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n_cov; i += (int64_t)gridDim.x * kBlock) cov[i] = 0;
 }
 
 // A record is 304 bytes, and a wave whose lanes each read their own record asks for 64 cache lines with
@@ -384,6 +401,92 @@ __global__ __launch_bounds__(kBlock) void k_sort_init(const Box* boxes, int64_t 
   if (i >= n) return;
   keys[i] = (uint64_t)boxes[i].fqn;
   idx[i] = (uint32_t)i;
+}
+
+// The same sort for at most kSortSmallMax boxes in ONE workgroup, keys and both index arrays in LDS: for a plan
+// of a few thousand records a pass of the device-wide sort is three launches that take longer to start than to
+// run.  Every thread owns kSortSmallItems consecutive positions; per pass it counts its digits (four 16-bit
+// counters to a 64-bit word, so four workgroup scans give the sixteen digits' offsets), the totals are
+// stacked into digit bases, and the positions are scattered in order: stable like the big one.
+constexpr int kSortSmallThreads = 1024;
+constexpr int kSortSmallItems = 4;
+constexpr int kSortSmallMax = kSortSmallThreads * kSortSmallItems;
+
+__global__ __launch_bounds__(kSortSmallThreads) void k_sort_small(const Box* boxes, int n, int bits, uint64_t* keys_out,
+                                                                  uint32_t* idx_out) {
+  __shared__ uint64_t key[kSortSmallMax];      // by box index
+  __shared__ uint16_t order[2][kSortSmallMax];  // box indices in the current / next order
+  __shared__ ull wave_tot[kSortSmallThreads / 64][4];
+  const int t = threadIdx.x;
+  for (int i = t; i < n; i += kSortSmallThreads) {
+    key[i] = (uint64_t)boxes[i].fqn;
+    order[0][i] = (uint16_t)i;
+  }
+  __syncthreads();
+  int cur = 0;
+  for (int shift = 0; shift < bits; shift += 4) {
+    const int j0 = t * kSortSmallItems;
+    unsigned dig[kSortSmallItems];
+    ull cnt[4] = {0, 0, 0, 0};  // cnt[q]: digits 4q .. 4q+3, 16 bits each (a digit occurs at most 4096 times)
+#pragma unroll
+    for (int u = 0; u < kSortSmallItems; ++u) {
+      dig[u] = j0 + u < n ? (unsigned)(key[order[cur][j0 + u]] >> shift) & 15u : 16u;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if ((dig[u] >> 2) == (unsigned)q) cnt[q] += 1ull << (16 * (dig[u] & 3u));
+    }
+    // exclusive scan of the four words over the workgroup, all four side by side: one pair of barriers
+    ull inc[4], before[4], total[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) inc[q] = cnt[q];
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const ull o = __shfl_up(inc[q], dlt, 64);
+        if (lane_id() >= (unsigned)dlt) inc[q] += o;
+      }
+    }
+    if (lane_id() == 63)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) wave_tot[t >> 6][q] = inc[q];
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ull below = 0, all = 0;
+      for (int w = 0; w < kSortSmallThreads / 64; ++w) {
+        const ull c = wave_tot[w][q];
+        if (w < (t >> 6)) below += c;
+        all += c;
+      }
+      before[q] = below + inc[q] - cnt[q];
+      total[q] = all;
+    }
+    // base of digit d: occurrences of all smaller digits
+    unsigned base[16];
+    unsigned run = 0;
+#pragma unroll
+    for (int d = 0; d < 16; ++d) {
+      base[d] = run + (unsigned)((before[d >> 2] >> (16 * (d & 3))) & 0xffffu);
+      run += (unsigned)((total[d >> 2] >> (16 * (d & 3))) & 0xffffu);
+    }
+#pragma unroll
+    for (int u = 0; u < kSortSmallItems; ++u) {
+      if (dig[u] > 15u) continue;
+      unsigned pos = 0;
+#pragma unroll
+      for (int d = 0; d < 16; ++d)
+        if (dig[u] == (unsigned)d) pos = base[d]++;
+      order[cur ^ 1][pos] = order[cur][j0 + u];
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+  for (int i = t; i < n; i += kSortSmallThreads) {
+    const uint16_t b = order[cur][i];
+    keys_out[i] = key[b];
+    idx_out[i] = b;
+  }
 }
 
 __global__ __launch_bounds__(kBlock) void k_radix_hist(const uint64_t* keys, int64_t n, int shift, uint32_t* hist,
@@ -730,10 +833,18 @@ __device__ inline int64_t locate_in_block(const uint64_t* start, int64_t n, uint
 // region list that pass 2 writes from these lists is ordered by (target box, saved box) and reproducible.
 __global__ __launch_bounds__(kBlock) void k_pairs_find(const Box* boxes, int64_t nbs, int64_t nbt, const uint32_t* sidx,
                                                        const uint32_t* grp_lo, const uint64_t* pair_start,
-                                                       uint64_t n_pairs, uint32_t* blk_cnt, uint2* hits) {
+                                                       uint64_t n_pairs, uint32_t* blk_cnt, uint2* hits,
+                                                       uint64_t* tile_cnt_zero, ull* ext_zero, uint64_t ext_words) {
   __shared__ uint32_t wcnt[kBlock / 64];
   __shared__ BlockSegments seg;
   const uint64_t p0 = (uint64_t)blockIdx.x * kBlock;
+  // what pass 2 expects to find cleared: the tile counts of a list sized by the number of candidates (slots
+  // beyond the region count stay zero, so that the scan of the counts may run over all of them) and the extent table
+  if (tile_cnt_zero) {
+    if (p0 + threadIdx.x < n_pairs) tile_cnt_zero[p0 + threadIdx.x] = 0;
+    if (p0 + threadIdx.x == 0) tile_cnt_zero[n_pairs] = 0;
+  }
+  for (uint64_t i = p0 + threadIdx.x; i < ext_words; i += (uint64_t)gridDim.x * kBlock) ext_zero[i] = 0;
   const unsigned w = threadIdx.x >> 6;
   uint64_t first = 0;
   const int64_t t = locate_in_block(pair_start, nbt, n_pairs, seg, &first);
@@ -1017,9 +1128,10 @@ __device__ inline uint64_t decode_tile(const Region& R, uint32_t local, TileDesc
 __global__ __launch_bounds__(kBlock) void k_tile_weights(const uint64_t* tile_start, const Region* regions,
                                                          int64_t n_regions, uint64_t n_tiles, uint32_t* tile_region,
                                                          uint32_t* tile_local, uint64_t* weight, uint64_t* key,
-                                                         uint32_t* order) {
+                                                         uint32_t* order, unsigned long long* queue) {
   __shared__ BlockSegments seg;
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < 8) queue[i] = 0;  // the copy kernel's queue words start at zero (and put themselves back there)
   uint64_t first = 0;
   const int64_t r = locate_in_block(tile_start, n_regions, n_tiles, seg, &first);
   if (r < 0) return;
@@ -1252,10 +1364,18 @@ hipError_t ensure_landing(Workspace& ws, size_t bytes) {
   if (ws.landing && ws.landing_bytes >= bytes) return hipSuccess;
   if (ws.landing) (void)hipHostFree(ws.landing);
   ws.landing = nullptr;
+  ws.landing_dev = nullptr;
   ws.landing_bytes = 0;
-  const hipError_t e = hipHostMalloc(&ws.landing, bytes, hipHostMallocDefault);
-  if (e == hipSuccess) ws.landing_bytes = bytes;
-  return e;
+  hipError_t e = hipHostMalloc(&ws.landing, bytes, hipHostMallocDefault);
+  if (e != hipSuccess) return e;
+  e = hipHostGetDevicePointer(&ws.landing_dev, ws.landing, 0);
+  if (e != hipSuccess) {
+    (void)hipHostFree(ws.landing);
+    ws.landing = nullptr;
+    return e;
+  }
+  ws.landing_bytes = bytes;
+  return hipSuccess;
 }
 
 // how the words of a Ctl combine
@@ -1309,7 +1429,6 @@ __global__ __launch_bounds__(kCtlStripes) void k_readback(Ctl* ctl, Ctl neutral,
     out->v[i] = !p[i] ? 0 : (w[i] == 8 ? *(const uint64_t*)p[i] : (uint64_t) * (const uint32_t*)p[i]);
 }
 
-// Synchronises the stream.  pK: device address of a 4-byte (wK == 4) or 8-byte value, or null.
 Ctl initial_ctl() {
   Ctl init{};
   init.err_key = ~0ull;
@@ -1318,14 +1437,26 @@ Ctl initial_ctl() {
   return init;
 }
 
-bcp_status read_back(Workspace& ws, hipStream_t st, Ctl* ctl, Readback* dev, Readback* host, const void* p0 = nullptr,
-                     int w0 = 4, const void* p1 = nullptr, int w1 = 4, const void* p2 = nullptr, int w2 = 4) {
-  hipLaunchKernelGGL(k_readback, dim3(1), dim3(kCtlStripes), 0, st, ctl, initial_ctl(), p0, w0, p1, w1, p2, w2, dev);
+// Synchronises the stream.  pK: device address of a 4-byte (wK == 4) or 8-byte value, or null.  The kernel writes
+// what the host wants straight into the pinned landing block (a copy of its own would be one more operation
+// on the stream, and a plan for a few thousand records is made of those).
+bcp_status read_back(Workspace& ws, hipStream_t st, Ctl* ctl, Readback* host, const void* p0 = nullptr, int w0 = 4,
+                     const void* p1 = nullptr, int w1 = 4, const void* p2 = nullptr, int w2 = 4) {
+  hipLaunchKernelGGL(k_readback, dim3(1), dim3(kCtlStripes), 0, st, ctl, initial_ctl(), p0, w0, p1, w1, p2, w2,
+                     (Readback*)ws.landing_dev);
   BCP_HIP(hipGetLastError());
-  BCP_HIP(hipMemcpyAsync(ws.landing, dev, sizeof(Readback), hipMemcpyDeviceToHost, st));
   BCP_HIP(hipStreamSynchronize(st));
   std::memcpy(host, ws.landing, sizeof(Readback));
   return BCP_OK;
+}
+
+// the last read-back of a plan: the batch count and, per buffer the plan uses, one past the highest byte it touches
+__global__ __launch_bounds__(kBlock) void k_final_readback(const uint32_t* n_batches, const ull* src_ext, uint32_t n_src,
+                                                           const ull* dst_ext, uint32_t n_dst, char* landing) {
+  if (threadIdx.x == 0) *reinterpret_cast<uint32_t*>(landing) = *n_batches;
+  ull* out = reinterpret_cast<ull*>(landing + kLandingExtents);
+  for (uint32_t i = threadIdx.x; i < n_src; i += kBlock) out[i] = src_ext[i];
+  for (uint32_t i = threadIdx.x; i < n_dst; i += kBlock) out[n_src + i] = dst_ext[i];
 }
 
 }  // namespace
@@ -1362,7 +1493,6 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   BCP_HIP(ensure_landing(ws, kLandingBytes));
   bcp_shard_meta* recs = nullptr;
   Ctl* ctl = nullptr;
-  Readback* rb_dev = nullptr;
   Readback rb;
   uint32_t* box_start = nullptr;
   BCP_HIP(ws.alloc(&recs, (size_t)n_total));
@@ -1371,12 +1501,13 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     BCP_HIP(ws.alloc(&copies, (size_t)kCtlStripes + 1));
     ctl = &copies->c;
   }
-  BCP_HIP(ws.alloc(&rb_dev, 1));
   BCP_HIP(ws.alloc(&box_start, (size_t)n_total + 1));
   const hipMemcpyKind up = (flags & BCP_META_ON_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
   if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, up, st));
   BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, up, st));
-  hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(kBlock), 0, st, ctl, init);
+  ull* cov = nullptr;  // per target record: elements found in saved shards
+  BCP_HIP(ws.alloc(&cov, (size_t)n_target));
+  hipLaunchKernelGGL(k_ctl_init, dim3(std::min(blocks_for(n_target), 1024u)), dim3(kBlock), 0, st, ctl, init, cov, n_target);
   BCP_HIP(hipGetLastError());
   BCP_HIP(hipEventRecord(ev0, st));
 
@@ -1384,7 +1515,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total, kRecBlock)), dim3(kRecBlock), 0, st, recs, n_saved, n_total, box_start, ctl);
   BCP_HIP(hipGetLastError());
   if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, ws, st)) return s;
-  if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, box_start + n_saved, 4, box_start + n_total, 4)) return s;
+  if (bcp_status s = read_back(ws, st, ctl, &rb, box_start + n_saved, 4, box_start + n_total, 4)) return s;
   Ctl h = rb.ctl;
   if (bcp_status s = device_error(h, n_saved)) return s;
   const int64_t nbs = (int64_t)rb.v[0], nbt = (int64_t)(rb.v[1] - rb.v[0]), nbx = (int64_t)rb.v[1];
@@ -1407,12 +1538,15 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   BCP_HIP(ws.alloc(&keys_b, (size_t)nbs));
   BCP_HIP(ws.alloc(&idx_a, (size_t)nbs));
   BCP_HIP(ws.alloc(&idx_b, (size_t)nbs));
-  if (nbs > 0) {
+  int bits = 0;  // significant bits of the largest saved FQN id
+  while (bits < 64 && (h.max_saved_fqn >> bits) != 0) ++bits;
+  if (nbs > 0 && nbs <= kSortSmallMax) {
+    hipLaunchKernelGGL(k_sort_small, dim3(1), dim3(kSortSmallThreads), 0, st, boxes, (int)nbs, bits, keys_a, idx_a);
+    BCP_HIP(hipGetLastError());
+  } else if (nbs > 0) {
     const unsigned nblk = blocks_for(nbs);
     hipLaunchKernelGGL(k_sort_init, dim3(nblk), dim3(kBlock), 0, st, boxes, nbs, keys_a, idx_a);
     BCP_HIP(hipGetLastError());
-    int bits = 0;
-    while (bits < 64 && (h.max_saved_fqn >> bits) != 0) ++bits;
     if (nbs > 1 && bits > 0) {
       uint32_t* hist = nullptr;
       BCP_HIP(ws.alloc(&hist, (size_t)16 * nblk + 1));
@@ -1431,11 +1565,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   // 3. candidate pairs                                                                     (sync 2)
   uint32_t* grp_lo = nullptr;
   uint64_t* pair_start = nullptr;
-  ull* cov = nullptr;
   BCP_HIP(ws.alloc(&grp_lo, (size_t)nbt));
   BCP_HIP(ws.alloc(&pair_start, (size_t)nbt + 1));
-  BCP_HIP(ws.alloc(&cov, (size_t)n_target));
-  BCP_HIP(hipMemsetAsync(cov, 0, sizeof(ull) * (size_t)n_target, st));
   hipLaunchKernelGGL(k_pair_count, dim3(blocks_for(nbt)), dim3(kBlock), 0, st, boxes, nbs, nbt, keys_a, idx_a, recs, n_saved,
                      (flags & BCP_CONVERT_F32_TO_BF16) ? 1 : 0, grp_lo, pair_start, ctl);
   BCP_HIP(hipGetLastError());
@@ -1445,7 +1576,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
                        (flags & BCP_SKIP_OVERLAP_CHECK) ? 0 : 1, ctl);
     BCP_HIP(hipGetLastError());
   }
-  if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, pair_start + nbt, 8)) return s;
+  if (bcp_status s = read_back(ws, st, ctl, &rb, pair_start + nbt, 8)) return s;
   h = rb.ctl;
   const uint64_t n_pairs = rb.v[0];
   if (bcp_status s = device_error(h, n_saved)) return s;
@@ -1467,26 +1598,25 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     nblk_pairs = blocks_for((int64_t)n_pairs);
     BCP_HIP(ws.alloc(&blk, (size_t)nblk_pairs + 1));
     BCP_HIP(ws.alloc(&hits, (size_t)nblk_pairs * kBlock));
-    hipLaunchKernelGGL(k_pairs_find, dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
-                       n_pairs, blk, hits);
-    BCP_HIP(hipGetLastError());
-    if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk_pairs, ws, st)) return s;
-    size_t cap = (size_t)n_pairs;
-    if (cap * sizeof(Region) > ((size_t)64 << 20)) {
-      if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, blk + nblk_pairs, 4)) return s;
-      n_regions = (uint32_t)rb.v[0];
-      cap = n_regions;
-    }
-    BCP_HIP(block_alloc(&owned.p[0], std::max<size_t>(cap, 1) * sizeof(Region), &owned.bytes[0], st));
-    regions = (Region*)owned.p[0];
-    BCP_HIP(ws.alloc(&tile_start, cap + 1));
-    // slots beyond the region count stay zero so that the scan below may run over `cap` entries
-    BCP_HIP(hipMemsetAsync(tile_start, 0, sizeof(uint64_t) * (cap + 1), st));
     // what each buffer must hold: a table over every buffer index the records name, in up to 64 copies
     const uint32_t ext_src_bufs = (uint32_t)(h.max_saved_rec_buf + 1), ext_bufs = ext_src_bufs + (uint32_t)(h.max_target_rec_buf + 1);
     const uint32_t ext_stripes = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(1, ((uint64_t)1 << 20) / std::max(ext_bufs, 1u)));
     BCP_HIP(ws.alloc(&ext, (size_t)ext_bufs * ext_stripes));
-    BCP_HIP(hipMemsetAsync(ext, 0, sizeof(ull) * (size_t)ext_bufs * ext_stripes, st));
+    size_t cap = (size_t)n_pairs;
+    const bool exact = cap * sizeof(Region) > ((size_t)64 << 20);  // then the region list is sized after counting
+    if (!exact) BCP_HIP(ws.alloc(&tile_start, cap + 1));
+    hipLaunchKernelGGL(k_pairs_find, dim3(nblk_pairs), dim3(kBlock), 0, st, boxes, nbs, nbt, idx_a, grp_lo, pair_start,
+                       n_pairs, blk, hits, tile_start, ext, (uint64_t)ext_bufs * ext_stripes);
+    BCP_HIP(hipGetLastError());
+    if (bcp_status s = device_scan<uint32_t, uint32_t>(blk, blk, nblk_pairs, ws, st)) return s;
+    if (exact) {
+      if (bcp_status s = read_back(ws, st, ctl, &rb, blk + nblk_pairs, 4)) return s;
+      n_regions = (uint32_t)rb.v[0];
+      cap = n_regions;
+      BCP_HIP(ws.alloc(&tile_start, cap + 1));  // (pass 2 writes every count; the scan writes the entry after them)
+    }
+    BCP_HIP(block_alloc(&owned.p[0], std::max<size_t>(cap, 1) * sizeof(Region), &owned.bytes[0], st));
+    regions = (Region*)owned.p[0];
     hipLaunchKernelGGL(k_pairs_build, dim3(nblk_pairs * (kBlock / kBuildWave)), dim3(kBuildWave), 0, st, boxes, nbs, hits, blk,
                        tile_bytes, regions, tile_start, cov, ctl, ext, ext_src_bufs, ext_bufs, ext_stripes);
     BCP_HIP(hipGetLastError());
@@ -1497,7 +1627,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     BCP_HIP(hipGetLastError());
     if (bcp_status s = device_scan<uint64_t, uint64_t>(tile_start, tile_start, (int64_t)cap, ws, st)) return s;
     // tile total and region count                                                         (sync 4)
-    if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb, tile_start + cap, 8, blk + nblk_pairs, 4)) return s;
+    if (bcp_status s = read_back(ws, st, ctl, &rb, tile_start + cap, 8, blk + nblk_pairs, 4)) return s;
     h = rb.ctl;
     const uint64_t n_tiles = rb.v[0];
     n_regions = (uint32_t)rb.v[1];
@@ -1521,7 +1651,6 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       tiles = heads + n_tiles;
       out->dev.queue = (unsigned long long*)(tiles + n_tiles);
       out->dev.batch_key = by_source ? (uint64_t*)((char*)owned.p[1] + desc_bytes + 64) : nullptr;
-      BCP_HIP(hipMemsetAsync(out->dev.queue, 0, 64, st));
       uint64_t* weight = nullptr;
       uint64_t* wprefix = nullptr;
       uint32_t* tile_region = nullptr;
@@ -1542,7 +1671,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       }
       const unsigned nblk = blocks_for((int64_t)n_tiles + 1);
       hipLaunchKernelGGL(k_tile_weights, dim3(nblk), dim3(kBlock), 0, st, tile_start, regions, (int64_t)n_regions,
-                         n_tiles, tile_region, tile_local, weight, key, order);
+                         n_tiles, tile_region, tile_local, weight, key, order, out->dev.queue);
       BCP_HIP(hipGetLastError());
       if (by_source) {
         // sort the tiles by (source buffer, last source byte): the plan can then run as blobs arrive
@@ -1592,10 +1721,9 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       // the extents of the buffers the plan uses come back with the batch count
       const size_t n_src = (size_t)(h.max_src_buf + 1), n_dst = (size_t)(h.max_dst_buf + 1);
       BCP_HIP(ensure_landing(ws, kLandingExtents + sizeof(ull) * (n_src + n_dst)));  // (nothing is in flight into it)
-      BCP_HIP(hipMemcpyAsync(ws.landing, bflags + n_tiles, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-      BCP_HIP(hipMemcpyAsync((char*)ws.landing + kLandingExtents, ext, sizeof(ull) * n_src, hipMemcpyDeviceToHost, st));
-      BCP_HIP(hipMemcpyAsync((char*)ws.landing + kLandingExtents + sizeof(ull) * n_src, ext + ext_src_bufs, sizeof(ull) * n_dst,
-                             hipMemcpyDeviceToHost, st));
+      hipLaunchKernelGGL(k_final_readback, dim3(1), dim3(kBlock), 0, st, bflags + n_tiles, ext, (uint32_t)n_src,
+                         ext + ext_src_bufs, (uint32_t)n_dst, (char*)ws.landing_dev);
+      BCP_HIP(hipGetLastError());
       out->src_extent.resize(n_src);
       out->dst_extent.resize(n_dst);
     }
@@ -1619,7 +1747,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     hipLaunchKernelGGL(k_coverage, dim3(blocks_for(n_target)), dim3(kBlock), 0, st, recs, n_saved, n_target, cov,
                        (flags & BCP_ALLOW_UNCOVERED) ? 1 : 0, ctl);
     BCP_HIP(hipGetLastError());
-    if (bcp_status s = read_back(ws, st, ctl, rb_dev, &rb)) return s;
+    if (bcp_status s = read_back(ws, st, ctl, &rb)) return s;
     h = rb.ctl;
     if (bcp_status s = device_error(h, n_saved)) return s;
   }
