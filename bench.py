@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188953883801,
-             "csrc_sha256": "c5072ad351efecbc0ff9208524703121f4d801c499e218f091305008c0649ffe"},
-    "eval_load": {"bytes_per_launch": 41230790267,
-             "csrc_sha256": "c5072ad351efecbc0ff9208524703121f4d801c499e218f091305008c0649ffe"},
-    "cfg5_small": {"bytes_per_launch": 1878263426,
-             "csrc_sha256": "c5072ad351efecbc0ff9208524703121f4d801c499e218f091305008c0649ffe"},
+    "cfg3": {"bytes_per_launch": 188958325692,
+             "csrc_sha256": "267d0b87b56e64e5e2462b66522ff001a81930b5a8672dec797fea52476c44f6"},
+    "eval_load": {"bytes_per_launch": 41246685166,
+             "csrc_sha256": "267d0b87b56e64e5e2462b66522ff001a81930b5a8672dec797fea52476c44f6"},
+    "cfg5_small": {"bytes_per_launch": 1878210874,
+             "csrc_sha256": "267d0b87b56e64e5e2462b66522ff001a81930b5a8672dec797fea52476c44f6"},
 }
 
 

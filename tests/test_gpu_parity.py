@@ -655,6 +655,37 @@ def test_long_stretch_of_targets_without_saved_data():
     p.destroy()
 
 
+@pytest.mark.parametrize("n", [4095, 4096, 4097])
+def test_saved_box_count_around_the_one_workgroup_sort_limit(n):
+    """Up to 4096 saved boxes are grouped by FQN inside one workgroup, more by the device-wide sort: the
+    same plan on either side of the limit.  FQN ids are sparse (several digits) and arrive in descending order,
+    two saved boxes per tensor, so that the grouping has work to do and its stability shows."""
+    half = n // 2
+    fqns = [(i * 40503) % 1000003 for i in range(half + 1)]
+    assert len(set(fqns)) == len(fqns)
+    spec, sv, tg = {}, [], []
+    so = to = 0
+    for k, f in enumerate(sorted(fqns, reverse=True)):
+        spec[f] = TensorSpec(f, f"t{f}", (4, 3), torch.float32, ("bits",))
+        parts = [((0, 0), (2, 3)), ((2, 0), (2, 3))] if 2 * k + 1 < n else [((0, 0), (4, 3))]
+        for off, ln in parts:
+            sv.append(regular(Part(f, (4, 3), off, ln), 4, 0, so))
+            so += ln[0] * ln[1] * 4
+        if len(sv) >= n:
+            break
+    for f in sorted(spec):  # asked for whole, in ascending order
+        tg.append(regular(Part(f, (4, 3), (0, 0), (4, 3)), 4, 0, to))
+        to += 48
+    assert len(sv) == n
+    case = Case("sortlimit", 12, spec, Layout(sv, [so]), Layout(tg, [to]))
+    src = synth.materialize(case.saved, spec, 12)
+    got, p = gpu_reshard(case, src)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    assert_same(got, want, f"sortlimit{n}")
+    assert p.stats()["n_saved_boxes"] == n
+    p.destroy()
+
+
 def _plan_error(saved: Layout, target: Layout, mutate=None):
     sm, tm = binding.layout_to_meta(saved), binding.layout_to_meta(target)
     if mutate:
