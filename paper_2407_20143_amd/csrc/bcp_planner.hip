@@ -160,6 +160,11 @@ struct Workspace {
     if (dev != device) {  // another device: drop everything that belongs to the old one (rare)
       for (Chunk& c : chunks) (void)hipFree(c.base);
       chunks.clear();
+      if (landing) {  // kernels of the old device wrote into it through that device's mapping
+        (void)hipHostFree(landing);
+        landing = landing_dev = nullptr;
+        landing_bytes = 0;
+      }
       for (hipEvent_t& e : ev)
         if (e) {
           (void)hipEventDestroy(e);
@@ -280,25 +285,37 @@ constexpr int kRecChunks = (int)(sizeof(bcp_shard_meta) / 16);
 static_assert(sizeof(bcp_shard_meta) % 16 == 0, "records are staged in 16-byte pieces");
 constexpr int kRecBlock = 128;  // records (threads) per workgroup of the kernels that stage records
 
-__device__ inline void stage_records(const bcp_shard_meta* recs, int64_t rec0, int count, uint4* lds) {
-  const uint4* from = reinterpret_cast<const uint4*>(recs + rec0);
+// Records rec0 .. rec0 + count of the concatenation [saved | target] come from two arrays (n_saved records in the
+// first); `gather`, if not null, receives them as well, as one array: the caller's two arrays -- in device memory,
+// or in pinned host memory that the device reads over the bus -- then need no copy of their own before the kernel.
+__device__ inline void stage_records(const bcp_shard_meta* saved, const bcp_shard_meta* target, int64_t n_saved,
+                                     int64_t rec0, int count, uint4* lds, bcp_shard_meta* gather) {
+  const uint4* from_s = reinterpret_cast<const uint4*>(saved);
+  const uint4* from_t = reinterpret_cast<const uint4*>(target);
+  uint4* to = reinterpret_cast<uint4*>(gather);
+  const int64_t g0 = rec0 * kRecChunks, split = n_saved * kRecChunks;  // in 16-byte pieces
   const int chunks = count * kRecChunks;
   uint4 v[kRecChunks];
 #pragma unroll
   for (int j = 0; j < kRecChunks; ++j) {
     const int i = j * kRecBlock + (int)threadIdx.x;
-    v[j] = from[i < chunks ? i : chunks - 1];  // (count >= 1; the copies of the last piece are not stored)
+    const int64_t g = g0 + (i < chunks ? i : chunks - 1);  // (count >= 1; the copies of the last piece are not stored)
+    v[j] = g < split ? from_s[g] : from_t[g - split];
   }
 #pragma unroll
   for (int j = 0; j < kRecChunks; ++j) {
     const int i = j * kRecBlock + (int)threadIdx.x;
-    if (i < chunks) lds[i] = v[j];
+    if (i < chunks) {
+      lds[i] = v[j];
+      if (to) to[g0 + i] = v[j];
+    }
   }
   __syncthreads();
 }
 
-__global__ __launch_bounds__(kRecBlock) void k_validate_count(const bcp_shard_meta* recs, int64_t n_saved,
-                                                              int64_t n_total, uint32_t* nboxes, Ctl* ctl) {
+__global__ __launch_bounds__(kRecBlock) void k_validate_count(const bcp_shard_meta* saved, const bcp_shard_meta* target,
+                                                              bcp_shard_meta* gather, int64_t n_saved, int64_t n_total,
+                                                              uint32_t* nboxes, Ctl* ctl) {
   // largest saved FQN id and largest buffer indices of the block: one global atomic per block, not per record
   __shared__ ull block_max;
   __shared__ int block_sbuf, block_tbuf;
@@ -308,7 +325,7 @@ __global__ __launch_bounds__(kRecBlock) void k_validate_count(const bcp_shard_me
     block_sbuf = block_tbuf = -1;
   }
   const int64_t rec0 = (int64_t)blockIdx.x * kRecBlock;
-  stage_records(recs, rec0, (int)(n_total - rec0 < kRecBlock ? n_total - rec0 : kRecBlock), staged);
+  stage_records(saved, target, n_saved, rec0, (int)(n_total - rec0 < kRecBlock ? n_total - rec0 : kRecBlock), staged, gather);
   const int64_t i = rec0 + threadIdx.x;
   if (i < n_total) {
     const bcp_shard_meta& r = reinterpret_cast<const bcp_shard_meta*>(staged)[threadIdx.x];
@@ -1429,6 +1446,18 @@ __global__ __launch_bounds__(kCtlStripes) void k_readback(Ctl* ctl, Ctl neutral,
     out->v[i] = !p[i] ? 0 : (w[i] == 8 ? *(const uint64_t*)p[i] : (uint64_t) * (const uint32_t*)p[i]);
 }
 
+// Host memory the device can read in place (pinned: hipHostMalloc): its address on the device.
+constexpr int64_t kDirectUploadRecords = 8192;  // more than these go by the copy engine, which moves large blocks faster
+bool device_visible(const void* host, const void** dev) {
+  void* d = nullptr;
+  if (hipHostGetDevicePointer(&d, const_cast<void*>(host), 0) != hipSuccess || !d) {
+    (void)hipGetLastError();  // pageable memory is unknown to the runtime: not an error of this call
+    return false;
+  }
+  *dev = d;
+  return true;
+}
+
 Ctl initial_ctl() {
   Ctl init{};
   init.err_key = ~0ull;
@@ -1502,9 +1531,27 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     ctl = &copies->c;
   }
   BCP_HIP(ws.alloc(&box_start, (size_t)n_total + 1));
-  const hipMemcpyKind up = (flags & BCP_META_ON_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
-  if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, up, st));
-  BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, up, st));
+  // The records reach `recs` (one array, saved then target) either by two copies, or -- records already in device
+  // memory, or a few of them in pinned host memory the device can read -- through the validation kernel, which
+  // has to read them anyway: two operations fewer on the stream, and for device metadata one pass over it.
+  const bcp_shard_meta *from_s = recs, *from_t = recs + n_saved;
+  bcp_shard_meta* gather = nullptr;
+  {
+    const bool aligned = (((uintptr_t)saved | (uintptr_t)target) & 15u) == 0;
+    const void *ds = saved, *dt = target;
+    bool direct = aligned && (flags & BCP_META_ON_DEVICE);
+    if (aligned && !direct && n_total <= kDirectUploadRecords)
+      direct = (n_saved == 0 || device_visible(saved, &ds)) && device_visible(target, &dt);
+    if (direct) {
+      from_s = (const bcp_shard_meta*)ds;
+      from_t = (const bcp_shard_meta*)dt;
+      gather = recs;
+    } else {
+      const hipMemcpyKind up = (flags & BCP_META_ON_DEVICE) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+      if (n_saved) BCP_HIP(hipMemcpyAsync(recs, saved, sizeof(bcp_shard_meta) * (size_t)n_saved, up, st));
+      BCP_HIP(hipMemcpyAsync(recs + n_saved, target, sizeof(bcp_shard_meta) * (size_t)n_target, up, st));
+    }
+  }
   ull* cov = nullptr;  // per target record: elements found in saved shards
   BCP_HIP(ws.alloc(&cov, (size_t)n_target));
   hipLaunchKernelGGL(k_ctl_init, dim3(std::min(blocks_for(n_target), 1024u)), dim3(kBlock), 0, st, ctl, init, cov, n_target);
@@ -1512,7 +1559,8 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   BCP_HIP(hipEventRecord(ev0, st));
 
   // 1. validate + count boxes, scan                                                    (sync 1)
-  hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total, kRecBlock)), dim3(kRecBlock), 0, st, recs, n_saved, n_total, box_start, ctl);
+  hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total, kRecBlock)), dim3(kRecBlock), 0, st, from_s, from_t, gather, n_saved,
+                     n_total, box_start, ctl);
   BCP_HIP(hipGetLastError());
   if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, ws, st)) return s;
   if (bcp_status s = read_back(ws, st, ctl, &rb, box_start + n_saved, 4, box_start + n_total, 4)) return s;

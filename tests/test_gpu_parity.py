@@ -241,6 +241,20 @@ def test_metadata_already_on_the_device():
     dt, nt = binding.meta_to_device(tm)
     b = binding.plan_from_device_meta(ds, ns, dt, nt)
     assert a.regions().tobytes() == b.regions().tobytes()
+    # the same records from pageable host memory, and from host arrays that are not 16-byte aligned: other
+    # ways into the planner (copies instead of the validation kernel reading the caller's arrays), same plan
+    pageable = binding.plan(np.array(sm), np.array(tm))
+    raw_s, raw_t = np.zeros(sm.nbytes + 16, np.uint8), np.zeros(tm.nbytes + 16, np.uint8)
+    off_s, off_t = (8 - raw_s.ctypes.data % 16) % 16, (8 - raw_t.ctypes.data % 16) % 16  # addresses 8 modulo 16
+    ms = raw_s[off_s:off_s + sm.nbytes].view(sm.dtype)
+    mt = raw_t[off_t:off_t + tm.nbytes].view(tm.dtype)
+    ms[:], mt[:] = sm, tm
+    assert ms.ctypes.data % 16 == 8 and mt.ctypes.data % 16 == 8
+    shifted = binding.plan(ms, mt)
+    for other in (pageable, shifted):
+        assert a.regions().tobytes() == other.regions().tobytes()
+        assert a.stats()["n_batches"] == other.stats()["n_batches"]
+        other.destroy()
     src = synth.materialize(case.saved, case.tensors, case.seed)
     want = oracle.reshard(case.saved, case.target, src, poison=POISON)
     dsrc = [x.cuda() for x in src]
