@@ -86,6 +86,9 @@ __device__ __forceinline__ void lds_st(char* p, typename Granule<G>::type v) {
 
 
 typedef u32x4 u32x4_unaligned __attribute__((aligned(1)));
+typedef u32x2 u32x2_unaligned __attribute__((aligned(1)));
+typedef uint32_t u32_unaligned __attribute__((aligned(1)));
+typedef uint16_t u16_unaligned __attribute__((aligned(1)));
 template <> struct Granule<-16> { typedef u32x4 type; };
 template <>
 __device__ __forceinline__ u32x4 ld<-16>(gsrc_t p) {
@@ -559,22 +562,21 @@ constexpr int kRound = 2;  // items of a lane in flight (measured: 2 beats 1 and
 
 struct SmallTile {  // 64 bytes, takes the descriptor's place in LDS
   enum Mode : uint32_t {
-    kUniform,  // rows of items of one size g
-    kRun,      // one contiguous run whose two sides disagree modulo 16: items of e bytes up to the destination's
-               // next 16-byte boundary, 16-byte items (aligned stores, unaligned loads), items of e bytes again
-    kMixed,    // rows of runs of 16 bytes or more whose accesses may be unaligned: per row 16-byte items, then
-               // items of e bytes
-    kElems,    // transposed tile: items of g bytes inside elements, source contiguous along a, destination along b
+    kRows,   // rows of items of g bytes, g the largest power of two that fits a row (16 at most); a row's last item
+             // is moved back so that it ends with the row (it may copy some bytes a second time).  Items sit at any
+             // address: what a batch of small tiles costs is vector memory instructions, not bytes or alignment,
+             // and a wave whose lanes all move items of one size issues one load and one store per round
+    kElems,  // transposed tile: items of g bytes inside elements, source contiguous along a, destination along b
   };
   uint64_t s, d;        // addresses of the tile's first byte on the two sides
   int64_t p0, p1;       // pitches of the descriptor
   uint32_t n_items;
-  uint32_t ipr;         // items per row (kUniform, kMixed); items per element (kElems)
+  uint32_t ipr;         // items per row (kRows); items per element (kElems)
   float inv_ipr;        // 1 / ipr, a little high: (i * inv_ipr) truncates to i / ipr or one more
-  uint32_t body;        // 16-byte items per row (kMixed) or in the run (kRun); kElems: element size
-  uint32_t head;        // kRun: bytes before the first 16-byte item; kElems: elements along a, and 1 / that
+  uint32_t body;        // kRows: offset of a row's last item; kElems: element size
+  uint32_t head;        // kElems: elements along a, and 1 / that
   float inv_na;
-  uint32_t mode_glog;   // mode | log2 of g (kUniform, kElems) or of e (kRun, kMixed) << 8
+  uint32_t mode_glog;   // mode | log2 of g << 8
   uint32_t pad_;
 };
 static_assert(sizeof(SmallTile) == sizeof(TileDesc), "takes the descriptor's slot");
@@ -611,39 +613,11 @@ __device__ __forceinline__ SmallTile small_tile(const TileDesc& T, gsrc_t s, gds
     c.n_items = T.a * T.b * c.ipr;
   } else {
     const uint32_t run = T.a, nrows = T.b;
-    uintptr_t al = (uintptr_t)s | (uintptr_t)d | (uintptr_t)run;
-    if (nrows > 1) al |= (uintptr_t)T.p0 | (uintptr_t)T.p1;
-    if ((al & 15u) == 0) {
-      mode = SmallTile::kUniform;
-      glog = 4;
-      c.ipr = run >> 4;
-      c.n_items = nrows * c.ipr;
-    } else if (nrows == 1 && run >= 64) {
-      mode = SmallTile::kRun;
-      glog = (al & 3u) == 0 ? 2u : 0u;
-      c.head = (uint32_t)(-(uintptr_t)d) & 15u;
-      c.body = (run - c.head) >> 4;
-      c.n_items = (c.head >> glog) + c.body + ((run - c.head - (c.body << 4)) >> glog);
-    } else if (run >= 16 && (al & 3u) == 0) {
-      // 16-byte accesses at 4-byte aligned addresses cost the memory system nothing extra, and four times
-      // fewer items than 4-byte ones
-      mode = SmallTile::kMixed;
-      glog = 2;
-      c.body = run >> 4;
-      c.ipr = c.body + ((run & 15u) >> 2);
-      c.n_items = nrows * c.ipr;
-    } else if (run >= 64) {
-      mode = SmallTile::kMixed;
-      glog = 0;
-      c.body = run >> 4;
-      c.ipr = c.body + (run & 15u);
-      c.n_items = nrows * c.ipr;
-    } else {
-      mode = SmallTile::kUniform;
-      glog = (al & 7u) == 0 ? 3u : (al & 3u) == 0 ? 2u : (al & 1u) == 0 ? 1u : 0u;
-      c.ipr = run >> glog;
-      c.n_items = nrows * c.ipr;
-    }
+    mode = SmallTile::kRows;
+    glog = run >= 16u ? 4u : (run ? 31u - (uint32_t)__clz((int)run) : 0u);
+    c.ipr = (run + (1u << glog) - 1u) >> glog;  // (0 for the empty spare segment of a long row)
+    c.body = run - (run ? 1u << glog : 0u);
+    c.n_items = nrows * c.ipr;
   }
   c.inv_ipr = inv_high(c.ipr);
   c.mode_glog = mode | (glog << 8);
@@ -653,60 +627,36 @@ __device__ __forceinline__ SmallTile small_tile(const TileDesc& T, gsrc_t s, gds
 // item i of the tile: byte offsets on the two sides and log2 of its size
 __device__ __forceinline__ void small_item(const SmallTile& c, uint32_t i, int64_t* so, int64_t* dof, uint32_t* gl) {
   const uint32_t mode = c.mode_glog & 0xffu, glog = c.mode_glog >> 8;
-  if (mode == SmallTile::kRun) {
-    const uint32_t nh = c.head >> glog;
-    uint32_t off;
-    *gl = glog;
-    if (i < nh) {
-      off = i << glog;
-    } else if (i < nh + c.body) {
-      off = c.head + ((i - nh) << 4);
-      *gl = 4;
-    } else {
-      off = c.head + (c.body << 4) + ((i - nh - c.body) << glog);
-    }
-    *so = *dof = off;
-    return;
-  }
   const uint32_t row = div_small(i, c.ipr, c.inv_ipr), col = i - row * c.ipr;
+  *gl = glog;
   if (mode == SmallTile::kElems) {  // row: element index, col: item inside the element
     const uint32_t b = div_small(row, c.head, c.inv_na), a = row - b * c.head, by = col << glog;
     *so = (int64_t)a * c.body + (int64_t)b * c.p0 + by;
     *dof = (int64_t)a * c.p1 + (int64_t)b * c.body + by;
-    *gl = glog;
     return;
   }
-  uint32_t off = col << glog;
-  *gl = glog;
-  if (mode == SmallTile::kMixed) {
-    if (col < c.body) {
-      off = col << 4;
-      *gl = 4;
-    } else {
-      off = (c.body << 4) + ((col - c.body) << glog);
-    }
-  }
+  const uint32_t off = min(col << glog, c.body);
   *so = (int64_t)row * c.p0 + off;
   *dof = (int64_t)row * c.p1 + off;
 }
 
 // One item: the load, and later the store.  Ordinary (temporal) accesses: neighbouring tiles share cache
 // lines at their edges, and the L2 that holds a line for one tile serves, or merges with, the next one's
-// part of it.  16-byte items may sit at any address on either side.
+// part of it.  Items of any size may sit at any address on either side.
 __device__ __forceinline__ u32x4 item_load(gsrc_t p, uint32_t gl) {
   u32x4 v = {0u, 0u, 0u, 0u};
   if (gl == 4) v = *(const u32x4_unaligned BCP_GLOBAL*)p;
-  else if (gl == 3) { const u32x2 t = *(const u32x2 BCP_GLOBAL*)p; v[0] = t[0]; v[1] = t[1]; }
-  else if (gl == 2) v[0] = *(const uint32_t BCP_GLOBAL*)p;
-  else if (gl == 1) v[0] = *(const uint16_t BCP_GLOBAL*)p;
+  else if (gl == 3) { const u32x2 t = *(const u32x2_unaligned BCP_GLOBAL*)p; v[0] = t[0]; v[1] = t[1]; }
+  else if (gl == 2) v[0] = *(const u32_unaligned BCP_GLOBAL*)p;
+  else if (gl == 1) v[0] = *(const u16_unaligned BCP_GLOBAL*)p;
   else if (gl == 0) v[0] = *(const uint8_t BCP_GLOBAL*)p;
   return v;
 }
 __device__ __forceinline__ void item_store(gdst_t p, uint32_t gl, const u32x4& v) {
   if (gl == 4) *(u32x4_unaligned BCP_GLOBAL*)p = v;
-  else if (gl == 3) *(u32x2 BCP_GLOBAL*)p = u32x2{v[0], v[1]};
-  else if (gl == 2) *(uint32_t BCP_GLOBAL*)p = v[0];
-  else if (gl == 1) *(uint16_t BCP_GLOBAL*)p = (uint16_t)v[0];
+  else if (gl == 3) *(u32x2_unaligned BCP_GLOBAL*)p = u32x2{v[0], v[1]};
+  else if (gl == 2) *(u32_unaligned BCP_GLOBAL*)p = v[0];
+  else if (gl == 1) *(u16_unaligned BCP_GLOBAL*)p = (uint16_t)v[0];
   else if (gl == 0) *(uint8_t BCP_GLOBAL*)p = (uint8_t)v[0];
 }
 
