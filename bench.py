@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188957064892,
-             "csrc_sha256": "2dd8f45a078f2c13556007a1f61686ae8c3d95cebfa4e4ec92a153858fe28b31"},
-    "eval_load": {"bytes_per_launch": 41233820732,
-             "csrc_sha256": "2dd8f45a078f2c13556007a1f61686ae8c3d95cebfa4e4ec92a153858fe28b31"},
-    "cfg5_small": {"bytes_per_launch": 1877990205,
-             "csrc_sha256": "2dd8f45a078f2c13556007a1f61686ae8c3d95cebfa4e4ec92a153858fe28b31"},
+    "cfg3": {"bytes_per_launch": 188957453729,
+             "csrc_sha256": "8b4a24cdb37ec215e9b5d375e3fcc486b78ab84357676ef70f665a5e909e6a08"},
+    "eval_load": {"bytes_per_launch": 41281428775,
+             "csrc_sha256": "8b4a24cdb37ec215e9b5d375e3fcc486b78ab84357676ef70f665a5e909e6a08"},
+    "cfg5_small": {"bytes_per_launch": 1891711254,
+             "csrc_sha256": "8b4a24cdb37ec215e9b5d375e3fcc486b78ab84357676ef70f665a5e909e6a08"},
 }
 
 
