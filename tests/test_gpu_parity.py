@@ -479,6 +479,34 @@ def test_small_tile_batches_longer_than_a_workgroup(tile_bytes, threads):
     check_case(Case("small_batches_u8", 78, specs, saved, target))
 
 
+def test_small_tiles_every_row_length_and_alignment():
+    """Rows of 1 .. 40 bytes (items of 1, 2, 4, 8 and 16 bytes, the last one of a row moved back to end with
+    it) at every source and destination address modulo 16, as single runs and as three rows with padding
+    between them on either side; the gaps between the tensors keep their poison, so an item that reached
+    beyond its row on the destination side shows."""
+    spec, sv, tg = {}, [], []
+    so = to = 0
+    f = 0
+    for rows in (1, 3):
+        for L in (list(range(1, 41)) if rows == 1 else [1, 2, 3, 5, 7, 8, 12, 13, 16, 17, 31, 33]):
+            for a in range(16):
+                for b in range(16):
+                    shape = (rows, L)
+                    spec[f] = TensorSpec(f, f"t{f}", shape, torch.uint8, ("bits",))
+                    part = Part(f, shape, (0, 0), shape)
+                    so = (so + 15) // 16 * 16 + a
+                    to = (to + 15) // 16 * 16 + b
+                    ps, pt = (L + 3, L + 6) if rows > 1 else (L, L)
+                    sv.append(regular(part, 1, 0, so, (ps, 1) if rows > 1 else None))
+                    tg.append(regular(part, 1, 0, to, (pt, 1) if rows > 1 else None))
+                    so += rows * ps + 5
+                    to += rows * pt + 5
+                    f += 1
+    case = Case("rows_x_alignments", 13, spec, Layout(sv, [so]), Layout(tg, [to]))
+    st = check_case(case)
+    assert st["n_regions"] == f
+
+
 def test_plan_destroyed_right_after_its_launch():
     """Destroying a plan while its copy is still queued is legal: its device blocks are recycled by the
     next plan (same sizes here, so it does take them), ordered behind the copy that still reads them."""
