@@ -33,8 +33,10 @@ namespace {
 constexpr int kMaxThreads = 1024;
 // The staging area in LDS is sized at launch: what the plan's largest transposed tile needs, and
 // at least the room the small-tile batches take (one descriptor and one counter per thread).
+constexpr uint32_t kItemClasses = 8;  // item sizes 1 .. 16 bytes, converting tiles, and room to a power of two
 constexpr uint32_t small_batch_lds_bytes(uint32_t threads) {
-  return threads * (uint32_t)sizeof(TileDesc) + (threads + 1 + kMaxThreads / 64) * 4u;
+  return threads * (uint32_t)sizeof(TileDesc) + (threads + 1 + kMaxThreads / 64) * 4u + threads * 4u +
+         kItemClasses * (kMaxThreads / 64) * 4u;
 }
 constexpr uint32_t kMaxDynamicLds = 144 * 1024;  // of the CU's 160 KiB; pointers and queue slots are static
 constexpr int kLdsPtrs = 1024;           // buffer pointers staged in LDS (more: read from global)
@@ -774,9 +776,13 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
     SmallTile* ltile = reinterpret_cast<SmallTile*>(lds);                                // [nthr]
     uint32_t* lstart = reinterpret_cast<uint32_t*>(lds + sizeof(SmallTile) * nthr);      // [nthr + 1]
     uint32_t* lwave = lstart + nthr + 1;                                                 // [waves]
+    uint32_t* lcount = lwave + kMaxThreads / 64;                                         // [nthr]
+    uint32_t* lclass = lcount + nthr;                                                    // [kItemClasses][waves]
+    constexpr uint32_t kWaves = kMaxThreads / 64;
     for (uint32_t base = 0; base < H.count; base += nthr) {
       const uint32_t n = min(nthr, H.count - base);
-      uint32_t c = 0;
+      uint32_t c = 0, cls = kItemClasses - 1;
+      SmallTile rec;
       if (tid < n) {
         const TileDesc T = tiles[H.first + base + tid];
         if (CV && (T.kind & 0xffu) == kConvert) {  // converting tiles: what convert_rows needs, marked by the mode
@@ -789,14 +795,50 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
           raw.ipr = T.b;       // rows
           raw.body = T.a;      // elements per row
           raw.mode_glog = 0xffu;
-          ltile[tid] = raw;
+          rec = raw;
           c = raw.n_items;
+          cls = 5;
         } else {
-          const SmallTile st = small_tile(T, src_of(T), dst_of(T));
-          ltile[tid] = st;
-          c = (st.n_items + kRound - 1) / kRound;
+          rec = small_tile(T, src_of(T), dst_of(T));
+          c = (rec.n_items + kRound - 1) / kRound;
+          cls = rec.mode_glog >> 8;  // log2 of the item size: 0 .. 4
         }
         c = c < 1 ? 1u : (c > nthr ? nthr : c);
+      }
+      // The slice's tiles are put in the order of their item sizes (stable inside a size): the lanes of a wave
+      // then mostly move items of one size, and a wave issues one load and one store per round and size.
+      // Rank inside the class from ballots, class and wave bases from a scan of the 8 x 16 table of counts.
+      {
+        uint32_t rank = 0, mine = 0;
+#pragma unroll
+        for (uint32_t k = 0; k < kItemClasses - 1; ++k) {
+          const unsigned long long m = __ballot(cls == k);
+          if (cls == k) rank = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+          if (lane == k) mine = (uint32_t)__popcll(m);
+        }
+        if (lane < kItemClasses) lclass[lane * kWaves + wave] = mine;
+        __syncthreads();
+        if (wave == 0) {  // exclusive scan of the table, class by class, wave by wave: two entries per lane
+          const uint32_t nw = nthr >> 6;
+          const uint32_t e0 = 2u * lane, e1 = e0 + 1u;
+          const uint32_t a = (e0 % kWaves) < nw ? lclass[e0] : 0u, b = (e1 % kWaves) < nw ? lclass[e1] : 0u;
+          uint32_t inc = a + b;
+#pragma unroll
+          for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
+            const uint32_t y = __shfl_up(inc, dlt);
+            if (lane >= dlt) inc += y;
+          }
+          lclass[e0] = inc - a - b;
+          lclass[e1] = inc - b;
+        }
+        __syncthreads();
+        if (tid < n) {
+          const uint32_t pos = lclass[cls * kWaves + wave] + rank;
+          ltile[pos] = rec;
+          lcount[pos] = c;
+        }
+        __syncthreads();
+        c = tid < n ? lcount[tid] : 0u;
       }
       uint32_t x = c;  // inclusive scan of the lane counts: within the wave, then over the waves' totals
 #pragma unroll
