@@ -33,6 +33,7 @@ namespace {
 constexpr int kMaxThreads = 1024;
 // The staging area in LDS is sized at launch: what the plan's largest transposed tile needs, and
 // at least the room the small-tile batches take (one descriptor and one counter per thread).
+constexpr uint32_t kOrderWaves = 4;   // tiles are put in the order of their item sizes inside windows of this many waves
 constexpr uint32_t kItemClasses = 8;  // item sizes 1 .. 16 bytes, converting tiles, and room to a power of two
 constexpr uint32_t small_batch_lds_bytes(uint32_t threads) {
   return threads * (uint32_t)sizeof(TileDesc) + (threads + 1 + kMaxThreads / 64) * 4u + threads * 4u +
@@ -805,9 +806,12 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
         }
         c = c < 1 ? 1u : (c > nthr ? nthr : c);
       }
-      // The slice's tiles are put in the order of their item sizes (stable inside a size): the lanes of a wave
-      // then mostly move items of one size, and a wave issues one load and one store per round and size.
-      // Rank inside the class from ballots, class and wave bases from a scan of the 8 x 16 table of counts.
+      // The tiles of every kOrderWaves waves (256 tiles, neighbours in memory) are put in the order of their item sizes
+      // (stable inside a size): the lanes of a wave then mostly move items of one size, and a wave issues one load
+      // and one store per round and size.  (Ordering the whole slice makes the waves a little more uniform still,
+      // but tiles that share cache lines at their edges are then copied so far apart in time that the lines leave the
+      // L2 in between.)  Rank inside the class from ballots; bases from a scan of the table of counts, whose
+      // entries run window by window, class by class, wave by wave.
       {
         uint32_t rank = 0, mine = 0;
 #pragma unroll
@@ -816,12 +820,15 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
           if (cls == k) rank = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
           if (lane == k) mine = (uint32_t)__popcll(m);
         }
-        if (lane < kItemClasses) lclass[lane * kWaves + wave] = mine;
+        constexpr uint32_t W = kOrderWaves;  // waves per window
+        auto entry = [](uint32_t w, uint32_t k) { return (w / W) * (W * kItemClasses) + k * W + (w % W); };
+        if (lane < kItemClasses) lclass[entry(wave, lane)] = mine;
         __syncthreads();
-        if (wave == 0) {  // exclusive scan of the table, class by class, wave by wave: two entries per lane
+        if (wave == 0) {  // exclusive scan of the table: two entries per lane
           const uint32_t nw = nthr >> 6;
           const uint32_t e0 = 2u * lane, e1 = e0 + 1u;
-          const uint32_t a = (e0 % kWaves) < nw ? lclass[e0] : 0u, b = (e1 % kWaves) < nw ? lclass[e1] : 0u;
+          auto wave_of = [](uint32_t e) { return (e / (W * kItemClasses)) * W + (e % W); };
+          const uint32_t a = wave_of(e0) < nw ? lclass[e0] : 0u, b = wave_of(e1) < nw ? lclass[e1] : 0u;
           uint32_t inc = a + b;
 #pragma unroll
           for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
@@ -833,7 +840,7 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
         }
         __syncthreads();
         if (tid < n) {
-          const uint32_t pos = lclass[cls * kWaves + wave] + rank;
+          const uint32_t pos = lclass[entry(wave, cls)] + rank;
           ltile[pos] = rec;
           lcount[pos] = c;
         }
