@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188960902496,
-             "csrc_sha256": "d3db8b0c9b1777bf55852aea6e44dcba845e1e1a90370893ef50784cd8808193"},
-    "eval_load": {"bytes_per_launch": 41274655843,
-             "csrc_sha256": "d3db8b0c9b1777bf55852aea6e44dcba845e1e1a90370893ef50784cd8808193"},
-    "cfg5_small": {"bytes_per_launch": 1989742439,
-             "csrc_sha256": "d3db8b0c9b1777bf55852aea6e44dcba845e1e1a90370893ef50784cd8808193"},
+    "cfg3": {"bytes_per_launch": 188952044801,
+             "csrc_sha256": "e5a1f4a964f0e228594cf7db93f338cee3e71524ea6c6ed9af1e4ae5d8004361"},
+    "eval_load": {"bytes_per_launch": 41298789649,
+             "csrc_sha256": "e5a1f4a964f0e228594cf7db93f338cee3e71524ea6c6ed9af1e4ae5d8004361"},
+    "cfg5_small": {"bytes_per_launch": 1924864091,
+             "csrc_sha256": "e5a1f4a964f0e228594cf7db93f338cee3e71524ea6c6ed9af1e4ae5d8004361"},
 }
 
 
