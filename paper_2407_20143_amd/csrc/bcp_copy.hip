@@ -779,7 +779,6 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
     uint32_t* lwave = lstart + nthr + 1;                                                 // [waves]
     uint32_t* lcount = lwave + kMaxThreads / 64;                                         // [nthr]
     uint32_t* lclass = lcount + nthr;                                                    // [kItemClasses][waves]
-    constexpr uint32_t kWaves = kMaxThreads / 64;
     for (uint32_t base = 0; base < H.count; base += nthr) {
       const uint32_t n = min(nthr, H.count - base);
       uint32_t c = 0, cls = kItemClasses - 1;

@@ -288,11 +288,12 @@ constexpr int kRecBlock = 128;  // records (threads) per workgroup of the kernel
 // Records rec0 .. rec0 + count of the concatenation [saved | target] come from two arrays (n_saved records in the
 // first); `gather`, if not null, receives them as well, as one array: the caller's two arrays -- in device memory,
 // or in pinned host memory that the device reads over the bus -- then need no copy of their own before the kernel.
+template <bool GATHER>
 __device__ inline void stage_records(const bcp_shard_meta* saved, const bcp_shard_meta* target, int64_t n_saved,
                                      int64_t rec0, int count, uint4* lds, bcp_shard_meta* gather) {
-  const uint4* from_s = reinterpret_cast<const uint4*>(saved);
-  const uint4* from_t = reinterpret_cast<const uint4*>(target);
-  uint4* to = reinterpret_cast<uint4*>(gather);
+  const uint4* __restrict__ from_s = reinterpret_cast<const uint4*>(saved);
+  const uint4* __restrict__ from_t = reinterpret_cast<const uint4*>(target);
+  uint4* __restrict__ to = reinterpret_cast<uint4*>(gather);
   const int64_t g0 = rec0 * kRecChunks, split = n_saved * kRecChunks;  // in 16-byte pieces
   const int chunks = count * kRecChunks;
   uint4 v[kRecChunks];
@@ -300,19 +301,25 @@ __device__ inline void stage_records(const bcp_shard_meta* saved, const bcp_shar
   for (int j = 0; j < kRecChunks; ++j) {
     const int i = j * kRecBlock + (int)threadIdx.x;
     const int64_t g = g0 + (i < chunks ? i : chunks - 1);  // (count >= 1; the copies of the last piece are not stored)
-    v[j] = g < split ? from_s[g] : from_t[g - split];
+    const uint4* at = g < split ? from_s + g : from_t + (g - split);  // (the address is chosen, not the value: one load)
+    v[j] = *at;
   }
 #pragma unroll
   for (int j = 0; j < kRecChunks; ++j) {
     const int i = j * kRecBlock + (int)threadIdx.x;
-    if (i < chunks) {
-      lds[i] = v[j];
-      if (to) to[g0 + i] = v[j];
-    }
+    if (i < chunks) lds[i] = v[j];
   }
   __syncthreads();
+  if (GATHER) {  // (from LDS, not from the registers of the loads: holding them for a second store spills them)
+#pragma unroll
+    for (int j = 0; j < kRecChunks; ++j) {
+      const int i = j * kRecBlock + (int)threadIdx.x;
+      if (i < chunks) to[g0 + i] = lds[i];
+    }
+  }
 }
 
+template <bool GATHER>
 __global__ __launch_bounds__(kRecBlock) void k_validate_count(const bcp_shard_meta* saved, const bcp_shard_meta* target,
                                                               bcp_shard_meta* gather, int64_t n_saved, int64_t n_total,
                                                               uint32_t* nboxes, Ctl* ctl) {
@@ -325,7 +332,7 @@ __global__ __launch_bounds__(kRecBlock) void k_validate_count(const bcp_shard_me
     block_sbuf = block_tbuf = -1;
   }
   const int64_t rec0 = (int64_t)blockIdx.x * kRecBlock;
-  stage_records(saved, target, n_saved, rec0, (int)(n_total - rec0 < kRecBlock ? n_total - rec0 : kRecBlock), staged, gather);
+  stage_records<GATHER>(saved, target, n_saved, rec0, (int)(n_total - rec0 < kRecBlock ? n_total - rec0 : kRecBlock), staged, gather);
   const int64_t i = rec0 + threadIdx.x;
   if (i < n_total) {
     const bcp_shard_meta& r = reinterpret_cast<const bcp_shard_meta*>(staged)[threadIdx.x];
@@ -369,15 +376,39 @@ __global__ __launch_bounds__(kBlock) void k_emit_boxes(const bcp_shard_meta* rec
     const uint32_t first = box_start[i];
     const int nb = (int)(box_start[i + 1] - first);
     if (nb) {
+      int nb_general = nb;
       const bcp_shard_meta& r = recs[i];
       int64_t len[kDims];
       const int n = local_shape(r, len);
-      LocalBox lb[kMaxBoxesPerRecord];
-      decompose_flat_range(len, n, r.flat_begin, r.flat_end, lb);
       bool strided = false;
-      for (int k = 0; k < r.ndim; ++k) strided |= r.strides[k] != 0;
+      int64_t vol = 1;
+      for (int k = 0; k < r.ndim; ++k) {
+        strided |= r.strides[k] != 0;
+        vol *= r.lengths[k];
+      }
       Box* out = staged ? reinterpret_cast<Box*>(stage) + (first - b0) : boxes + first;
-      for (int j = 0; j < nb; ++j) {
+      if (r.flat_begin == 0 && r.flat_end == vol) {
+        // a regular shard (the usual case): its one box is the record's box itself, and the general path below,
+        // whose list of up to fifteen boxes lives in scratch memory, is not entered
+        Box& b = out[0];
+        b.fqn = r.fqn_id;
+        b.rec = (int32_t)(i < n_saved ? i : i - n_saved);
+        b.ndim = n;
+        b.itemsize = r.itemsize;
+        b.buf = r.buf;
+        int64_t st = 1;
+        for (int k = kDims - 1; k >= 0; --k) {
+          b.off[k] = k < r.ndim ? r.offsets[k] : 0;
+          b.len[k] = k < n ? len[k] : 1;
+          b.stride[k] = k >= n ? 0 : (strided ? r.strides[k] : st);
+          if (k < n) st *= len[k];
+        }
+        b.byte_base = r.byte_offset;
+        nb_general = 0;
+      }
+      LocalBox lb[kMaxBoxesPerRecord];
+      if (nb_general) decompose_flat_range(len, n, r.flat_begin, r.flat_end, lb);
+      for (int j = 0; j < nb_general; ++j) {
         Box& b = out[j];
         b.fqn = r.fqn_id;
         b.rec = (int32_t)(i < n_saved ? i : i - n_saved);
@@ -1559,8 +1590,12 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
   BCP_HIP(hipEventRecord(ev0, st));
 
   // 1. validate + count boxes, scan                                                    (sync 1)
-  hipLaunchKernelGGL(k_validate_count, dim3(blocks_for(n_total, kRecBlock)), dim3(kRecBlock), 0, st, from_s, from_t, gather, n_saved,
-                     n_total, box_start, ctl);
+  if (gather)
+    hipLaunchKernelGGL(k_validate_count<true>, dim3(blocks_for(n_total, kRecBlock)), dim3(kRecBlock), 0, st, from_s, from_t, gather,
+                       n_saved, n_total, box_start, ctl);
+  else
+    hipLaunchKernelGGL(k_validate_count<false>, dim3(blocks_for(n_total, kRecBlock)), dim3(kRecBlock), 0, st, from_s, from_t, gather,
+                       n_saved, n_total, box_start, ctl);
   BCP_HIP(hipGetLastError());
   if (bcp_status s = device_scan<uint32_t, uint32_t>(box_start, box_start, n_total, ws, st)) return s;
   if (bcp_status s = read_back(ws, st, ctl, &rb, box_start + n_saved, 4, box_start + n_total, 4)) return s;
