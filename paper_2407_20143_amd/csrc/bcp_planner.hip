@@ -922,27 +922,30 @@ struct WaveStats {
   long long max_src, max_dst;
 };
 
-// Pass 2, one wave per 64 hits of a pass-1 block (workgroup (b, q) takes hits q*64.. of block b; most
-// blocks find fewer than 128, so the later waves of a block leave at once): build the copy regions and
-// write them at blk_off[b] + rank.  The regions of a wave are put together in LDS and leave as one
-// contiguous, coalesced copy (a 280-byte struct stored by each thread on its own is 18 partial-line
-// stores per region).  Waves share nothing, so no wave waits for another one's loads.
+// Pass 2, one wave per 32 hits of a pass-1 block (workgroup (b, q) takes hits q*32.. of block b; most blocks find
+// fewer than 128, so the later workgroups of a block leave at once): build the copy regions and write them at
+// blk_off[b] + rank.  The regions of a workgroup are put together in LDS and leave as one contiguous,
+// coalesced copy (a 280-byte struct stored by each thread on its own is 18 partial-line stores per region).
+// Only half of the wave's lanes build: the kernel waits for its scattered loads and stores, the two boxes
+// of a hit take 116 registers and 32 regions 9 KB of LDS, so 16 waves fit a CU this way -- with 64 hits per
+// wave it is 8, and the kernel takes a quarter longer.  Waves share nothing, so no wave waits for another one's loads.
 constexpr uint32_t kBuildWave = 64;
+constexpr uint32_t kBuildHits = 32;  // hits of a workgroup
 
 __global__ __launch_bounds__(kBuildWave) void k_pairs_build(const Box* boxes, int64_t nbs, const uint2* hits,
                                                             const uint32_t* blk_off, uint32_t tile_bytes, Region* regions,
                                                             uint64_t* tile_cnt, ull* cov, Ctl* ctl, ull* ext,
                                                             uint32_t ext_src_bufs, uint32_t ext_bufs, uint32_t ext_stripes) {
   __shared__ WaveStats ws;
-  __shared__ __attribute__((aligned(16))) char stage[kBuildWave * sizeof(Region)];
-  // (first every block's first 64 hits, then every block's second 64, ...: workgroups go to the chip's
+  __shared__ __attribute__((aligned(16))) char stage[kBuildHits * sizeof(Region)];
+  // (first every block's first 32 hits, then every block's second 32, ...: workgroups go to the chip's
   // eight dies in turn, and with the four waves of a block next to each other some dies would only ever see
   // the later waves, which mostly have nothing to do)
-  const uint32_t n_find_blocks = gridDim.x / (kBlock / kBuildWave);
+  const uint32_t n_find_blocks = gridDim.x / (kBlock / kBuildHits);
   const uint32_t b = blockIdx.x % n_find_blocks, q = blockIdx.x / n_find_blocks;
   const uint32_t first = blk_off[b], cnt = blk_off[b + 1] - first;
-  if (q * kBuildWave >= cnt) return;
-  const uint32_t mine = min(kBuildWave, cnt - q * kBuildWave);
+  if (q * kBuildHits >= cnt) return;
+  const uint32_t mine = min(kBuildHits, cnt - q * kBuildHits);
   if (threadIdx.x == 0) {
     ws.payload = ws.src_bytes = ws.converted = ws.transposed = 0;
     for (int k = 0; k <= kDims; ++k) ws.dims[k] = 0;
@@ -956,12 +959,12 @@ __global__ __launch_bounds__(kBuildWave) void k_pairs_build(const Box* boxes, in
   int src_buf = -1, dst_buf = -1;
   int64_t trec = -1;
   if (active) {
-    const uint2 h = hits[(uint64_t)b * kBlock + q * kBuildWave + threadIdx.x];
+    const uint2 h = hits[(uint64_t)b * kBlock + q * kBuildHits + threadIdx.x];
     // (both boxes whole, in registers, before anything looks at them: their loads are in flight together
     // instead of one dimension's after the other's)
     const Box sbox = boxes[h.x], tbox = boxes[nbs + h.y];
     const Box *sb = &sbox, *tb = &tbox;
-    const uint32_t pos = first + q * kBuildWave + threadIdx.x;
+    const uint32_t pos = first + q * kBuildHits + threadIdx.x;
     Region& R = reinterpret_cast<Region*>(stage)[threadIdx.x];
     int64_t vol = 0;
     build_region(sbox, tbox, tile_bytes, &R, &vol);
@@ -1044,7 +1047,7 @@ __global__ __launch_bounds__(kBuildWave) void k_pairs_build(const Box* boxes, in
   static_assert(sizeof(Region) % 8 == 0, "copied in 8-byte words");
   const uint32_t words = mine * (uint32_t)(sizeof(Region) / 8);
   const uint64_t* from = reinterpret_cast<const uint64_t*>(stage);
-  uint64_t* to = reinterpret_cast<uint64_t*>(regions + first + q * kBuildWave);
+  uint64_t* to = reinterpret_cast<uint64_t*>(regions + first + q * kBuildHits);
   for (uint32_t i = threadIdx.x; i < words; i += kBuildWave) to[i] = from[i];
   if (threadIdx.x == 0) {
     Ctl* part = &(reinterpret_cast<CtlStripe*>(ctl) + 1 + b % kCtlStripes)->c;
@@ -1700,7 +1703,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
     }
     BCP_HIP(block_alloc(&owned.p[0], std::max<size_t>(cap, 1) * sizeof(Region), &owned.bytes[0], st));
     regions = (Region*)owned.p[0];
-    hipLaunchKernelGGL(k_pairs_build, dim3(nblk_pairs * (kBlock / kBuildWave)), dim3(kBuildWave), 0, st, boxes, nbs, hits, blk,
+    hipLaunchKernelGGL(k_pairs_build, dim3(nblk_pairs * (kBlock / kBuildHits)), dim3(kBuildWave), 0, st, boxes, nbs, hits, blk,
                        tile_bytes, regions, tile_start, cov, ctl, ext, ext_src_bufs, ext_bufs, ext_stripes);
     BCP_HIP(hipGetLastError());
     hipLaunchKernelGGL(k_extents_fold, dim3(blocks_for(ext_bufs, kBlock / 64)), dim3(kBlock), 0, st, ext, ext_bufs, ext_stripes);
