@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188954266302,
-             "csrc_sha256": "22e80600b10908dd9ffb5a7649dc02e23051a6a7f08a7d691b10a7e32d0f2a70"},
-    "eval_load": {"bytes_per_launch": 41297646784,
-             "csrc_sha256": "22e80600b10908dd9ffb5a7649dc02e23051a6a7f08a7d691b10a7e32d0f2a70"},
-    "cfg5_small": {"bytes_per_launch": 1925057723,
-             "csrc_sha256": "22e80600b10908dd9ffb5a7649dc02e23051a6a7f08a7d691b10a7e32d0f2a70"},
+    "cfg3": {"bytes_per_launch": 188951865563,
+             "csrc_sha256": "320d182e2f3ed0b4e3bfd0f9cec986a5de62a905823425c7f41bb4291487ec89"},
+    "eval_load": {"bytes_per_launch": 41298049354,
+             "csrc_sha256": "320d182e2f3ed0b4e3bfd0f9cec986a5de62a905823425c7f41bb4291487ec89"},
+    "cfg5_small": {"bytes_per_launch": 1925455711,
+             "csrc_sha256": "320d182e2f3ed0b4e3bfd0f9cec986a5de62a905823425c7f41bb4291487ec89"},
 }
 
 
