@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188951865563,
-             "csrc_sha256": "320d182e2f3ed0b4e3bfd0f9cec986a5de62a905823425c7f41bb4291487ec89"},
-    "eval_load": {"bytes_per_launch": 41298049354,
-             "csrc_sha256": "320d182e2f3ed0b4e3bfd0f9cec986a5de62a905823425c7f41bb4291487ec89"},
-    "cfg5_small": {"bytes_per_launch": 1925455711,
-             "csrc_sha256": "320d182e2f3ed0b4e3bfd0f9cec986a5de62a905823425c7f41bb4291487ec89"},
+    "cfg3": {"bytes_per_launch": 188957544311,
+             "csrc_sha256": "205b487309c32a01abc64f91e1695beaff73e0e2b53d979c149c561c3f7c7a55"},
+    "eval_load": {"bytes_per_launch": 41317211718,
+             "csrc_sha256": "205b487309c32a01abc64f91e1695beaff73e0e2b53d979c149c561c3f7c7a55"},
+    "cfg5_small": {"bytes_per_launch": 1930200459,
+             "csrc_sha256": "205b487309c32a01abc64f91e1695beaff73e0e2b53d979c149c561c3f7c7a55"},
 }
 
 
