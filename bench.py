@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188957544311,
-             "csrc_sha256": "205b487309c32a01abc64f91e1695beaff73e0e2b53d979c149c561c3f7c7a55"},
-    "eval_load": {"bytes_per_launch": 41317211718,
-             "csrc_sha256": "205b487309c32a01abc64f91e1695beaff73e0e2b53d979c149c561c3f7c7a55"},
-    "cfg5_small": {"bytes_per_launch": 1930200459,
-             "csrc_sha256": "205b487309c32a01abc64f91e1695beaff73e0e2b53d979c149c561c3f7c7a55"},
+    "cfg3": {"bytes_per_launch": 188960144834,
+             "csrc_sha256": "3e7573b2faaa2690cedbd300cf5d7ea8a91f453a749d4479a639d086371180db"},
+    "eval_load": {"bytes_per_launch": 41313680848,
+             "csrc_sha256": "3e7573b2faaa2690cedbd300cf5d7ea8a91f453a749d4479a639d086371180db"},
+    "cfg5_small": {"bytes_per_launch": 1929914401,
+             "csrc_sha256": "3e7573b2faaa2690cedbd300cf5d7ea8a91f453a749d4479a639d086371180db"},
 }
 
 

@@ -8,7 +8,12 @@
 //   * misaligned-run path   -- long runs whose source and destination disagree modulo 16 (ZeRO
 //                              slice boundaries): peel to a 16-byte aligned destination, then
 //                              unaligned 16-byte loads + aligned 16-byte stores;
-//   * granule path          -- short runs: 8/4/2/1-byte elements, flat over rows x run;
+//   * granule path          -- whole-workgroup tiles of short misaligned rows: 8/4/2/1-byte granules, flat
+//                              over rows x run;
+//   * small-tile batches    -- tiles below 16 KiB share a workgroup: per tile one item size (16 bytes, or the
+//                              largest power of two a short row holds) at any address, a row's last item
+//                              moved back to end with the row; tiles ordered by item size so that a wave
+//                              issues one load and one store per round;
 //   * LDS-staged transpose  -- the source-contiguous and destination-contiguous dimensions
 //                              differ (strided shards): both global sides stay coalesced;
 //   * narrowing rows        -- dtype-converting loads (fp32 saved, bf16 asked for): 4 bytes read and
