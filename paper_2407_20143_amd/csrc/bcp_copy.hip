@@ -172,8 +172,32 @@ __device__ __forceinline__ void copy_rows(gsrc_t __restrict__ s, gdst_t __restri
   }
 }
 
+// Bytes m .. m + 15 of the 32 bytes [lo | hi], m = 4 q + r the same for every lane.
+__device__ __forceinline__ u32x4 funnel16(const u32x4& lo, const u32x4& hi, uint32_t q, uint32_t r) {
+  uint32_t w0, w1, w2, w3, w4;
+  switch (q) {
+    case 0: w0 = lo[0], w1 = lo[1], w2 = lo[2], w3 = lo[3], w4 = hi[0]; break;
+    case 1: w0 = lo[1], w1 = lo[2], w2 = lo[3], w3 = hi[0], w4 = hi[1]; break;
+    case 2: w0 = lo[2], w1 = lo[3], w2 = hi[0], w3 = hi[1], w4 = hi[2]; break;
+    default: w0 = lo[3], w1 = hi[0], w2 = hi[1], w3 = hi[2], w4 = hi[3]; break;
+  }
+  u32x4 o;  // v_alignbyte_b32: ({high, low} >> 8 r), low word
+  o[0] = __builtin_amdgcn_alignbyte(w1, w0, r);
+  o[1] = __builtin_amdgcn_alignbyte(w2, w1, r);
+  o[2] = __builtin_amdgcn_alignbyte(w3, w2, r);
+  o[3] = __builtin_amdgcn_alignbyte(w4, w3, r);
+  return o;
+}
+
 // one contiguous run whose two sides disagree modulo 16: byte head up to the destination's next
-// 16-byte boundary, aligned 16-byte stores fed by unaligned 16-byte loads, byte tail.
+// 16-byte boundary, then aligned 16-byte stores, byte tail.  What is stored comes from ALIGNED 16-byte loads too
+// (a vector load at an address that is no multiple of 4 is taken apart by the hardware, and one at a multiple of 4
+// still touches two chunks): the wave loads 64 consecutive aligned source chunks, every lane gets its right-hand
+// neighbour's chunk by a shuffle (the last lane loads one chunk more) and shifts the 16 bytes it needs out of
+// the two.  Chunks are read whole, so up to 15 bytes before the run and after it are read as well: they lie in
+// 16-byte pieces that also hold bytes of the run, hence inside the same allocation.
+// nt: a multiple of 64.  U: consecutive strips of 64 output chunks a wave takes per round (its loads in flight).
+template <uint32_t U>
 __device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t run,
                                                     uint32_t tid, uint32_t nt) {
   uint32_t head = (uint32_t)(-(uintptr_t)d) & 15u;
@@ -182,18 +206,40 @@ __device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_
   const uint32_t body = (run - head) >> 4;
   gsrc_t s2 = s + head;
   gdst_t d2 = d + head;
-  uint32_t i = tid;
-  for (; i + 3 * nt < body; i += 4 * nt) {
-    const u32x4 a = ld<-16>(s2 + (size_t)i * 16);
-    const u32x4 b = ld<-16>(s2 + (size_t)(i + nt) * 16);
-    const u32x4 c = ld<-16>(s2 + (size_t)(i + 2 * nt) * 16);
-    const u32x4 e = ld<-16>(s2 + (size_t)(i + 3 * nt) * 16);
-    st<16>(d2 + (size_t)i * 16, a);
-    st<16>(d2 + (size_t)(i + nt) * 16, b);
-    st<16>(d2 + (size_t)(i + 2 * nt) * 16, c);
-    st<16>(d2 + (size_t)(i + 3 * nt) * 16, e);
+  const uint32_t m = (uint32_t)(uintptr_t)s2 & 15u;
+  if (m == 0) {  // (the two sides agree after all)
+    for (uint32_t i = tid; i < body; i += nt) st<16>(d2 + (size_t)i * 16, ld<16>(s2 + (size_t)i * 16));
+  } else {
+    gsrc_t sa = s2 - m;  // aligned; output chunk c is bytes m .. m + 15 of the source chunks c and c + 1
+    const uint32_t q = m >> 2, r = m & 3u;
+    const uint32_t lane = tid & 63u, wave = tid >> 6, nw = nt >> 6;
+    const uint32_t rounds = (body + 64u * U - 1u) / (64u * U);
+    for (uint32_t rd = wave; rd < rounds; rd += nw) {
+      const uint32_t c0 = rd * (64u * U) + lane;   // this lane's chunk of the round's first strip
+      u32x4 lo[U], last = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) {
+        const uint32_t c = c0 + 64u * u;
+        lo[u] = u32x4{0u, 0u, 0u, 0u};
+        if (c <= body) lo[u] = ld<16>(sa + (size_t)c * 16);
+      }
+      // (the chunk after the round's last one: only the last lane of the last strip needs it from memory; inside
+      // the round the next strip's first lane has it)
+      if (lane == 63u && c0 + 64u * (U - 1u) + 1u <= body) last = ld<16>(sa + (size_t)(c0 + 64u * (U - 1u) + 1u) * 16);
+#pragma unroll
+      for (uint32_t u = 0; u < U; ++u) {
+        const uint32_t c = c0 + 64u * u;
+        u32x4 next;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          next[k] = (uint32_t)__shfl_down((int)lo[u][k], 1);
+          const uint32_t first_of_next = u + 1u < U ? (uint32_t)__builtin_amdgcn_readfirstlane((int)lo[u + 1u < U ? u + 1u : u][k]) : last[k];
+          if (lane == 63u) next[k] = first_of_next;
+        }
+        if (c < body) st<16>(d2 + (size_t)c * 16, funnel16(lo[u], next, q, r));
+      }
+    }
   }
-  for (; i < body; i += nt) st<16>(d2 + (size_t)i * 16, ld<-16>(s2 + (size_t)i * 16));
   const uint32_t done = head + (body << 4);
   for (uint32_t i = done + tid; i < run; i += nt) d[i] = s[i];
 }
@@ -566,7 +612,10 @@ __device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __res
 // by binary search in the scanned lane counts, reads the record, decodes its items with a few
 // instructions each, and all loads of the wave are issued -- whatever their sizes and tiles -- before
 // the first store: one round trip per round for lanes that work on different tiles and alignments.
-constexpr int kRound = 3;  // items of a lane in flight (measured: 3 beats 2 by 3 %, and 1 and 4 by more)
+// items of a lane in flight (measured: 3 beats 2 by 3 %, and 1 and 4 by more); the instance with the converting path
+// has no registers left for the third
+constexpr int kRound = 3;
+constexpr int kRoundConverting = 2;
 
 struct SmallTile {  // 64 bytes, takes the descriptor's place in LDS
   enum Mode : uint32_t {
@@ -668,9 +717,9 @@ __device__ __forceinline__ void item_store(gdst_t p, uint32_t gl, const u32x4& v
   else if (gl == 0) *(uint8_t BCP_GLOBAL*)p = (uint8_t)v[0];
 }
 
-// a whole tile by `nt` lanes (tid in [0, nt)), kRound items of a lane in flight at a time
+// a whole tile by `nt` lanes (tid in [0, nt)), R items of a lane in flight at a time
+template <int R>
 __device__ __forceinline__ void small_tile_copy(const SmallTile& c, uint32_t tid, uint32_t nt) {
-  constexpr int R = kRound;
   gsrc_t s = (gsrc_t)c.s;
   gdst_t d = (gdst_t)c.d;
   for (uint32_t base = tid; base < c.n_items; base += R * nt) {
@@ -715,7 +764,7 @@ __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t
         default: transpose_any<16>(s, d, na, nb, spb, dpa, tda, tdb, lds); break;
       }
     } else {  // elements not aligned to their own size (or a plan without staged tiles): item by item
-      small_tile_copy(small_tile(T, s, d), tid, nt);
+      small_tile_copy<CV ? kRoundConverting : kRound>(small_tile(T, s, d), tid, nt);
     }
     return;
   }
@@ -726,7 +775,7 @@ __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t
   if ((al & 15u) == 0) {
     copy_rows<16>(s, d, nrows, run >> 4, sp, dp, tid, nt);
   } else if (run >= 64) {
-    if (nrows == 1) copy_run_misaligned(s, d, run, tid, nt);
+    if (nrows == 1) copy_run_misaligned<4u>(s, d, run, tid, nt);
     else copy_rows_unaligned(s, d, nrows, run, sp, dp, tid, nt);
   } else if ((al & 7u) == 0) {
     copy_rows<8>(s, d, nrows, run >> 3, sp, dp, tid, nt);
@@ -805,7 +854,7 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
           cls = 5;
         } else {
           rec = small_tile(T, src_of(T), dst_of(T));
-          c = (rec.n_items + kRound - 1) / kRound;
+          c = (rec.n_items + (CV ? kRoundConverting : kRound) - 1) / (CV ? kRoundConverting : kRound);
           cls = rec.mode_glog >> 8;  // log2 of the item size: 0 .. 4
         }
         c = c < 1 ? 1u : (c > nthr ? nthr : c);
@@ -875,7 +924,7 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
         const SmallTile st = ltile[lo];
         const uint32_t t0 = lstart[lo], cnt = lstart[lo + 1] - t0;
         if (CV && st.mode_glog == 0xffu) convert_rows((gsrc_t)st.s, (gdst_t)st.d, st.ipr, st.body, st.p0, st.p1, v - t0, cnt);
-        else small_tile_copy(st, v - t0, cnt);
+        else small_tile_copy<CV ? kRoundConverting : kRound>(st, v - t0, cnt);
       }
       __syncthreads();  // the staging area is written again by the next slice or batch
     }
