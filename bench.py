@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188960144834,
-             "csrc_sha256": "3e7573b2faaa2690cedbd300cf5d7ea8a91f453a749d4479a639d086371180db"},
-    "eval_load": {"bytes_per_launch": 41313680848,
-             "csrc_sha256": "3e7573b2faaa2690cedbd300cf5d7ea8a91f453a749d4479a639d086371180db"},
-    "cfg5_small": {"bytes_per_launch": 1929914401,
-             "csrc_sha256": "3e7573b2faaa2690cedbd300cf5d7ea8a91f453a749d4479a639d086371180db"},
+    "cfg3": {"bytes_per_launch": 188957175777,
+             "csrc_sha256": "1fabbdbd24c5fd85e5ddf65e1277a6665de27d257a92b2238048ed8c77539c54"},
+    "eval_load": {"bytes_per_launch": 41268087117,
+             "csrc_sha256": "1fabbdbd24c5fd85e5ddf65e1277a6665de27d257a92b2238048ed8c77539c54"},
+    "cfg5_small": {"bytes_per_launch": 1923370072,
+             "csrc_sha256": "1fabbdbd24c5fd85e5ddf65e1277a6665de27d257a92b2238048ed8c77539c54"},
 }
 
 

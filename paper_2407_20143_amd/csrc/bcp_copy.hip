@@ -6,8 +6,10 @@
 // actual addresses, one of
 //   * 16-byte vector path   -- bases, run length and pitches all 16-byte aligned;
 //   * misaligned-run path   -- long runs whose source and destination disagree modulo 16 (ZeRO
-//                              slice boundaries): peel to a 16-byte aligned destination, then
-//                              unaligned 16-byte loads + aligned 16-byte stores;
+//                              slice boundaries): peel to a 16-byte aligned destination; then aligned
+//                              16-byte loads of the source chunks, each lane taking its right-hand
+//                              neighbour's chunk by a shuffle and funnel-shifting the pair into one
+//                              aligned 16-byte store;
 //   * granule path          -- whole-workgroup tiles of short misaligned rows: 8/4/2/1-byte granules, flat
 //                              over rows x run;
 //   * small-tile batches    -- tiles below 16 KiB share a workgroup: per tile one item size (16 bytes, or the

@@ -68,8 +68,10 @@ struct Region {
 //
 // The queue of the copy kernel hands out BATCHES: one big tile, or a run of consecutive small
 // tiles (each below kSmallTileBytes, together about one tile budget) that the threads of a
-// workgroup share.  `heads[batch]` is a copy of the batch's first tile descriptor with `first`
-// and `count` filled in, so the kernel still needs one descriptor load per queue pop.
+// workgroup share.  `heads[slot]` is a copy of a batch's first tile descriptor with `first`
+// and `count` filled in, so the kernel still needs one descriptor load per queue pop.  Slots are
+// in queue order: the batches in tile order, except that the small-tile batches are spread evenly
+// among the big tiles (plans ordered by source keep tile order throughout).
 struct TileDesc {
   int64_t src_off, dst_off;  // byte offsets inside the source / destination buffer
   int64_t p0, p1;

@@ -1222,48 +1222,77 @@ __global__ __launch_bounds__(kBlock) void k_gather_tiles(const uint32_t* order, 
   weight_out[i] = weight_in[o];
 }
 
+constexpr uint32_t kTailBatches = 256;  // about one batch per workgroup of the copy kernel's grid
+constexpr uint32_t kTailSplit = 4;
+
 // A batch starts at tile i when i is big, follows a big tile, or the running weight of the small
 // tiles crosses a multiple of the batch budget.  wprefix: exclusive scan of weight.
 // key (optional, sorted): a batch never spans two source buffers.
+// flags[i]: low word 1 when a batch starts here, high word 1 when that batch is one of small tiles, so
+// that one scan numbers the batches and, among them, the small-tile ones.
 __global__ __launch_bounds__(kBlock) void k_batch_flags(const uint64_t* weight, const uint64_t* wprefix,
                                                         uint64_t n_tiles, uint32_t budget, const uint64_t* key,
-                                                        uint32_t* flags) {
+                                                        uint64_t* flags) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
   uint32_t f = 1;
-  if (i > 0 && weight[i] != 0 && weight[i - 1] != 0) f = (wprefix[i] / budget) != (wprefix[i - 1] / budget);
+  const bool small = weight[i] != 0;
+  if (i > 0 && small && weight[i - 1] != 0) {
+    // the last kTailBatches budgets of weight are cut kTailSplit times finer: the queue's last round of small-tile
+    // batches then leaves the workgroups idle for a fraction of a batch, not for most of one
+    const uint64_t total = wprefix[n_tiles];
+    auto cell = [&](uint64_t w) {
+      const uint64_t q = w / budget;
+      return q * kTailSplit + (total - w <= (uint64_t)kTailBatches * budget ? (w - q * budget) * kTailSplit / budget : 0);
+    };
+    f = cell(wprefix[i]) != cell(wprefix[i - 1]);
+  }
   if (key && i > 0 && (key[i] >> kKeyShift) != (key[i - 1] >> kKeyShift)) f = 1;
-  flags[i] = f;
+  flags[i] = f ? (small ? (1ull << 32) | 1ull : 1ull) : 0ull;
 }
 
-// batch_id: exclusive scan of the start flags, so a start tile's batch is batch_id[i]; bstart[b] is
+__device__ __forceinline__ uint32_t batch_of(uint64_t scanned) { return (uint32_t)scanned; }
+
+// batch_id: exclusive scan of the start flags, so a start tile's batch is batch_of(batch_id[i]); bstart[b] is
 // batch b's first tile, with a sentinel after the last batch.
-__global__ __launch_bounds__(kBlock) void k_batch_starts(const uint32_t* batch_id, uint64_t n_tiles, uint32_t* bstart) {
+__global__ __launch_bounds__(kBlock) void k_batch_starts(const uint64_t* batch_id, uint64_t n_tiles, uint32_t* bstart) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i > n_tiles) return;
   if (i == n_tiles) {
-    bstart[batch_id[n_tiles]] = (uint32_t)n_tiles;
+    bstart[batch_of(batch_id[n_tiles])] = (uint32_t)n_tiles;
     return;
   }
-  if (batch_id[i + 1] != batch_id[i]) bstart[batch_id[i]] = (uint32_t)i;
+  if (batch_of(batch_id[i + 1]) != batch_of(batch_id[i])) bstart[batch_of(batch_id[i])] = (uint32_t)i;
 }
 
-// Pass B, one thread per tile: the decoded descriptor goes to heads[batch] when the tile opens a
+// Where batch b goes in the queue.  Plans in plan order spread their small-tile batches evenly among the
+// big tiles: a workgroup on a small-tile batch waits on memory latency most of the time, and the workgroups
+// streaming big tiles beside it keep the memory busy meanwhile, which a stretch of the queue made of small-tile
+// batches alone cannot.  With n batches, S of them small: the k-th small one takes the slot where
+// floor(slot * S / n) steps to k + 1, the j-th big one slot floor(j * n / (n - S)); together a permutation.
+__device__ __forceinline__ uint32_t batch_slot(uint32_t b, uint32_t small_rank, bool small, uint64_t n, uint64_t S) {
+  if (S == 0 || S == n) return b;
+  if (small) return (uint32_t)((((uint64_t)small_rank + 1) * n + S - 1) / S - 1);
+  return (uint32_t)(((uint64_t)(b - small_rank) * n) / (n - S));
+}
+
+// Pass B, one thread per tile: the decoded descriptor goes to heads[slot of its batch] when the tile opens a
 // batch and to tiles[i] when it is small (members of multi-tile batches are fetched from there).
-// key / batch_key (optional, source-ordered plans): batch_key[b] = key of the batch's last tile,
-// the largest in the batch.
+// key / batch_key (optional, source-ordered plans, whose batches keep their order): batch_key[b] = key of
+// the batch's last tile, the largest in the batch.
 __global__ __launch_bounds__(kBlock) void k_fill_tiles(const Region* regions, const uint32_t* tile_region,
                                                        const uint32_t* tile_local, const uint64_t* weight,
-                                                       const uint32_t* batch_id, const uint32_t* bstart,
+                                                       const uint64_t* batch_id, const uint32_t* bstart,
                                                        uint64_t n_tiles, TileDesc* tiles, TileDesc* heads,
                                                        const uint64_t* key, uint64_t* batch_key) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
-  const bool opens = batch_id[i + 1] != batch_id[i];
+  const uint64_t id = batch_id[i];
+  const bool opens = batch_of(batch_id[i + 1]) != batch_of(id);
   const bool small = weight[i] != 0;
-  if (key && (i + 1 == n_tiles || batch_id[i + 2] != batch_id[i + 1])) {
+  if (key && (i + 1 == n_tiles || batch_of(batch_id[i + 2]) != batch_of(batch_id[i + 1]))) {
     // tile i closes its batch (the next tile opens one, or there is none)
-    batch_key[batch_id[i + 1] - 1] = key[i];
+    batch_key[batch_of(batch_id[i + 1]) - 1] = key[i];
   }
   if (!opens && !small) return;
   TileDesc t;
@@ -1271,9 +1300,10 @@ __global__ __launch_bounds__(kBlock) void k_fill_tiles(const Region* regions, co
   t.first = (uint32_t)i;
   if (small) tiles[i] = t;
   if (opens) {
-    const uint32_t b = batch_id[i];
+    const uint32_t b = batch_of(id);
     t.count = bstart[b + 1] - bstart[b];
-    heads[b] = t;
+    const uint64_t total = batch_id[n_tiles];
+    heads[key ? b : batch_slot(b, (uint32_t)(id >> 32), small, batch_of(total), total >> 32)] = t;
   }
 }
 
@@ -1741,7 +1771,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       uint64_t* wprefix = nullptr;
       uint32_t* tile_region = nullptr;
       uint32_t* tile_local = nullptr;
-      uint32_t* bflags = nullptr;
+      uint64_t* bflags = nullptr;
       uint32_t* bstart = nullptr;
       uint64_t* key = nullptr;
       uint32_t* order = nullptr;
@@ -1799,7 +1829,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       if (bcp_status s = device_scan<uint64_t, uint64_t>(weight, wprefix, (int64_t)n_tiles, ws, st)) return s;
       hipLaunchKernelGGL(k_batch_flags, dim3(nblk), dim3(kBlock), 0, st, weight, wprefix, n_tiles, tile_bytes * kSmallBatchTiles, key, bflags);
       BCP_HIP(hipGetLastError());
-      if (bcp_status s = device_scan<uint32_t, uint32_t>(bflags, bflags, (int64_t)n_tiles, ws, st)) return s;
+      if (bcp_status s = device_scan<uint64_t, uint64_t>(bflags, bflags, (int64_t)n_tiles, ws, st)) return s;
       hipLaunchKernelGGL(k_batch_starts, dim3(nblk), dim3(kBlock), 0, st, bflags, n_tiles, bstart);
       hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, regions, tile_region, tile_local, weight,
                          bflags, bstart, n_tiles, tiles, heads, key, out->dev.batch_key);
@@ -1807,7 +1837,7 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       // the extents of the buffers the plan uses come back with the batch count
       const size_t n_src = (size_t)(h.max_src_buf + 1), n_dst = (size_t)(h.max_dst_buf + 1);
       BCP_HIP(ensure_landing(ws, kLandingExtents + sizeof(ull) * (n_src + n_dst)));  // (nothing is in flight into it)
-      hipLaunchKernelGGL(k_final_readback, dim3(1), dim3(kBlock), 0, st, bflags + n_tiles, ext, (uint32_t)n_src,
+      hipLaunchKernelGGL(k_final_readback, dim3(1), dim3(kBlock), 0, st, (const uint32_t*)(bflags + n_tiles), ext, (uint32_t)n_src,
                          ext + ext_src_bufs, (uint32_t)n_dst, (char*)ws.landing_dev);
       BCP_HIP(hipGetLastError());
       out->src_extent.resize(n_src);
