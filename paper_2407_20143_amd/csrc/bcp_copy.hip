@@ -19,7 +19,9 @@
 //   * LDS-staged transpose  -- the source-contiguous and destination-contiguous dimensions
 //                              differ (strided shards): both global sides stay coalesced;
 //   * narrowing rows        -- dtype-converting loads (fp32 saved, bf16 asked for): 4 bytes read and
-//                              2 written per element, eight elements per lane and access.
+//                              2 written per element; a wave takes 512 elements with two load instructions
+//                              that each cover 1 KiB without gaps, neighbouring lanes swap halves and
+//                              every lane stores 16 bytes.
 // Scheduling: a persistent grid of (CU count x wg_per_cu) workgroups pops batch indices from an
 // atomic queue; a batch is one big tile (whole workgroup) or a run of small tiles that share the
 // workgroup's threads in proportion to their size, so 100k tiny tensors do not cost one queue pop
@@ -532,9 +534,62 @@ __device__ __forceinline__ void narrow_one(gsrc_t s, gdst_t d) {
 
 // `nrows` rows of `n` elements; source rows sp bytes apart, destination rows dp bytes apart.  Fast
 // path: groups of eight elements, two 16-byte loads (at any 4-byte aligned address) and one aligned
-// 16-byte store.  One long row is peeled to the destination's next 16-byte boundary first; rows that
+// 16-byte store; whole waves take 64 groups at a time (convert_units) and leave a lane a group of its
+// own only for the last groups of a row.  One long row is peeled to the destination's next 16-byte boundary first; rows that
 // rule the groups out (odd addresses, a destination pitch or run that breaks the alignment from row to
 // row) go element by element.  No barriers: any group of threads may run it.
+// Units of 64 groups, a wave each: 2 KiB of source as two load instructions that each cover 1 KiB without
+// gaps (lane l: chunk l, then chunk 64 + l), where a lane reading the two chunks of its own group would
+// leave every other chunk of the lines an instruction touches to the next one (measured: 73 -> 79 % of
+// peak).  Narrowed, the chunks are half a store each: lane 2k keeps its first (elements 8k .. 8k+3 of the
+// unit), sends its second to lane 2k+1 and gets that lane's first (8k+4 .. 8k+7): output chunk k; lane
+// 2k+1 stores output chunk 32 + k.  `nrows` rows with the first `upr` units of each; tid counts whole waves.
+__device__ __forceinline__ void convert_units(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows, uint32_t upr,
+                                              int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
+  asm volatile("" : "+v"(tid));  // opaque, see transpose_full_tile
+  const uint32_t lane = tid & 63u, nw = nt >> 6, units = nrows * upr;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));  // (scalar: so is what follows from it)
+  const bool odd = (lane & 1u) != 0;
+  const uint32_t out_off = (odd ? 512u : 0u) + 16u * (lane >> 1);
+  auto finish = [&](const u32x4& a, const u32x4& b, gdst_t du) {
+    const uint32_t a0 = narrow_pair(a[0], a[1]), a1 = narrow_pair(a[2], a[3]);
+    const uint32_t b0 = narrow_pair(b[0], b[1]), b1 = narrow_pair(b[2], b[3]);
+    // (quad_perm [1,0,3,2]: every lane reads its neighbour in the pair)
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)(odd ? a0 : b0), 0xB1, 0xF, 0xF, true);
+    const uint32_t r1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)(odd ? a1 : b1), 0xB1, 0xF, 0xF, true);
+    const u32x4 out = odd ? u32x4{r0, r1, b0, b1} : u32x4{a0, a1, r0, r1};
+    st<16>(du + out_off, out);
+  };
+  auto place = [&](uint32_t unit, gsrc_t* su, gdst_t* du) {  // (the same for all lanes of the wave)
+    const uint32_t row = nrows == 1 ? 0 : unit / upr, cu = unit - row * upr;
+    *su = s + (int64_t)row * sp + (size_t)cu * 2048 + lane * 16u;
+    *du = d + (int64_t)row * dp + (size_t)cu * 1024;
+  };
+  uint32_t unit = wave;
+  for (; unit + 3 * nw < units; unit += 4 * nw) {  // four units of a wave in flight: 128 bytes of loads per lane
+    u32x4 a[4], b[4];
+    gdst_t du[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      gsrc_t su;
+      place(unit + u * nw, &su, &du[u]);
+      a[u] = ld<-16>(su);
+      b[u] = ld<-16>(su + 1024);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) finish(a[u], b[u], du[u]);
+  }
+  for (; unit < units; unit += nw) {
+    gsrc_t su;
+    gdst_t du;
+    place(unit, &su, &du);
+    const u32x4 a = ld<-16>(su), b = ld<-16>(su + 1024);
+    finish(a, b, du);
+  }
+}
+
+// WAVES: tid counts whole waves (nt a multiple of 64, lane == tid % 64), which lets the lanes of a wave share a unit.
+template <bool WAVES>
 __device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows, uint32_t n,
                                              int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
   const bool src4 = (((uintptr_t)s | (nrows > 1 ? (uintptr_t)sp : 0)) & 3u) == 0;
@@ -546,6 +601,11 @@ __device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __res
     gsrc_t s2 = s + (size_t)head * 4;
     gdst_t d2 = d + (size_t)head * 2;
     uint32_t g = tid;
+    if constexpr (WAVES) {
+      const uint32_t units = groups >> 6;
+      convert_units(s2, d2, 1u, units, 0, 0, tid, nt);
+      g = (units << 6) + tid;  // the groups after the last whole unit, one lane each
+    }
     for (; g + 3 * nt < groups; g += 4 * nt) {  // four groups of a lane in flight: 128 bytes of loads
       u32x4 a[4], b[4];
 #pragma unroll
@@ -564,7 +624,18 @@ __device__ __forceinline__ void convert_rows(gsrc_t __restrict__ s, gdst_t __res
     return;
   }
   if (nrows > 1 && src4 && (((uintptr_t)d | (uintptr_t)dp) & 15u) == 0 && (n & 7u) == 0) {
-    const uint32_t gpr = n >> 3, total = nrows * gpr;  // groups per row
+    uint32_t gpr = n >> 3;  // groups per row
+    if constexpr (WAVES) {  // whole units first, then what is left of every row, group by group
+      const uint32_t upr = gpr >> 6;
+      if (upr) {
+        convert_units(s, d, nrows, upr, sp, dp, tid, nt);
+        s += (size_t)upr * 2048;
+        d += (size_t)upr * 1024;
+        gpr &= 63u;
+        if (gpr == 0) return;
+      }
+    }
+    const uint32_t total = nrows * gpr;
     uint32_t row = tid / gpr, col = tid - row * gpr;
     const uint32_t drow = nt / gpr, dcol = nt - drow * gpr;
     auto advance = [&]() {
@@ -749,7 +820,7 @@ template <bool TR, bool CV>
 __device__ __forceinline__ void process_tile(const TileDesc& T, gsrc_t s, gdst_t d, char* lds, uint32_t tid,
                                              uint32_t nt) {
   if (CV && (T.kind & 0xffu) == kConvert) {
-    convert_rows(s, d, T.b, T.a, T.p0, T.p1, tid, nt);
+    convert_rows<true>(s, d, T.b, T.a, T.p0, T.p1, tid, nt);
     return;
   }
   if ((T.kind & 0xffu) == kTranspose) {
@@ -925,7 +996,7 @@ __device__ __forceinline__ void reshard_body(const TileDesc* __restrict__ heads,
         }
         const SmallTile st = ltile[lo];
         const uint32_t t0 = lstart[lo], cnt = lstart[lo + 1] - t0;
-        if (CV && st.mode_glog == 0xffu) convert_rows((gsrc_t)st.s, (gdst_t)st.d, st.ipr, st.body, st.p0, st.p1, v - t0, cnt);
+        if (CV && st.mode_glog == 0xffu) convert_rows<false>((gsrc_t)st.s, (gdst_t)st.d, st.ipr, st.body, st.p0, st.p1, v - t0, cnt);
         else small_tile_copy<CV ? kRoundConverting : kRound>(st, v - t0, cnt);
       }
       __syncthreads();  // the staging area is written again by the next slice or batch

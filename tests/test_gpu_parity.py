@@ -86,6 +86,26 @@ def test_convert_every_upper_half_and_the_rounding_edges():
     p.destroy()
 
 
+@pytest.mark.parametrize("n1", [504, 512, 520, 1032, 2752])
+def test_convert_rows_around_the_64_group_units(n1):
+    """Big converting tiles take whole units of 64 groups (512 elements) a wave at a time and the rest of every
+    row group by group: rows just below, at and above one unit, and a row of five units and 24 groups; one
+    long run with the destination 6 bytes off a 16-byte boundary besides."""
+    rows, n = 72, n1 + 1024
+    spec = TensorSpec(0, "w", (rows, n), torch.float32, ("bits",))
+    saved = Layout([regular(Part(0, (rows, n), (0, 0), (rows, n)), 4, 0, 0)], [rows * n * 4])
+    left, right = Part(0, (rows, n), (0, 0), (rows, n1)), Part(0, (rows, n), (0, n1), (rows, 1024))
+    target = Layout([regular(left, 2, 0, 0), regular(right, 2, 1, 0)], [rows * n1 * 2, rows * 1024 * 2])
+    check_case(Case("convert_rows", 40 + n1, {0: spec}, saved, target, convert=1), also_closed_form=False)
+    flat = rows * n
+    spec = TensorSpec(0, "f", (flat,), torch.float32, ("bits",))
+    saved = Layout([regular(Part(0, (flat,), (0,), (flat,)), 4, 0, 0)], [flat * 4])
+    cut = 8 * n1 + 3
+    target = Layout([regular(Part(0, (flat,), (0,), (cut,)), 2, 0, 6), regular(Part(0, (flat,), (cut,), (flat - cut,)), 2, 1, 0)],
+                    [cut * 2 + 6, (flat - cut) * 2])
+    check_case(Case("convert_flat", 41 + n1, {0: spec}, saved, target, convert=1), also_closed_form=False)
+
+
 def test_convert_model_shaped_scaled():
     for case in (synth.eval_load_case(layers=2, hidden=256, ffn=688, vocab=1000),
                  synth.eval_load_case(layers=2, hidden=264, ffn=696, vocab=1000, zero_saved=True)):
