@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188957175777,
-             "csrc_sha256": "1fabbdbd24c5fd85e5ddf65e1277a6665de27d257a92b2238048ed8c77539c54"},
-    "eval_load": {"bytes_per_launch": 41268087117,
-             "csrc_sha256": "1fabbdbd24c5fd85e5ddf65e1277a6665de27d257a92b2238048ed8c77539c54"},
-    "cfg5_small": {"bytes_per_launch": 1923370072,
-             "csrc_sha256": "1fabbdbd24c5fd85e5ddf65e1277a6665de27d257a92b2238048ed8c77539c54"},
+    "cfg3": {"bytes_per_launch": 188957483511,
+             "csrc_sha256": "a76a398904d3ab87d9b540cbf617a8dfb19799dac9af21b894ae4a0ab3097314"},
+    "eval_load": {"bytes_per_launch": 40468586931,
+             "csrc_sha256": "a76a398904d3ab87d9b540cbf617a8dfb19799dac9af21b894ae4a0ab3097314"},
+    "cfg5_small": {"bytes_per_launch": 1929209766,
+             "csrc_sha256": "a76a398904d3ab87d9b540cbf617a8dfb19799dac9af21b894ae4a0ab3097314"},
 }
 
 

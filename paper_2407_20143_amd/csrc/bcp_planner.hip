@@ -1222,9 +1222,6 @@ __global__ __launch_bounds__(kBlock) void k_gather_tiles(const uint32_t* order, 
   weight_out[i] = weight_in[o];
 }
 
-constexpr uint32_t kTailBatches = 256;  // about one batch per workgroup of the copy kernel's grid
-constexpr uint32_t kTailSplit = 4;
-
 // A batch starts at tile i when i is big, follows a big tile, or the running weight of the small
 // tiles crosses a multiple of the batch budget.  wprefix: exclusive scan of weight.
 // key (optional, sorted): a batch never spans two source buffers.
@@ -1237,16 +1234,7 @@ __global__ __launch_bounds__(kBlock) void k_batch_flags(const uint64_t* weight, 
   if (i >= n_tiles) return;
   uint32_t f = 1;
   const bool small = weight[i] != 0;
-  if (i > 0 && small && weight[i - 1] != 0) {
-    // the last kTailBatches budgets of weight are cut kTailSplit times finer: the queue's last round of small-tile
-    // batches then leaves the workgroups idle for a fraction of a batch, not for most of one
-    const uint64_t total = wprefix[n_tiles];
-    auto cell = [&](uint64_t w) {
-      const uint64_t q = w / budget;
-      return q * kTailSplit + (total - w <= (uint64_t)kTailBatches * budget ? (w - q * budget) * kTailSplit / budget : 0);
-    };
-    f = cell(wprefix[i]) != cell(wprefix[i - 1]);
-  }
+  if (i > 0 && small && weight[i - 1] != 0) f = (wprefix[i] / budget) != (wprefix[i - 1] / budget);
   if (key && i > 0 && (key[i] >> kKeyShift) != (key[i - 1] >> kKeyShift)) f = 1;
   flags[i] = f ? (small ? (1ull << 32) | 1ull : 1ull) : 0ull;
 }
