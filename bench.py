@@ -102,10 +102,10 @@ def build_case(name: str):
                 f"fp32 [16384,16384] <-> 128 column blocks, 512-byte runs at a 64 KiB pitch on the {side} side, no transposition")
     if name == "fused_qkv":
         return synth.fused_qkv_case(), "fused GQA QKV blobs (32 layers, h4096, 32q/8kv heads) TP4 -> separate q,k,v TP2"
-    if name.startswith("copy"):  # copy, copy_s4 (source shifted 4 bytes), copy_d4, copy_d2 ...
+    if name.startswith("copy"):  # copy, copy_s4 (source shifted 4 bytes), copy_d4, copy_d2, copy_b4 (both sides) ...
         shift = int(name.split("_")[1][1:]) if "_" in name else 0
         side = name.split("_")[1][0] if "_" in name else "s"
-        return (synth.copy_case(8 << 30, shift if side == "s" else 0, shift if side == "d" else 0),
+        return (synth.copy_case(8 << 30, shift if side in "sb" else 0, shift if side in "db" else 0),
                 "plain copy of one 8 GiB byte tensor through the reshard kernel (bandwidth ceiling)")
     raise SystemExit(f"unknown workload {name}")
 
