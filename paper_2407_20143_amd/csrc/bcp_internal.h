@@ -66,19 +66,21 @@ struct Region {
 //               p0 along b, the destination contiguous along b with pitch p1 along a
 //   kConvert:   `b` rows of `a` ELEMENTS (4 bytes in the source, 2 in the destination), pitches in bytes
 //
-// The queue of the copy kernel hands out BATCHES: one big tile, or a run of consecutive small
-// tiles (each below kSmallTileBytes, together about one tile budget) that the threads of a
-// workgroup share.  `heads[slot]` is a copy of a batch's first tile descriptor with `first`
-// and `count` filled in, so the kernel still needs one descriptor load per queue pop.  Slots are
-// in queue order: the batches in tile order, except that the small-tile batches are spread evenly
-// among the big tiles (plans ordered by source keep tile order throughout).
+// The queue of the copy kernel hands out BATCHES: one big tile, or a run of small tiles (each
+// below kSmallTileBytes, together a few tile budgets) that the threads of a workgroup share.  The
+// small tiles are numbered among themselves, in tile order, and `tiles[]` holds them by that number:
+// a batch is a run of it, whatever big tiles stand between its members in tile order.
+// `heads[slot]` is a copy of a batch's first tile descriptor with `first` and `count` filled in,
+// so the kernel still needs one descriptor load per queue pop.  Slots are in queue order: the big
+// tiles in tile order with the small-tile batches spread evenly among them (plans ordered by
+// source keep tile order throughout, and their batches are runs of consecutive tiles).
 struct TileDesc {
   int64_t src_off, dst_off;  // byte offsets inside the source / destination buffer
   int64_t p0, p1;
   uint32_t a, b;
   uint32_t src_buf, dst_buf;
   uint32_t kind;             // RegionKind | esize << 8 | kTranspose: log2 of the full tile's edges, a << 16, b << 24
-  uint32_t first;            // heads[] only: index of the batch's first tile
+  uint32_t first;            // heads[] only: index in tiles[] of the batch's first tile
   uint32_t count;            // heads[] only: tiles in the batch
   uint32_t pad_;
 };

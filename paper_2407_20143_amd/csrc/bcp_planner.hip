@@ -1222,76 +1222,101 @@ __global__ __launch_bounds__(kBlock) void k_gather_tiles(const uint32_t* order, 
   weight_out[i] = weight_in[o];
 }
 
-// A batch starts at tile i when i is big, follows a big tile, or the running weight of the small
-// tiles crosses a multiple of the batch budget.  wprefix: exclusive scan of weight.
-// key (optional, sorted): a batch never spans two source buffers.
-// flags[i]: low word 1 when a batch starts here, high word 1 when that batch is one of small tiles, so
-// that one scan numbers the batches and, among them, the small-tile ones.
+// Batches.  A big tile (weight 0) is a batch of its own.  The small tiles form batches among themselves,
+// in tile order but across the big tiles that stand between them (a long run's last few KiB, a bias between
+// two matrices: alone in a batch each would cost a workgroup more than a full tile does): with wprefix the
+// exclusive scan of the weights -- which the big tiles do not move -- a small tile belongs to the budget
+// window its END falls into, (wprefix + weight - 1) / budget, and opens a batch when the small tile before
+// it, which ends at wprefix, belongs to an earlier one.  Ends are at least kMinBatchWeight apart, so a batch
+// has at most budget / kMinBatchWeight tiles, and less than budget + kSmallTileBytes of weight.
+// key (optional, sorted; plans ordered by source): batches stay runs of consecutive tiles and never span
+// two source buffers, so a small tile after a big one or in another buffer opens a batch as well.
+// flags[i]: low word 1 for a small tile, high word 1 when it opens a batch; scanned, the words are the
+// tile's index among the small tiles and its batch's index among the small-tile batches.
 __global__ __launch_bounds__(kBlock) void k_batch_flags(const uint64_t* weight, const uint64_t* wprefix,
                                                         uint64_t n_tiles, uint32_t budget, const uint64_t* key,
                                                         uint64_t* flags) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
-  uint32_t f = 1;
-  const bool small = weight[i] != 0;
-  if (i > 0 && small && weight[i - 1] != 0) f = (wprefix[i] / budget) != (wprefix[i - 1] / budget);
-  if (key && i > 0 && (key[i] >> kKeyShift) != (key[i - 1] >> kKeyShift)) f = 1;
-  flags[i] = f ? (small ? (1ull << 32) | 1ull : 1ull) : 0ull;
+  const uint64_t w = weight[i], before = wprefix[i];
+  if (w == 0) {
+    flags[i] = 0;
+    return;
+  }
+  bool opens = before == 0 || (before + w - 1) / budget != (before - 1) / budget;
+  if (key && i > 0 && (weight[i - 1] == 0 || (key[i] >> kKeyShift) != (key[i - 1] >> kKeyShift))) opens = true;
+  flags[i] = opens ? (1ull << 32) | 1ull : 1ull;
 }
 
-__device__ __forceinline__ uint32_t batch_of(uint64_t scanned) { return (uint32_t)scanned; }
+// What the scanned flags say about tile i (scan[i], and scan[i + 1] for what the tile itself adds).
+struct TileRank {
+  uint32_t small_rank;   // small tiles before it
+  uint32_t small_batch;  // small-tile batches opened before it
+  bool small, opens;     // opens: a batch starts here (every big tile; a small one as flagged)
+  __device__ uint32_t big_rank(uint64_t i) const { return (uint32_t)(i - small_rank); }
+};
+__device__ __forceinline__ TileRank tile_rank(const uint64_t* scan, uint64_t i) {
+  const uint64_t a = scan[i], b = scan[i + 1];
+  TileRank r;
+  r.small_rank = (uint32_t)a;
+  r.small_batch = (uint32_t)(a >> 32);
+  r.small = (uint32_t)b != (uint32_t)a;
+  r.opens = !r.small || (b >> 32) != (a >> 32);
+  return r;
+}
 
-// batch_id: exclusive scan of the start flags, so a start tile's batch is batch_of(batch_id[i]); bstart[b] is
-// batch b's first tile, with a sentinel after the last batch.
-__global__ __launch_bounds__(kBlock) void k_batch_starts(const uint64_t* batch_id, uint64_t n_tiles, uint32_t* bstart) {
+// bstart[k]: index among the small tiles of small-tile batch k's first tile, with a sentinel after the last batch.
+__global__ __launch_bounds__(kBlock) void k_batch_starts(const uint64_t* scan, uint64_t n_tiles, uint32_t* bstart) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i > n_tiles) return;
   if (i == n_tiles) {
-    bstart[batch_of(batch_id[n_tiles])] = (uint32_t)n_tiles;
+    bstart[(uint32_t)(scan[n_tiles] >> 32)] = (uint32_t)scan[n_tiles];
     return;
   }
-  if (batch_of(batch_id[i + 1]) != batch_of(batch_id[i])) bstart[batch_of(batch_id[i])] = (uint32_t)i;
+  const TileRank r = tile_rank(scan, i);
+  if (r.small && r.opens) bstart[r.small_batch] = r.small_rank;
 }
 
-// Where batch b goes in the queue.  Plans in plan order spread their small-tile batches evenly among the
+// Where a batch goes in the queue.  Plans in plan order spread their small-tile batches evenly among the
 // big tiles: a workgroup on a small-tile batch waits on memory latency most of the time, and the workgroups
 // streaming big tiles beside it keep the memory busy meanwhile, which a stretch of the queue made of small-tile
 // batches alone cannot.  With n batches, S of them small: the k-th small one takes the slot where
 // floor(slot * S / n) steps to k + 1, the j-th big one slot floor(j * n / (n - S)); together a permutation.
-__device__ __forceinline__ uint32_t batch_slot(uint32_t b, uint32_t small_rank, bool small, uint64_t n, uint64_t S) {
-  if (S == 0 || S == n) return b;
-  if (small) return (uint32_t)((((uint64_t)small_rank + 1) * n + S - 1) / S - 1);
-  return (uint32_t)(((uint64_t)(b - small_rank) * n) / (n - S));
+__device__ __forceinline__ uint32_t small_batch_slot(uint32_t k, uint64_t n, uint64_t S) {
+  return (uint32_t)((((uint64_t)k + 1) * n + S - 1) / S - 1);
+}
+__device__ __forceinline__ uint32_t big_tile_slot(uint32_t j, uint64_t n, uint64_t S) {
+  return (uint32_t)(((uint64_t)j * n) / (n - S));
 }
 
 // Pass B, one thread per tile: the decoded descriptor goes to heads[slot of its batch] when the tile opens a
-// batch and to tiles[i] when it is small (members of multi-tile batches are fetched from there).
-// key / batch_key (optional, source-ordered plans, whose batches keep their order): batch_key[b] = key of
-// the batch's last tile, the largest in the batch.
+// batch and, when it is small, to tiles[its index among the small tiles] (members of multi-tile batches are
+// fetched from there).
+// key / batch_key (optional, source-ordered plans): batches keep tile order, slot = big tiles before it +
+// small-tile batches before it; batch_key[slot] = key of the batch's last tile, the largest in the batch.
 __global__ __launch_bounds__(kBlock) void k_fill_tiles(const Region* regions, const uint32_t* tile_region,
-                                                       const uint32_t* tile_local, const uint64_t* weight,
-                                                       const uint64_t* batch_id, const uint32_t* bstart,
-                                                       uint64_t n_tiles, TileDesc* tiles, TileDesc* heads,
-                                                       const uint64_t* key, uint64_t* batch_key) {
+                                                       const uint32_t* tile_local, const uint64_t* scan,
+                                                       const uint32_t* bstart, uint64_t n_tiles, TileDesc* tiles,
+                                                       TileDesc* heads, const uint64_t* key, uint64_t* batch_key) {
   const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_tiles) return;
-  const uint64_t id = batch_id[i];
-  const bool opens = batch_of(batch_id[i + 1]) != batch_of(id);
-  const bool small = weight[i] != 0;
-  if (key && (i + 1 == n_tiles || batch_of(batch_id[i + 2]) != batch_of(batch_id[i + 1]))) {
+  const TileRank r = tile_rank(scan, i);
+  if (key && (i + 1 == n_tiles || tile_rank(scan, i + 1).opens)) {
     // tile i closes its batch (the next tile opens one, or there is none)
-    batch_key[batch_of(batch_id[i + 1]) - 1] = key[i];
+    batch_key[r.big_rank(i) + r.small_batch + (r.small && r.opens ? 1u : 0u) - (r.small ? 1u : 0u)] = key[i];
   }
-  if (!opens && !small) return;
   TileDesc t;
   decode_tile(regions[tile_region[i]], tile_local[i], &t);
-  t.first = (uint32_t)i;
-  if (small) tiles[i] = t;
-  if (opens) {
-    const uint32_t b = batch_of(id);
-    t.count = bstart[b + 1] - bstart[b];
-    const uint64_t total = batch_id[n_tiles];
-    heads[key ? b : batch_slot(b, (uint32_t)(id >> 32), small, batch_of(total), total >> 32)] = t;
+  t.first = r.small_rank;
+  if (r.small) tiles[r.small_rank] = t;
+  if (r.opens) {
+    const uint64_t total = scan[n_tiles];
+    const uint64_t S = total >> 32, n = n_tiles - (uint32_t)total + S;
+    t.count = r.small ? bstart[r.small_batch + 1] - bstart[r.small_batch] : 1u;
+    uint32_t slot;
+    if (key || S == 0 || S == n) slot = r.big_rank(i) + r.small_batch;
+    else slot = r.small ? small_batch_slot(r.small_batch, n, S) : big_tile_slot(r.big_rank(i), n, S);
+    heads[slot] = t;
   }
 }
 
@@ -1532,9 +1557,11 @@ bcp_status read_back(Workspace& ws, hipStream_t st, Ctl* ctl, Readback* host, co
 }
 
 // the last read-back of a plan: the batch count and, per buffer the plan uses, one past the highest byte it touches
-__global__ __launch_bounds__(kBlock) void k_final_readback(const uint32_t* n_batches, const ull* src_ext, uint32_t n_src,
-                                                           const ull* dst_ext, uint32_t n_dst, char* landing) {
-  if (threadIdx.x == 0) *reinterpret_cast<uint32_t*>(landing) = *n_batches;
+// (scan_total: the scanned batch flags' last entry, small tiles below, small-tile batches above)
+__global__ __launch_bounds__(kBlock) void k_final_readback(const uint64_t* scan_total, uint64_t n_tiles, const ull* src_ext,
+                                                           uint32_t n_src, const ull* dst_ext, uint32_t n_dst, char* landing) {
+  if (threadIdx.x == 0)
+    *reinterpret_cast<uint32_t*>(landing) = (uint32_t)(n_tiles - (uint32_t)*scan_total + (*scan_total >> 32));
   ull* out = reinterpret_cast<ull*>(landing + kLandingExtents);
   for (uint32_t i = threadIdx.x; i < n_src; i += kBlock) out[i] = src_ext[i];
   for (uint32_t i = threadIdx.x; i < n_dst; i += kBlock) out[n_src + i] = dst_ext[i];
@@ -1819,13 +1846,13 @@ bcp_status run_planner(const bcp_shard_meta* saved, int64_t n_saved, const bcp_s
       BCP_HIP(hipGetLastError());
       if (bcp_status s = device_scan<uint64_t, uint64_t>(bflags, bflags, (int64_t)n_tiles, ws, st)) return s;
       hipLaunchKernelGGL(k_batch_starts, dim3(nblk), dim3(kBlock), 0, st, bflags, n_tiles, bstart);
-      hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, regions, tile_region, tile_local, weight,
+      hipLaunchKernelGGL(k_fill_tiles, dim3(nblk), dim3(kBlock), 0, st, regions, tile_region, tile_local,
                          bflags, bstart, n_tiles, tiles, heads, key, out->dev.batch_key);
       BCP_HIP(hipGetLastError());
       // the extents of the buffers the plan uses come back with the batch count
       const size_t n_src = (size_t)(h.max_src_buf + 1), n_dst = (size_t)(h.max_dst_buf + 1);
       BCP_HIP(ensure_landing(ws, kLandingExtents + sizeof(ull) * (n_src + n_dst)));  // (nothing is in flight into it)
-      hipLaunchKernelGGL(k_final_readback, dim3(1), dim3(kBlock), 0, st, (const uint32_t*)(bflags + n_tiles), ext, (uint32_t)n_src,
+      hipLaunchKernelGGL(k_final_readback, dim3(1), dim3(kBlock), 0, st, bflags + n_tiles, n_tiles, ext, (uint32_t)n_src,
                          ext + ext_src_bufs, (uint32_t)n_dst, (char*)ws.landing_dev);
       BCP_HIP(hipGetLastError());
       out->src_extent.resize(n_src);

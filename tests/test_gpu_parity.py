@@ -407,6 +407,50 @@ def test_source_ordered_plan_runs_as_chunks_arrive(idx):
     p.destroy()
 
 
+@pytest.mark.parametrize("by_source", [False, True])
+def test_small_tensors_between_big_ones_share_batches(by_source):
+    """Tensors of 200 000 bytes alternating with tensors of 40 to 1200 bytes, on both sides in one buffer at odd
+    offsets.  In plan order the small tiles are batched among themselves across the big tiles between them
+    (fewer batches than one per small tensor); ordered by source every batch stays a run of consecutive tiles.
+    Bytes against the oracle both ways, and chunk by chunk for the ordered plan."""
+    rng = np.random.default_rng(11)
+    specs, sv, tg, so, to = {}, [], [], 3, 5
+    for f in range(120):
+        n = 200_000 if f % 2 == 0 else int(rng.integers(40, 1200))
+        specs[f] = TensorSpec(f, f"t{f}", (n,), torch.uint8, ("bits",))
+        part = Part(f, (n,), (0,), (n,))
+        sv.append(regular(part, 1, 0, so))
+        tg.append(regular(part, 1, 0, to))
+        so += n + int(rng.integers(0, 9))
+        to += n + int(rng.integers(0, 9))
+    case = Case("between", 12, specs, Layout(sv, [so]), Layout(tg, [to]))
+    src = synth.materialize(case.saved, specs, case.seed)
+    want = oracle.reshard(case.saved, case.target, src, poison=POISON)
+    p = binding.plan(binding.layout_to_meta(case.saved), binding.layout_to_meta(case.target),
+                     flags=binding.BCP_ORDER_BY_SOURCE if by_source else 0)
+    st = p.stats()
+    assert st["n_tiles"] >= 60 * 4 + 60
+    if not by_source:
+        assert st["n_batches"] < st["n_tiles"] - 50, st   # the 60 small tensors do not take a batch each
+    dsrc = [b.cuda() for b in src]
+    ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+    binding.reshard(p, dsrc, ddst)
+    torch.cuda.synchronize()
+    assert_same([t.cpu().numpy() for t in ddst], want, "small between big, one launch")
+    if by_source:
+        dsrc = [torch.full((b.numel(),), 0x3C, dtype=torch.uint8, device="cuda") for b in src]
+        ddst = [torch.full((n,), POISON, dtype=torch.uint8, device="cuda") for n in case.target.buf_bytes]
+        n, off = src[0].numel(), 0
+        while off < n:
+            end = min(n, off + int(rng.integers(1, 700_000)))
+            dsrc[0][off:end] = src[0][off:end].cuda()
+            binding.reshard_arrived(p, dsrc, ddst, 0, off, end)
+            off = end
+        torch.cuda.synchronize()
+        assert_same([t.cpu().numpy() for t in ddst], want, "small between big, chunked arrival")
+    p.destroy()
+
+
 def test_source_ordered_plan_with_a_spare_segment_at_the_end_of_a_blob():
     """A long run with a misaligned destination is cut where the DESTINATION offset is a multiple of 256, which
     reserves a possibly empty last segment per row; here that empty segment sits at the very end of a blob,
