@@ -107,6 +107,10 @@ def build_case(name: str):
         side = name.split("_")[1][0] if "_" in name else "s"
         return (synth.copy_case(8 << 30, shift if side in "sb" else 0, shift if side in "db" else 0),
                 "plain copy of one 8 GiB byte tensor through the reshard kernel (bandwidth ceiling)")
+    if name.startswith("regions_"):  # regions_<bytes>_<gap before each, source>_<the same, destination>_<jitter>
+        size, gs, gd, jit = (int(v) for v in name.split("_")[1:5])
+        return (synth.regions_case(size, gs, gd, jit),
+                f"6 GiB of byte tensors of {size} (+ up to {jit}) bytes packed with {gs} / {gd} bytes between them (source / destination)")
     raise SystemExit(f"unknown workload {name}")
 
 

@@ -665,6 +665,25 @@ def copy_case(nbytes: int = 8 << 30, src_shift: int = 0, dst_shift: int = 0) -> 
                 Layout([regular(part, 1, 0, dst_shift)], [nbytes + dst_shift]))
 
 
+def regions_case(size: int, src_gap: int = 0, dst_gap: int = 0, jitter: int = 0, total: int = 6 << 30) -> Case:
+    """About `total` bytes as byte tensors of `size` (+ up to `jitter`, drawn per tensor) bytes, packed into one
+    buffer on either side with `src_gap` / `dst_gap` bytes before each: a plain copy cut into regions, to
+    show what the region size (partial tiles at both ends of a region) and the alignment of the two sides cost."""
+    rng = np.random.default_rng(BASE_SEED + 12)
+    specs: Dict[int, TensorSpec] = {}
+    sv, tg, so, to, f = [], [], src_gap, dst_gap, 0
+    while so + size + jitter <= total:
+        n = size + (int(rng.integers(0, jitter)) if jitter else 0)
+        specs[f] = TensorSpec(f, f"r{f}", (n,), torch.uint8, ("bits",))
+        part = Part(f, (n,), (0,), (n,))
+        sv.append(regular(part, 1, 0, so))
+        tg.append(regular(part, 1, 0, to))
+        so += n + src_gap
+        to += n + dst_gap
+        f += 1
+    return Case(f"regions_{size}_{src_gap}_{dst_gap}_{jitter}", BASE_SEED + 12, specs, Layout(sv, [so]), Layout(tg, [to]))
+
+
 def llama_case(name: str, seed: int, layers: int, hidden: int, ffn: int, vocab: int, states,
                tp_s: int, pp_s: int, tp_t: int, pp_t: int, only_target_ranks=None) -> Case:
     model = llama_tensors(layers, hidden, ffn, vocab)
