@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188954478875,
-             "csrc_sha256": "979bc5e471293c14e4b411c4961d484abf34981de5b50aa4bf99a20b873724d8"},
-    "eval_load": {"bytes_per_launch": 40469079945,
-             "csrc_sha256": "979bc5e471293c14e4b411c4961d484abf34981de5b50aa4bf99a20b873724d8"},
-    "cfg5_small": {"bytes_per_launch": 1930152837,
-             "csrc_sha256": "979bc5e471293c14e4b411c4961d484abf34981de5b50aa4bf99a20b873724d8"},
+    "cfg3": {"bytes_per_launch": 188966501838,
+             "csrc_sha256": "1a75be408574609b6645dbc468a27c8fda1e0210b2b48e588afc72f1251903ea"},
+    "eval_load": {"bytes_per_launch": 40469535775,
+             "csrc_sha256": "1a75be408574609b6645dbc468a27c8fda1e0210b2b48e588afc72f1251903ea"},
+    "cfg5_small": {"bytes_per_launch": 1934688607,
+             "csrc_sha256": "1a75be408574609b6645dbc468a27c8fda1e0210b2b48e588afc72f1251903ea"},
 }
 
 

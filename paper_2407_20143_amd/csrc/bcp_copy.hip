@@ -6,10 +6,10 @@
 // actual addresses, one of
 //   * 16-byte vector path   -- bases, run length and pitches all 16-byte aligned;
 //   * misaligned-run path   -- long runs whose source and destination disagree modulo 16 (ZeRO
-//                              slice boundaries): from the destination's next 16-byte boundary on, aligned
+//                              slice boundaries): peel to a 16-byte aligned destination; then aligned
 //                              16-byte loads of the source chunks, each lane taking its right-hand
 //                              neighbour's chunk by a shuffle and funnel-shifting the pair into one
-//                              aligned 16-byte store; the run's first and last 16 bytes go as they lie;
+//                              aligned 16-byte store;
 //   * granule path          -- whole-workgroup tiles of short misaligned rows: 8/4/2/1-byte granules, flat
 //                              over rows x run;
 //   * small-tile batches    -- tiles below 16 KiB share a workgroup: per tile one item size (16 bytes, or the
@@ -212,9 +212,8 @@ __device__ __forceinline__ u32x4 funnel16(const u32x4& lo, const u32x4& hi, uint
   return o;
 }
 
-// one contiguous run whose two sides disagree modulo 16: aligned 16-byte stores from the destination's next
-// 16-byte boundary on; what lies before and after them goes as two unaligned 16-byte vectors.  What is stored
-// comes from ALIGNED 16-byte loads too
+// one contiguous run whose two sides disagree modulo 16: byte head up to the destination's next
+// 16-byte boundary, then aligned 16-byte stores, byte tail.  What is stored comes from ALIGNED 16-byte loads too
 // (a vector load at an address that is no multiple of 4 is taken apart by the hardware, and one at a multiple of 4
 // still touches two chunks): the wave loads 64 consecutive aligned source chunks, every lane gets its right-hand
 // neighbour's chunk by a shuffle (the last lane loads one chunk more) and shifts the 16 bytes it needs out of
@@ -224,20 +223,15 @@ __device__ __forceinline__ u32x4 funnel16(const u32x4& lo, const u32x4& hi, uint
 template <uint32_t U>
 __device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t run,
                                                     uint32_t tid, uint32_t nt) {
-  const uint32_t head = (uint32_t)(-(uintptr_t)d) & 15u;  // (run >= 64)
+  uint32_t head = (uint32_t)(-(uintptr_t)d) & 15u;
+  if (head > run) head = run;
+  for (uint32_t i = tid; i < head; i += nt) d[i] = s[i];
   const uint32_t body = (run - head) >> 4;
-  // The bytes before and after the aligned body: the run's first and last 16 bytes as they lie, one lane each,
-  // loaded before the body so that they do not cost a memory round trip of their own (they overlap the body by
-  // a few bytes, which are then written twice with the same values).
-  const uint32_t edge_off = tid == 0 ? 0u : run - 16u;
-  const bool edge = (tid == 0 && head != 0) || (tid == 1 && ((run - head) & 15u) != 0);
-  u32x4 edge_v = {0u, 0u, 0u, 0u};
-  if (edge) edge_v = ld<-16>(s + edge_off);
   gsrc_t s2 = s + head;
   gdst_t d2 = d + head;
   const uint32_t m = (uint32_t)(uintptr_t)s2 & 15u;
   if (m == 0) {  // (the two sides agree after all)
-    copy_rows<16>(s2, d2, 1u, body, 0, 0, tid, nt);
+    for (uint32_t i = tid; i < body; i += nt) st<16>(d2 + (size_t)i * 16, ld<16>(s2 + (size_t)i * 16));
   } else {
     gsrc_t sa = s2 - m;  // aligned; output chunk c is bytes m .. m + 15 of the source chunks c and c + 1
     const uint32_t q = m >> 2, r = m & 3u;
@@ -269,7 +263,8 @@ __device__ __forceinline__ void copy_run_misaligned(gsrc_t __restrict__ s, gdst_
       }
     }
   }
-  if (edge) st<-16>(d + edge_off, edge_v);
+  const uint32_t done = head + (body << 4);
+  for (uint32_t i = done + tid; i < run; i += nt) d[i] = s[i];
 }
 
 // ---- transposed tiles ----------------------------------------------------------------------------
@@ -498,53 +493,19 @@ __device__ __forceinline__ void transpose_any(gsrc_t __restrict__ s, gdst_t __re
   else transpose_tile<E>(s, d, na, nb, spb, dpa, tda, tdb, lds);
 }
 
-// rows of `run` >= 16 bytes where 16-byte alignment does not hold everywhere: unaligned 16-byte vectors over all
-// rows at once; a row's last vector is moved back so that it ends with the row (and copies up to 15 bytes a
-// second time), so that no bytes are left over for a pass of their own.
+// rows of `run` bytes where 16-byte alignment does not hold everywhere: unaligned 16-byte vectors
+// over all rows at once, then the (run mod 16) tail bytes of every row.
 __device__ __forceinline__ void copy_rows_unaligned(gsrc_t __restrict__ s, gdst_t __restrict__ d, uint32_t nrows,
                                                     uint32_t run, int64_t sp, int64_t dp, uint32_t tid, uint32_t nt) {
-  const uint32_t gpr = (run + 15u) >> 4, last = run - 16u, total = nrows * gpr;  // vectors per row
-  uint32_t row = tid / gpr, col = tid - row * gpr;
-  const uint32_t drow = nt / gpr, dcol = nt - drow * gpr;
-  auto advance = [&]() {
-    col += dcol;
-    row += drow;
-    if (col >= gpr) {
-      col -= gpr;
-      ++row;
+  const uint32_t body = run >> 4, tail = run & 15u;
+  if (body) copy_rows<-16>(s, d, nrows, body, sp, dp, tid, nt);
+  if (tail) {
+    const uint32_t total = nrows * tail;
+    const size_t off = (size_t)body << 4;
+    for (uint32_t i = tid; i < total; i += nt) {
+      const uint32_t r = i / tail, b = i - r * tail;
+      d[(int64_t)r * dp + off + b] = s[(int64_t)r * sp + off + b];
     }
-  };
-  uint32_t i = tid;
-  for (; i + 3 * nt < total; i += 4 * nt) {
-    u32x4 v[4];
-    int64_t so[4], dof[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint32_t off = min(col << 4, last);
-      so[u] = (int64_t)row * sp + off;
-      dof[u] = (int64_t)row * dp + off;
-      advance();
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) v[u] = ld<-16>(s + so[u]);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) st<-16>(d + dof[u], v[u]);
-  }
-  if (i < total) {  // up to three vectors of a lane are left: all in flight together, like a full round
-    u32x4 v[3];
-    int64_t dof[3];
-    bool have[3];
-#pragma unroll
-    for (int u = 0; u < 3; ++u) {
-      have[u] = i + u * nt < total;
-      const uint32_t off = min(col << 4, last);
-      dof[u] = (int64_t)row * dp + off;
-      if (have[u]) v[u] = ld<-16>(s + (int64_t)row * sp + off);
-      advance();
-    }
-#pragma unroll
-    for (int u = 0; u < 3; ++u)
-      if (have[u]) st<-16>(d + dof[u], v[u]);
   }
 }
 
