@@ -27,12 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E peak
 # counters read for a plain elementwise copy kernel of known size in the same run), per workload, with
 # the hash of the kernel sources they were taken on.  Reported as null as soon as the sources differ.
 MEASURED_TRAFFIC = {
-    "cfg3": {"bytes_per_launch": 188966501838,
-             "csrc_sha256": "1a75be408574609b6645dbc468a27c8fda1e0210b2b48e588afc72f1251903ea"},
-    "eval_load": {"bytes_per_launch": 40469535775,
-             "csrc_sha256": "1a75be408574609b6645dbc468a27c8fda1e0210b2b48e588afc72f1251903ea"},
-    "cfg5_small": {"bytes_per_launch": 1934688607,
-             "csrc_sha256": "1a75be408574609b6645dbc468a27c8fda1e0210b2b48e588afc72f1251903ea"},
+    "cfg3": {"bytes_per_launch": 188969525202,
+             "csrc_sha256": "6a676953f265eddf8e8b5184ea30e5899df7c83bbe3b806aa825c7a06df2d7ad"},
+    "eval_load": {"bytes_per_launch": 40469871576,
+             "csrc_sha256": "6a676953f265eddf8e8b5184ea30e5899df7c83bbe3b806aa825c7a06df2d7ad"},
+    "cfg5_small": {"bytes_per_launch": 1930523436,
+             "csrc_sha256": "6a676953f265eddf8e8b5184ea30e5899df7c83bbe3b806aa825c7a06df2d7ad"},
 }
 
 
