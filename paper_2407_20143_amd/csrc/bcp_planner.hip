@@ -621,6 +621,7 @@ __device__ inline bool boxes_intersect(const Box& a, const Box& b) {
 // saved boxes of one FQN must agree on the tensor and be pairwise disjoint (one saver per element,
 // Sec. 4.1 "Balancing saving workload"): every sorted position checks itself against the rest of
 // its FQN's run.
+constexpr int kCheckStep = 4;  // (eight gain nothing more)
 __global__ __launch_bounds__(kBlock) void k_saved_check(const Box* boxes, int64_t nbs, const uint64_t* skeys,
                                                         const uint32_t* sidx, const bcp_shard_meta* recs,
                                                         int check_overlap, Ctl* ctl) {
@@ -636,12 +637,40 @@ __global__ __launch_bounds__(kBlock) void k_saved_check(const Box* boxes, int64_
     }
   }
   if (!check_overlap) return;
-  for (int64_t j = i + 1; j < nbs && skeys[j] == skeys[i]; ++j) {
-    const Box& b = boxes[sidx[j]];
-    if (a.ndim == b.ndim && boxes_intersect(a, b)) {
-      report(ctl, a.rec > b.rec ? a.rec : b.rec, kErrOverlap);
-      return;
+  // kCheckStep positions of the run per step, their boxes' first dimensions loaded side by side (a step costs one
+  // memory round trip, and a run of a flat-sharded tensor has hundreds of boxes, nearly all of them apart
+  // in the first dimension already); the rest of a box is looked at only when that one overlaps.
+  const uint64_t key = skeys[i];
+  const int64_t a_lo = a.off[0], a_hi = a.off[0] + a.len[0];
+  for (int64_t j = i + 1; j < nbs; j += kCheckStep) {
+    bool in[kCheckStep];
+    uint32_t ix[kCheckStep];
+    int64_t lo[kCheckStep], ln[kCheckStep];
+    int nd[kCheckStep];
+#pragma unroll
+    for (int u = 0; u < kCheckStep; ++u) {
+      in[u] = j + u < nbs && skeys[j + u < nbs ? j + u : i] == key;
+      ix[u] = sidx[in[u] ? j + u : i];
     }
+#pragma unroll
+    for (int u = 0; u < kCheckStep; ++u) {
+      const Box& b = boxes[ix[u]];
+      lo[u] = b.off[0];
+      ln[u] = b.len[0];
+      nd[u] = b.ndim;
+    }
+#pragma unroll
+    for (int u = 0; u < kCheckStep; ++u) {
+      const int64_t l = a_lo > lo[u] ? a_lo : lo[u], hb = lo[u] + ln[u], h = a_hi < hb ? a_hi : hb;
+      if (in[u] && nd[u] == a.ndim && l < h) {
+        const Box& b = boxes[ix[u]];
+        if (boxes_intersect(a, b)) {
+          report(ctl, a.rec > b.rec ? a.rec : b.rec, kErrOverlap);
+          return;
+        }
+      }
+    }
+    if (!in[kCheckStep - 1]) break;  // the run ends inside this step
   }
 }
 
