@@ -147,7 +147,9 @@ def test_closed_form_model_shapes():
              synth.table3_vdit(8, 16, layers=2, hidden=24, text_dim=40),
              synth.table3_vdit(16, 8, layers=2, hidden=24, text_dim=40),
              synth.table3_tgpt_group(5, 10, layers=2, hidden=32, vocab=128),
-             synth.table3_tgpt_group(10, 5, layers=1, hidden=32, vocab=128, first_stage=False)]
+             synth.table3_tgpt_group(10, 5, layers=1, hidden=32, vocab=128, first_stage=False),
+             synth.regions_case(700, 4, 12, 90, total=40_000), synth.copy_case(5000, 3, 9),
+             synth.column_blocks_case(40, 96, 8, "write")]
     for case in cases:
         _, got = run(case)
         assert_bufs_equal(got, expect(case))
