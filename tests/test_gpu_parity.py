@@ -407,6 +407,14 @@ def test_source_ordered_plan_runs_as_chunks_arrive(idx):
     p.destroy()
 
 
+@pytest.mark.parametrize("size,gaps,jitter", [(70_000, (4, 12), 900), (200_000, (0, 4), 0), (131_072, (1, 0), 5000)])
+def test_packed_regions_at_shifting_offsets(size, gaps, jitter):
+    """Byte tensors of one to three tiles packed with a few bytes between them, so that the alignment of the two
+    sides changes from region to region: first tiles cut short to a 256-byte boundary of the destination, partial
+    last tiles, the shifted-load path at every shift."""
+    check_case(synth.regions_case(size, gaps[0], gaps[1], jitter, total=6_000_000))
+
+
 @pytest.mark.parametrize("by_source", [False, True])
 def test_small_tensors_between_big_ones_share_batches(by_source):
     """Tensors of 200 000 bytes alternating with tensors of 40 to 1200 bytes, on both sides in one buffer at odd
